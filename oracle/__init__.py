@@ -1,0 +1,197 @@
+"""fp64 CPU oracle for FastMKA route-fused attention (TEST INFRASTRUCTURE ONLY).
+
+Thin ctypes loader around ``oracle/mka_oracle.c``.  Nothing in the product
+package imports this module; it is used by the tests, by the smoke check and by
+the CPU-baseline leg of the benchmark.  It imports nothing from the HIP path.
+
+Every function takes array-likes (numpy arrays or CPU torch tensors of any
+float dtype, bf16 included), up-casts their exact values to fp64 and returns
+fp64 numpy arrays.  Shapes: Q [B,H,Tq,d]; K_l, V_l [B,H,S,d]; G [B,H,S,3];
+W_r [d,3]; b_r [3].
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mka_oracle.c")
+_LIB = os.path.join(_HERE, "libmka_oracle.so")
+
+_dp = ctypes.POINTER(ctypes.c_double)
+_ip = ctypes.POINTER(ctypes.c_int32)
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (fp contraction off so fma() is the only fused op)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared",
+               "-Wall", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.mka_oracle_num_threads.restype = ctypes.c_int
+        _lib.mka_oracle_decode.restype = ctypes.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().mka_oracle_num_threads())
+
+
+def f64(x) -> np.ndarray:
+    """Exact up-cast of an array-like (numpy / torch, any float dtype) to contiguous fp64."""
+    if x is None:
+        return None
+    if hasattr(x, "detach"):  # torch tensor, without importing torch here
+        x = x.detach().cpu().double().numpy()
+    return np.ascontiguousarray(np.asarray(x, dtype=np.float64))
+
+
+def _p(a):
+    return a.ctypes.data_as(_dp) if a is not None else None
+
+
+def _ilen(len3, S):
+    return np.ascontiguousarray(np.asarray(len3 if len3 is not None else (S, S, S), dtype=np.int32))
+
+
+def route(Q, W_r, b_r=None, S=None, G_prev=None):
+    """Router gates for the Tq new slots.  Returns (G [B,H,S,3], idx [B,H,Tq] int32)."""
+    Q, W_r, b_r = f64(Q), f64(W_r), f64(b_r)
+    B, H, Tq, d = Q.shape
+    S = Tq if S is None else S
+    G = np.zeros((B, H, S, 3)) if G_prev is None else f64(G_prev).copy()
+    assert G.shape == (B, H, S, 3) and W_r.shape == (d, 3)
+    idx = np.zeros((B, H, Tq), dtype=np.int32)
+    lib().mka_oracle_route(_p(Q), _p(W_r), _p(b_r), B, H, Tq, S, d, _p(G),
+                           idx.ctypes.data_as(_ip))
+    return G, idx
+
+
+def fuse(X, G, len3=None):
+    """Xf[j] = sum_l [j < len_l] G[j,l] X_l[j] for a triple of memories X = (X1, X2, X3)."""
+    X = [f64(x) for x in X]
+    G = f64(G)
+    ref = next(x for x in X if x is not None)
+    B, H, S, d = ref.shape
+    out = np.empty((B, H, S, d))
+    ln = _ilen(len3, S)
+    lib().mka_oracle_fuse(_p(X[0]), _p(X[1]), _p(X[2]), _p(G), ln.ctypes.data_as(_ip), B, H, S, d,
+                          _p(out))
+    return out
+
+
+def attn_fwd(Q, Kf, Vf, causal=True, tau=1.0, return_p=False):
+    """Plain softmax attention of Q over one K/V stream.  Returns (O, LSE[, P])."""
+    Q, Kf, Vf = f64(Q), f64(Kf), f64(Vf)
+    B, H, Tq, d = Q.shape
+    S = Kf.shape[2]
+    O = np.empty((B, H, Tq, d))
+    LSE = np.empty((B, H, Tq))
+    P = np.empty((B, H, Tq, S)) if return_p else None
+    lib().mka_oracle_attn_fwd(_p(Q), _p(Kf), _p(Vf), B, H, Tq, S, d, int(bool(causal)),
+                              ctypes.c_double(tau), _p(O), _p(LSE), _p(P))
+    return (O, LSE, P) if return_p else (O, LSE)
+
+
+def attn_fwd_blockwise(Q, Kf, Vf, Bc, causal=True, tau=1.0):
+    """Same result through the max-shift recursion over KV blocks of Bc slots."""
+    Q, Kf, Vf = f64(Q), f64(Kf), f64(Vf)
+    B, H, Tq, d = Q.shape
+    S = Kf.shape[2]
+    O = np.empty((B, H, Tq, d))
+    LSE = np.empty((B, H, Tq))
+    lib().mka_oracle_attn_fwd_blockwise(_p(Q), _p(Kf), _p(Vf), B, H, Tq, S, d, int(bool(causal)),
+                                        ctypes.c_double(tau), int(Bc), _p(O), _p(LSE))
+    return O, LSE
+
+
+def fwd(Q, K, V, G, len3=None, causal=True, tau=1.0):
+    """Route-fused attention forward on given gates.  K, V are triples.  Returns (O, LSE)."""
+    Q, G = f64(Q), f64(G)
+    K = [f64(x) for x in K]
+    V = [f64(x) for x in V]
+    B, H, Tq, d = Q.shape
+    S = G.shape[2]
+    ln = _ilen(len3, S)
+    O = np.empty((B, H, Tq, d))
+    LSE = np.empty((B, H, Tq))
+    lib().mka_oracle_fwd(_p(Q), _p(K[0]), _p(K[1]), _p(K[2]), _p(V[0]), _p(V[1]), _p(V[2]), _p(G),
+                         ln.ctypes.data_as(_ip), B, H, Tq, S, d, int(bool(causal)),
+                         ctypes.c_double(tau), _p(O), _p(LSE))
+    return O, LSE
+
+
+def fwd_routed(Q, K, V, W_r, b_r=None, G_prev=None, len3=None, causal=True, tau=1.0):
+    """Router on Q for the new slots, then the forward.  Returns (O, LSE, G, idx)."""
+    S = f64(K[0]).shape[2] if K[0] is not None else None
+    G, idx = route(Q, W_r, b_r, S=S, G_prev=G_prev)
+    O, LSE = fwd(Q, K, V, G, len3=len3, causal=causal, tau=tau)
+    return O, LSE, G, idx
+
+
+def decode(q, k_new, v_new, Kc, Vc, Gc, len3, W_r, b_r=None, tau=1.0):
+    """One decode step.  Kc, Vc: lists of fp64 numpy caches [B,H,cap_l,d] UPDATED IN PLACE,
+    Gc fp64 [B,H,capG,3] updated in place, len3 a length-3 int list updated in place.
+    k_new / v_new: triples with None for a level that gets no new entry.
+    Returns (O [B,H,1,d], LSE [B,H,1], idx [B,H])."""
+    q = f64(q)
+    B, H, _, d = q.shape
+    kn = [f64(x) for x in k_new]
+    vn = [f64(x) for x in v_new]
+    for a in list(Kc) + list(Vc) + [Gc]:
+        assert a.dtype == np.float64 and a.flags.c_contiguous
+    W_r, b_r = f64(W_r), f64(b_r)
+    cap = np.asarray([a.shape[2] for a in Kc], dtype=np.int32)
+    capG = int(Gc.shape[2])
+    ln = np.asarray(len3, dtype=np.int32)
+    arr3 = _dp * 3
+    O = np.empty((B, H, 1, d))
+    LSE = np.empty((B, H, 1))
+    idx = np.zeros((B, H), dtype=np.int32)
+    rc = lib().mka_oracle_decode(_p(q), arr3(*[_p(x) for x in kn]), arr3(*[_p(x) for x in vn]),
+                                 arr3(*[_p(x) for x in Kc]), arr3(*[_p(x) for x in Vc]), _p(Gc),
+                                 ln.ctypes.data_as(_ip), cap.ctypes.data_as(_ip), capG, _p(W_r),
+                                 _p(b_r), B, H, d, ctypes.c_double(tau), _p(O), _p(LSE),
+                                 idx.ctypes.data_as(_ip))
+    if rc != 0:
+        raise ValueError("inconsistent append or cache full")
+    for l in range(3):
+        len3[l] = int(ln[l])
+    return O, LSE, idx
+
+
+def bwd(dO, Q, K, V, G, W_r, len3=None, causal=True, tau=1.0, want_dG=False):
+    """Gradients of sum(dO*O).  Returns dict with dQ, dK (triple), dV (triple), dW_r, db_r[, dG]."""
+    dO, Q, G, W_r = f64(dO), f64(Q), f64(G), f64(W_r)
+    K = [f64(x) for x in K]
+    V = [f64(x) for x in V]
+    B, H, Tq, d = Q.shape
+    S = G.shape[2]
+    ln = _ilen(len3, S)
+    dQ = np.empty_like(Q)
+    dK = [np.empty((B, H, S, d)) for _ in range(3)]
+    dV = [np.empty((B, H, S, d)) for _ in range(3)]
+    dW = np.empty((d, 3))
+    db = np.empty(3)
+    dG = np.empty((B, H, S, 3)) if want_dG else None
+    lib().mka_oracle_bwd(_p(dO), _p(Q), _p(K[0]), _p(K[1]), _p(K[2]), _p(V[0]), _p(V[1]), _p(V[2]),
+                         _p(G), _p(W_r), ln.ctypes.data_as(_ip), B, H, Tq, S, d, int(bool(causal)),
+                         ctypes.c_double(tau), _p(dQ), _p(dK[0]), _p(dK[1]), _p(dK[2]), _p(dV[0]),
+                         _p(dV[1]), _p(dV[2]), _p(dW), _p(db), _p(dG))
+    out = {"dQ": dQ, "dK": dK, "dV": dV, "dW_r": dW, "db_r": db}
+    if want_dG:
+        out["dG"] = dG
+    return out
