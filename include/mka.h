@@ -1,0 +1,162 @@
+/*
+ * mka.h — C ABI of the MI355X (gfx950) FastMKA route-fused attention library.
+ *
+ * The operations are those of the paper's Algorithm 2 ("FastMKA: Route-Fused
+ * MKA"), restricted to head-level tensors:
+ *   step 5   routing gates        lam = softmax_3(Q W_r + b_r), one triple per token
+ *   step 6-7 route-fusion         Kf[j] = sum_l lam_l[j] K_l[j],  Vf[j] likewise
+ *   step 8   cache update         append the new token's entries
+ *   step 9   single attention     O = softmax(tau Q Kf^T, causal) Vf     (Eq. 1, tau of Eq. 3)
+ * evaluated block-wise with the max-shift online softmax of the section
+ * "Numerical Stability via Max-Shift".  The gate of slot j is the gate of the
+ * token that produced slot j (token-aligned product of step 6), so the three
+ * memories are slot-aligned: K_l, V_l all have S slots, the last Tq of which
+ * belong to the Tq query rows of the call.
+ *
+ * Conventions, all entry points:
+ *  - every tensor pointer is a DEVICE pointer owned by the caller, dense
+ *    row-major, 16-byte aligned:  Q,O,dO,dQ [B,H,Tq,d];  K_l,V_l,dK_l,dV_l
+ *    [B,H,S,d];  G [B,H,S,3] f32;  LSE [B,H,Tq] f32;  idx [B,H,Tq] int32;
+ *    W_r [d,3] f32;  b_r [3] f32.  `dtype` is the element type of Q,K,V,O,dO
+ *    and of the K/V/Q gradients; gates, LSE and router weights are always f32.
+ *  - `stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work
+ *    and return; they never synchronise, allocate, throw or abort.
+ *  - scratch memory comes from the caller: `workspace` of at least
+ *    mka_workspace_bytes(op, shape) bytes (device memory, 256-byte aligned).
+ *  - every argument error is found on the host BEFORE anything is launched and
+ *    reported as a status; nothing is written in that case.
+ *  - supported: d in {64,128}; dtype MKA_BF16 (MFMA path) for every entry
+ *    point, MKA_F32 (accuracy path) for route, forward and decode.
+ *  - a level l with len[l] < S has no entry at slots j >= len[l]; it then
+ *    contributes the zero vector there (Alg. 1's "M_3 <- 0") and the gates are
+ *    not renormalised.  A NULL K[l]/V[l] pair means len[l] = 0.
+ *  - causal masks are bottom-right aligned: row t sees slots j <= t + (S - Tq).
+ */
+#ifndef MKA_H_
+#define MKA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MKA_OK = 0,
+  MKA_ERR_NULL = 1,        /* a required pointer is NULL                           */
+  MKA_ERR_SHAPE = 2,       /* non-positive size, S < Tq with causal, len[l] > S ... */
+  MKA_ERR_DTYPE = 3,       /* unknown dtype                                        */
+  MKA_ERR_ALIGN = 4,       /* a tensor pointer is not 16-byte aligned              */
+  MKA_ERR_WORKSPACE = 5,   /* workspace missing or too small                       */
+  MKA_ERR_UNSUPPORTED = 6, /* valid request this build has no kernel for           */
+  MKA_ERR_LAUNCH = 7       /* the HIP runtime refused a launch                     */
+} mka_status;
+
+typedef enum { MKA_F32 = 0, MKA_BF16 = 1 } mka_dtype;
+
+typedef enum { MKA_OP_ROUTE = 0, MKA_OP_FWD = 1, MKA_OP_DECODE = 2, MKA_OP_BWD = 3 } mka_op;
+
+/* Problem shape of route / forward / backward. */
+typedef struct {
+  int32_t B, H;   /* batch, heads (K/V have the same H as Q)                         */
+  int32_t Tq;     /* query rows of this call                                          */
+  int32_t S;      /* visible slots, including the Tq new ones (S >= Tq)               */
+  int32_t d;      /* head dimension                                                   */
+  int32_t len[3]; /* valid slots of each level, 0 <= len[l] <= S                      */
+  int32_t dtype;  /* mka_dtype                                                        */
+  int32_t causal; /* 0: every row sees all S slots; 1: bottom-right aligned causal    */
+  float scale;    /* tau                                                              */
+} mka_shape;
+
+/* Problem shape of one decode step. */
+typedef struct {
+  int32_t B, H, d;
+  int32_t cap[3];   /* allocated slots per (b,h) of each level's K and V cache        */
+  int32_t capG;     /* allocated rows per (b,h) of the gate cache                     */
+  int32_t dtype;    /* mka_dtype of q, k_new, v_new, caches, O                        */
+  int32_t n_splits; /* split-K factor along the slots; 0 = let the library choose     */
+  float scale;      /* tau                                                            */
+} mka_decode_shape;
+
+/* Bytes of device scratch the given operation needs (0 if none, and 0 for an
+ * invalid shape: the entry point itself reports what is wrong).  For
+ * MKA_OP_DECODE pass a mka_shape with B,H,d,dtype filled and S = the largest
+ * slot count the cache will reach; the answer covers any n_splits choice. */
+size_t mka_workspace_bytes(mka_op op, const mka_shape* shape);
+
+/* Alg. 2 step 5.  Logits g[t,l] = b_r[l] + sum_k Q[t,k] W_r[k,l] are an fp64 fma
+ * chain in ascending k (so the argmax is reproducible bit for bit); gates are
+ * the 3-way softmax of the logits.
+ *   Q      in   [B,H,Tq,d] dtype
+ *   W_r    in   [d,3] f32;  b_r in [3] f32, NULL = zeros
+ *   G_out  out  [B,H,S,3] f32: rows S-Tq .. S-1 are written, others untouched; NULL = skip
+ *   idx_out out [B,H,Tq] int32: argmax_l g[t,l], ties to the lowest l; NULL = skip
+ * Only B,H,Tq,S,d,dtype of the shape are read. */
+mka_status mka_route(const void* Q, const float* W_r, const float* b_r, float* G_out,
+                     int32_t* idx_out, const mka_shape* shape, void* stream);
+
+/* Alg. 2 steps 5-7 and 9 for Tq query rows (prefill, or a training forward).
+ *   Q     in     [B,H,Tq,d]
+ *   K,V   in     three [B,H,S,d] each (entry NULL = level absent)
+ *   W_r   in     router weights; NULL = take every row of G as given
+ *   b_r   in     router bias, NULL = zeros
+ *   G     in/out [B,H,S,3] f32, required.  With W_r: rows S-Tq..S-1 are computed
+ *                from Q and written (rows below are the caller's, from earlier
+ *                calls); without W_r: read only.
+ *   O     out    [B,H,Tq,d] dtype
+ *   LSE   out    [B,H,Tq] f32, log-sum-exp of the scaled visible scores; NULL = skip
+ *   idx_out out  [B,H,Tq] int32 gate argmax (needs W_r); NULL = skip
+ * The router and the fusion are folded into the attention launch sequence; Kf
+ * and Vf are never written to memory. */
+mka_status mka_fused_attn_fwd(const void* Q, const void* const K[3], const void* const V[3],
+                              const float* W_r, const float* b_r, float* G, void* O, float* LSE,
+                              int32_t* idx_out, const mka_shape* shape, void* workspace,
+                              size_t workspace_bytes, void* stream);
+
+/* One decode step (Alg. 2 steps 5-9 with one query row per (b,h)):
+ * the new token's slot is j_new = max_l len[l]; for every level with k_new[l] and
+ * v_new[l] given, the entries are written to slot j_new of that level's cache
+ * (requires len[l] == j_new < cap[l]) and len[l] becomes j_new+1; the new slot's
+ * gate is the router on q and is written to Gc; then q attends over slots
+ * 0..j_new of the fused stream (it sees itself), split along the slots.
+ *   q        in      [B,H,1,d]
+ *   k_new,v_new in   three [B,H,1,d] each, entry NULL = level gets no entry
+ *   Kc,Vc    in/out  three caches [B,H,cap[l],d] each (NULL allowed if len[l]==0 and no k_new[l])
+ *   Gc       in/out  [B,H,capG,3] f32 gate cache
+ *   len      in/out  HOST array of 3: valid slots per level before / after the call
+ *   W_r,b_r  in      router (W_r required)
+ *   O        out     [B,H,1,d];  LSE out [B,H] f32 or NULL;  idx_out out [B,H] int32 or NULL
+ * At least one level must be appended. */
+mka_status mka_fused_attn_decode(const void* q, const void* const k_new[3],
+                                 const void* const v_new[3], void* const Kc[3], void* const Vc[3],
+                                 float* Gc, int32_t len[3], const float* W_r, const float* b_r,
+                                 void* O, float* LSE, int32_t* idx_out,
+                                 const mka_decode_shape* shape, void* workspace,
+                                 size_t workspace_bytes, void* stream);
+
+/* Backward of mka_fused_attn_fwd (chain rule through Alg. 2 steps 5-9) for the
+ * loss sum(dO * O): gradients w.r.t. Q, every K_l, V_l, and the router.
+ *   dO,Q,O in  [B,H,Tq,d];  K,V in three [B,H,S,d];  G in [B,H,S,3];  LSE in [B,H,Tq]
+ *   W_r    in  [d,3] or NULL (gates were given: no router gradient, dW_r/db_r untouched)
+ *   dQ     out [B,H,Tq,d] dtype (includes the path through the gates of the new slots)
+ *   dK,dV  out three [B,H,S,d] dtype each (entry NULL = skip; zero where the level is absent)
+ *   dW_r   out [d,3] f32, db_r out [3] f32 (set, not accumulated; NULL = skip)
+ * dQ accumulates across KV tiles with f32 atomics (run-to-run differences in
+ * the last bits); dW_r/db_r use a fixed-order two-stage reduction. */
+mka_status mka_fused_attn_bwd(const void* dO, const void* Q, const void* const K[3],
+                              const void* const V[3], const float* G, const void* O,
+                              const float* LSE, const float* W_r, void* dQ, void* const dK[3],
+                              void* const dV[3], float* dW_r, float* db_r, const mka_shape* shape,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/* Static, human-readable name of a status. */
+const char* mka_status_string(mka_status status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int32_t mka_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MKA_H_ */

@@ -1,0 +1,236 @@
+"""ctypes binding of the C ABI in include/mka.h (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, c_float, c_int32, c_size_t, c_void_p
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmka.so")
+
+MKA_F32, MKA_BF16 = 0, 1
+MKA_OP_ROUTE, MKA_OP_FWD, MKA_OP_DECODE, MKA_OP_BWD = 0, 1, 2, 3
+
+
+class MkaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        super().__init__(f"{where}: {status_string(status)}")
+
+
+class MkaShape(ctypes.Structure):
+    _fields_ = [("B", c_int32), ("H", c_int32), ("Tq", c_int32), ("S", c_int32), ("d", c_int32),
+                ("len", c_int32 * 3), ("dtype", c_int32), ("causal", c_int32), ("scale", c_float)]
+
+
+class MkaDecodeShape(ctypes.Structure):
+    _fields_ = [("B", c_int32), ("H", c_int32), ("d", c_int32), ("cap", c_int32 * 3),
+                ("capG", c_int32), ("dtype", c_int32), ("n_splits", c_int32), ("scale", c_float)]
+
+
+_P3 = c_void_p * 3
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded shared library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2603_20586_amd.build` "
+                "(or __graft_entry__.build()); there is no CPU fallback")
+        L = ctypes.CDLL(_LIB_PATH)
+        L.mka_version.restype = c_int32
+        L.mka_status_string.restype = ctypes.c_char_p
+        L.mka_status_string.argtypes = [ctypes.c_int]
+        L.mka_workspace_bytes.restype = c_size_t
+        L.mka_workspace_bytes.argtypes = [ctypes.c_int, POINTER(MkaShape)]
+        L.mka_route.restype = ctypes.c_int
+        L.mka_route.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                POINTER(MkaShape), c_void_p]
+        L.mka_fused_attn_fwd.restype = ctypes.c_int
+        L.mka_fused_attn_fwd.argtypes = [c_void_p, POINTER(_P3), POINTER(_P3), c_void_p, c_void_p,
+                                         c_void_p, c_void_p, c_void_p, c_void_p,
+                                         POINTER(MkaShape), c_void_p, c_size_t, c_void_p]
+        L.mka_fused_attn_decode.restype = ctypes.c_int
+        L.mka_fused_attn_decode.argtypes = [c_void_p, POINTER(_P3), POINTER(_P3), POINTER(_P3),
+                                            POINTER(_P3), c_void_p, POINTER(c_int32 * 3),
+                                            c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                            POINTER(MkaDecodeShape), c_void_p, c_size_t, c_void_p]
+        L.mka_fused_attn_bwd.restype = ctypes.c_int
+        L.mka_fused_attn_bwd.argtypes = [c_void_p, c_void_p, POINTER(_P3), POINTER(_P3), c_void_p,
+                                         c_void_p, c_void_p, c_void_p, c_void_p, POINTER(_P3),
+                                         POINTER(_P3), c_void_p, c_void_p, POINTER(MkaShape),
+                                         c_void_p, c_size_t, c_void_p]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().mka_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise MkaError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else c_void_p(t.data_ptr())
+
+
+def _p3(ts):
+    return _P3(*[(t.data_ptr() if t is not None else None) for t in ts])
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return MKA_BF16
+    if t.dtype == torch.float32:
+        return MKA_F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _stream() -> c_void_p:
+    return c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev_check(*ts):
+    for t in ts:
+        if t is not None:
+            if not t.is_cuda:
+                raise ValueError("tensors must live in device memory")
+            if not t.is_contiguous():
+                raise ValueError("tensors must be contiguous")
+
+
+def _shape(Q, S, len3, causal, scale) -> MkaShape:
+    B, H, Tq, d = Q.shape
+    s = MkaShape()
+    s.B, s.H, s.Tq, s.S, s.d = B, H, Tq, S, d
+    ln = len3 if len3 is not None else (S, S, S)
+    for l in range(3):
+        s.len[l] = int(ln[l])
+    s.dtype = _dtype_code(Q)
+    s.causal = int(bool(causal))
+    s.scale = float(scale)
+    return s
+
+
+def mka_workspace_bytes(op: int, shape: MkaShape) -> int:
+    return int(lib().mka_workspace_bytes(op, ctypes.byref(shape)))
+
+
+def _workspace(nbytes: int, device):
+    # torch's caching allocator returns 512-byte aligned blocks
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def mka_route(Q, W_r, b_r=None, S=None, G=None, want_idx=True):
+    """Router gates (Alg. 2 step 5).  Returns (G [B,H,S,3] f32, idx [B,H,Tq] int32 or None).
+    `G` may be an existing gate tensor whose rows S-Tq.. are overwritten."""
+    _dev_check(Q, W_r, b_r, G)
+    B, H, Tq, d = Q.shape
+    S = Tq if S is None else S
+    if G is None:
+        G = torch.zeros((B, H, S, 3), dtype=torch.float32, device=Q.device)
+    idx = torch.empty((B, H, Tq), dtype=torch.int32, device=Q.device) if want_idx else None
+    s = _shape(Q, S, None, False, 1.0)
+    _check(lib().mka_route(_ptr(Q), _ptr(W_r), _ptr(b_r), _ptr(G), _ptr(idx), ctypes.byref(s),
+                           _stream()), "mka_route")
+    return G, idx
+
+
+def mka_fused_attn_fwd(Q, K, V, W_r=None, b_r=None, G=None, len3=None, causal=True, scale=1.0,
+                       want_lse=True, want_idx=True, O=None, LSE=None, idx=None):
+    """Route-fused attention forward.  K, V: sequences of three tensors (None = level absent).
+    With W_r the router runs on Q and fills G's last Tq rows.  Returns (O, LSE, G, idx)."""
+    _dev_check(Q, W_r, b_r, G, *K, *V)
+    B, H, Tq, d = Q.shape
+    ref = next(k for k in K if k is not None)
+    S = ref.shape[2]
+    if G is None:
+        if W_r is None:
+            raise ValueError("either W_r or G is required")
+        G = torch.zeros((B, H, S, 3), dtype=torch.float32, device=Q.device)
+    if O is None:
+        O = torch.empty_like(Q)
+    if LSE is None and want_lse:
+        LSE = torch.empty((B, H, Tq), dtype=torch.float32, device=Q.device)
+    if idx is None and want_idx and W_r is not None:
+        idx = torch.empty((B, H, Tq), dtype=torch.int32, device=Q.device)
+    s = _shape(Q, S, len3, causal, scale)
+    k3, v3 = _p3(K), _p3(V)
+    _check(lib().mka_fused_attn_fwd(_ptr(Q), ctypes.byref(k3), ctypes.byref(v3), _ptr(W_r),
+                                    _ptr(b_r), _ptr(G), _ptr(O), _ptr(LSE), _ptr(idx),
+                                    ctypes.byref(s), None, 0, _stream()), "mka_fused_attn_fwd")
+    return O, LSE, G, idx
+
+
+def mka_fused_attn_decode(q, k_new, v_new, Kc, Vc, Gc, len3, W_r, b_r=None, scale=1.0,
+                          n_splits=0, workspace=None, O=None, LSE=None, idx=None, want_lse=True,
+                          want_idx=True):
+    """One decode step; caches and `len3` (a python list of 3 ints) are updated in place.
+    Returns (O [B,H,1,d], LSE [B,H] or None, idx [B,H] or None)."""
+    _dev_check(q, W_r, b_r, Gc, *k_new, *v_new, *Kc, *Vc)
+    B, H, _, d = q.shape
+    s = MkaDecodeShape()
+    s.B, s.H, s.d = B, H, d
+    for l in range(3):
+        s.cap[l] = int(Kc[l].shape[2]) if Kc[l] is not None else 0
+    s.capG = int(Gc.shape[2])
+    s.dtype = _dtype_code(q)
+    s.n_splits = int(n_splits)
+    s.scale = float(scale)
+    if workspace is None:
+        qs = MkaShape()
+        qs.B, qs.H, qs.d, qs.S, qs.Tq, qs.dtype = B, H, d, s.capG, 1, s.dtype
+        workspace = _workspace(mka_workspace_bytes(MKA_OP_DECODE, qs), q.device)
+    if O is None:
+        O = torch.empty_like(q)
+    if LSE is None and want_lse:
+        LSE = torch.empty((B, H), dtype=torch.float32, device=q.device)
+    if idx is None and want_idx:
+        idx = torch.empty((B, H), dtype=torch.int32, device=q.device)
+    ln = (c_int32 * 3)(*[int(x) for x in len3])
+    kn, vn, kc, vc = _p3(k_new), _p3(v_new), _p3(Kc), _p3(Vc)
+    _check(lib().mka_fused_attn_decode(_ptr(q), ctypes.byref(kn), ctypes.byref(vn),
+                                       ctypes.byref(kc), ctypes.byref(vc), _ptr(Gc),
+                                       ctypes.byref(ln), _ptr(W_r), _ptr(b_r), _ptr(O), _ptr(LSE),
+                                       _ptr(idx), ctypes.byref(s), _ptr(workspace),
+                                       workspace.numel(), _stream()), "mka_fused_attn_decode")
+    for l in range(3):
+        len3[l] = int(ln[l])
+    return O, LSE, idx
+
+
+def mka_fused_attn_bwd(dO, Q, K, V, G, O, LSE, W_r=None, len3=None, causal=True, scale=1.0,
+                       workspace=None, grads_for=(True, True, True)):
+    """Backward of the forward.  Returns dict(dQ, dK[3], dV[3], dW_r, db_r)."""
+    _dev_check(dO, Q, G, O, LSE, W_r, *K, *V)
+    B, H, Tq, d = Q.shape
+    S = G.shape[2]
+    s = _shape(Q, S, len3, causal, scale)
+    if workspace is None:
+        workspace = _workspace(mka_workspace_bytes(MKA_OP_BWD, s), Q.device)
+    dQ = torch.empty_like(Q)
+    dK = [torch.empty_like(K[l]) if (K[l] is not None and grads_for[l]) else None
+          for l in range(3)]
+    dV = [torch.empty_like(V[l]) if (V[l] is not None and grads_for[l]) else None
+          for l in range(3)]
+    dW = torch.empty((d, 3), dtype=torch.float32, device=Q.device) if W_r is not None else None
+    db = torch.empty((3,), dtype=torch.float32, device=Q.device) if W_r is not None else None
+    k3, v3, dk3, dv3 = _p3(K), _p3(V), _p3(dK), _p3(dV)
+    _check(lib().mka_fused_attn_bwd(_ptr(dO), _ptr(Q), ctypes.byref(k3), ctypes.byref(v3),
+                                    _ptr(G), _ptr(O), _ptr(LSE), _ptr(W_r), _ptr(dQ),
+                                    ctypes.byref(dk3), ctypes.byref(dv3), _ptr(dW), _ptr(db),
+                                    ctypes.byref(s), _ptr(workspace), workspace.numel(),
+                                    _stream()), "mka_fused_attn_bwd")
+    return dict(dQ=dQ, dK=dK, dV=dV, dW_r=dW, db_r=db)

@@ -1,0 +1,228 @@
+// C-ABI layer: argument validation on the host, workspace carve-up, kernel launches.
+// Every error is found before anything is enqueued; see include/mka.h for the contract.
+#include <math.h>
+#include <string.h>
+
+#include "../../include/mka.h"
+#include "mka_internal.h"
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Checks shared by route / forward / backward.  `empty` is set for a valid problem with no
+// query rows, which the caller answers with MKA_OK without launching.
+mka_status check_shape(const mka_shape* s, bool* empty) {
+  if (!s) return MKA_ERR_NULL;
+  if (s->dtype != MKA_F32 && s->dtype != MKA_BF16) return MKA_ERR_DTYPE;
+  if (s->B < 0 || s->H < 0 || s->Tq < 0 || s->S < 0 || s->d <= 0) return MKA_ERR_SHAPE;
+  if (s->S < s->Tq) return MKA_ERR_SHAPE;
+  for (int l = 0; l < 3; ++l)
+    if (s->len[l] < 0 || s->len[l] > s->S) return MKA_ERR_SHAPE;
+  if (s->d != 64 && s->d != 128) return MKA_ERR_UNSUPPORTED;
+  if (!(s->scale >= 0.f) || isinf(s->scale)) return MKA_ERR_UNSUPPORTED;
+  const long long bh = (long long)s->B * s->H;
+  if (bh > 0x7fffffffLL / 4096) return MKA_ERR_UNSUPPORTED;  // grid index must fit
+  if (bh * (long long)((s->Tq + 31) / 32) > 0x7fffffffLL) return MKA_ERR_UNSUPPORTED;
+  *empty = (bh == 0 || s->Tq == 0);
+  return MKA_OK;
+}
+
+size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+}  // namespace
+
+extern "C" {
+
+int32_t mka_version(void) { return 100; }
+
+const char* mka_status_string(mka_status st) {
+  switch (st) {
+    case MKA_OK: return "MKA_OK";
+    case MKA_ERR_NULL: return "MKA_ERR_NULL: a required pointer is NULL";
+    case MKA_ERR_SHAPE: return "MKA_ERR_SHAPE: inconsistent sizes";
+    case MKA_ERR_DTYPE: return "MKA_ERR_DTYPE: unknown dtype";
+    case MKA_ERR_ALIGN: return "MKA_ERR_ALIGN: pointer not 16-byte aligned";
+    case MKA_ERR_WORKSPACE: return "MKA_ERR_WORKSPACE: workspace missing or too small";
+    case MKA_ERR_UNSUPPORTED: return "MKA_ERR_UNSUPPORTED: no kernel for this request";
+    case MKA_ERR_LAUNCH: return "MKA_ERR_LAUNCH: the HIP runtime refused a launch";
+  }
+  return "MKA_ERR_?: unknown status";
+}
+
+size_t mka_workspace_bytes(mka_op op, const mka_shape* s) {
+  if (!s || s->B <= 0 || s->H <= 0 || s->d <= 0) return 0;
+  const size_t bh = (size_t)s->B * s->H;
+  switch (op) {
+    case MKA_OP_ROUTE:
+    case MKA_OP_FWD:
+      return 0;
+    case MKA_OP_DECODE:
+      return align256(bh * mka::kMaxSplits * (size_t)(s->d + 2) * sizeof(float));
+    case MKA_OP_BWD:
+      if (s->Tq <= 0 || s->S < s->Tq) return 0;
+      return mka::bwd_workspace_bytes((int)bh, s->Tq, s->S, s->d);
+  }
+  return 0;
+}
+
+mka_status mka_route(const void* Q, const float* W_r, const float* b_r, float* G_out,
+                     int32_t* idx_out, const mka_shape* shape, void* stream) {
+  bool empty = false;
+  mka_shape tmp;
+  if (!shape) return MKA_ERR_NULL;
+  tmp = *shape;  // route reads only B,H,Tq,S,d,dtype
+  tmp.len[0] = tmp.len[1] = tmp.len[2] = 0;
+  tmp.scale = 1.f;
+  const mka_status st = check_shape(&tmp, &empty);
+  if (st != MKA_OK) return st;
+  if (!Q || !W_r) return MKA_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(G_out) || (reinterpret_cast<uintptr_t>(W_r) & 3u) ||
+      (reinterpret_cast<uintptr_t>(idx_out) & 3u))
+    return MKA_ERR_ALIGN;
+  if (empty || (!G_out && !idx_out)) return MKA_OK;
+  mka::RouteArgs a;
+  a.Q = Q; a.W_r = W_r; a.b_r = b_r; a.G = G_out; a.idx = idx_out;
+  a.BH = shape->B * shape->H; a.Tq = shape->Tq; a.S = shape->S; a.d = shape->d;
+  a.bf16 = shape->dtype == MKA_BF16;
+  return mka::launch_route(a, (hipStream_t)stream) == hipSuccess ? MKA_OK : MKA_ERR_LAUNCH;
+}
+
+mka_status mka_fused_attn_fwd(const void* Q, const void* const K[3], const void* const V[3],
+                              const float* W_r, const float* b_r, float* G, void* O, float* LSE,
+                              int32_t* idx_out, const mka_shape* shape, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  bool empty = false;
+  const mka_status st = check_shape(shape, &empty);
+  if (st != MKA_OK) return st;
+  if (!Q || !K || !V || !G || !O) return MKA_ERR_NULL;
+  if (idx_out && !W_r) return MKA_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(G) || !aligned16(O) || !aligned16(LSE)) return MKA_ERR_ALIGN;
+  mka::FwdArgs a;
+  for (int l = 0; l < 3; ++l) {
+    if (!aligned16(K[l]) || !aligned16(V[l])) return MKA_ERR_ALIGN;
+    const bool present = K[l] && V[l];
+    a.K[l] = present ? K[l] : nullptr;
+    a.V[l] = present ? V[l] : nullptr;
+    a.len[l] = present ? shape->len[l] : 0;
+  }
+  if (empty) return MKA_OK;
+  hipStream_t hs = (hipStream_t)stream;
+  const int BH = shape->B * shape->H;
+  const bool is_bf16 = shape->dtype == MKA_BF16;
+  if (W_r) {
+    mka::RouteArgs r;
+    r.Q = Q; r.W_r = W_r; r.b_r = b_r; r.G = G; r.idx = idx_out;
+    r.BH = BH; r.Tq = shape->Tq; r.S = shape->S; r.d = shape->d; r.bf16 = is_bf16;
+    if (mka::launch_route(r, hs) != hipSuccess) return MKA_ERR_LAUNCH;
+  }
+  a.Q = Q; a.G = G; a.O = O; a.LSE = LSE;
+  a.BH = BH; a.Tq = shape->Tq; a.S = shape->S; a.d = shape->d;
+  a.causal = shape->causal ? 1 : 0;
+  a.scale = shape->scale;
+  const hipError_t e = is_bf16 ? mka::launch_fwd_bf16(a, hs) : mka::launch_fwd_f32(a, hs);
+  return e == hipSuccess ? MKA_OK : MKA_ERR_LAUNCH;
+}
+
+mka_status mka_fused_attn_decode(const void* q, const void* const k_new[3],
+                                 const void* const v_new[3], void* const Kc[3], void* const Vc[3],
+                                 float* Gc, int32_t len[3], const float* W_r, const float* b_r,
+                                 void* O, float* LSE, int32_t* idx_out,
+                                 const mka_decode_shape* s, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
+  if (!s) return MKA_ERR_NULL;
+  if (s->dtype != MKA_F32 && s->dtype != MKA_BF16) return MKA_ERR_DTYPE;
+  if (s->B < 0 || s->H < 0 || s->d <= 0 || s->capG <= 0 || s->n_splits < 0) return MKA_ERR_SHAPE;
+  if (s->d != 64 && s->d != 128) return MKA_ERR_UNSUPPORTED;
+  if (!(s->scale >= 0.f) || isinf(s->scale)) return MKA_ERR_UNSUPPORTED;
+  if (s->n_splits > mka::kMaxSplits) return MKA_ERR_UNSUPPORTED;
+  if (!q || !k_new || !v_new || !Kc || !Vc || !Gc || !len || !W_r || !O) return MKA_ERR_NULL;
+  const long long bh = (long long)s->B * s->H;
+  if (bh > 65535) return MKA_ERR_UNSUPPORTED;  // grid.y
+  int j_new = 0;
+  for (int l = 0; l < 3; ++l) {
+    if (s->cap[l] < 0 || len[l] < 0 || len[l] > s->cap[l]) return MKA_ERR_SHAPE;
+    if (len[l] > j_new) j_new = len[l];
+  }
+  if (j_new >= s->capG) return MKA_ERR_SHAPE;
+  mka::DecodeArgs a;
+  bool any = false;
+  for (int l = 0; l < 3; ++l) {
+    const bool app = k_new[l] && v_new[l];
+    if ((k_new[l] != nullptr) != (v_new[l] != nullptr)) return MKA_ERR_NULL;
+    if (app) {
+      if (len[l] != j_new || j_new >= s->cap[l]) return MKA_ERR_SHAPE;
+      if (!Kc[l] || !Vc[l]) return MKA_ERR_NULL;
+      any = true;
+    }
+    if (len[l] > 0 && (!Kc[l] || !Vc[l])) return MKA_ERR_NULL;
+    if (!aligned16(k_new[l]) || !aligned16(v_new[l]) || !aligned16(Kc[l]) || !aligned16(Vc[l]))
+      return MKA_ERR_ALIGN;
+    a.k_new[l] = app ? k_new[l] : nullptr;
+    a.v_new[l] = app ? v_new[l] : nullptr;
+    a.Kc[l] = Kc[l];
+    a.Vc[l] = Vc[l];
+    a.cap[l] = s->cap[l];
+    a.len[l] = app ? j_new + 1 : len[l];
+  }
+  if (!any) return MKA_ERR_SHAPE;
+  if (!aligned16(q) || !aligned16(O) || (reinterpret_cast<uintptr_t>(Gc) & 3u)) return MKA_ERR_ALIGN;
+  if (bh == 0) return MKA_OK;
+  a.S = j_new + 1;
+  a.n_splits = s->n_splits > 0 ? s->n_splits : mka::decode_auto_splits((int)bh, a.S);
+  const size_t need = (size_t)bh * a.n_splits * (size_t)(s->d + 2) * sizeof(float);
+  if (!workspace || workspace_bytes < need) return MKA_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MKA_ERR_ALIGN;
+  a.q = q; a.Gc = Gc; a.W_r = W_r; a.b_r = b_r; a.O = O; a.LSE = LSE; a.idx = idx_out;
+  a.BH = (int)bh; a.d = s->d; a.capG = s->capG; a.j_new = j_new;
+  a.scale = s->scale; a.bf16 = s->dtype == MKA_BF16;
+  a.partial = static_cast<float*>(workspace);
+  if (mka::launch_decode(a, (hipStream_t)stream) != hipSuccess) return MKA_ERR_LAUNCH;
+  for (int l = 0; l < 3; ++l) len[l] = a.len[l];
+  return MKA_OK;
+}
+
+mka_status mka_fused_attn_bwd(const void* dO, const void* Q, const void* const K[3],
+                              const void* const V[3], const float* G, const void* O,
+                              const float* LSE, const float* W_r, void* dQ, void* const dK[3],
+                              void* const dV[3], float* dW_r, float* db_r, const mka_shape* shape,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  bool empty = false;
+  const mka_status st = check_shape(shape, &empty);
+  if (st != MKA_OK) return st;
+  if (shape->dtype != MKA_BF16) return MKA_ERR_UNSUPPORTED;
+  if (!dO || !Q || !K || !V || !G || !O || !LSE || !dQ || !dK || !dV) return MKA_ERR_NULL;
+  if (!aligned16(dO) || !aligned16(Q) || !aligned16(G) || !aligned16(O) || !aligned16(LSE) ||
+      !aligned16(dQ))
+    return MKA_ERR_ALIGN;
+  mka::BwdArgs a;
+  for (int l = 0; l < 3; ++l) {
+    if (!aligned16(K[l]) || !aligned16(V[l]) || !aligned16(dK[l]) || !aligned16(dV[l]))
+      return MKA_ERR_ALIGN;
+    const bool present = K[l] && V[l];
+    a.K[l] = present ? K[l] : nullptr;
+    a.V[l] = present ? V[l] : nullptr;
+    a.len[l] = present ? shape->len[l] : 0;
+    a.dK[l] = dK[l];
+    a.dV[l] = dV[l];
+  }
+  if (empty) return MKA_OK;
+  const int BH = shape->B * shape->H;
+  const size_t need = mka::bwd_workspace_bytes(BH, shape->Tq, shape->S, shape->d);
+  if (!workspace || workspace_bytes < need) return MKA_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MKA_ERR_ALIGN;
+  a.dO = dO; a.Q = Q; a.G = G; a.O = O; a.LSE = LSE; a.W_r = W_r; a.dQ = dQ;
+  a.dW_r = W_r ? dW_r : nullptr;
+  a.db_r = W_r ? db_r : nullptr;
+  a.BH = BH; a.Tq = shape->Tq; a.S = shape->S; a.d = shape->d;
+  a.causal = shape->causal ? 1 : 0;
+  a.scale = shape->scale;
+  a.workspace = workspace;
+  const hipError_t e = mka::launch_bwd_bf16(a, (hipStream_t)stream);
+  if (e == hipErrorNotSupported) return MKA_ERR_UNSUPPORTED;
+  return e == hipSuccess ? MKA_OK : MKA_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,84 @@
+// Host-side declarations shared by the C-ABI layer and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace mka {
+
+struct RouteArgs {
+  const void* Q;      // [rows = B*H*Tq, d]
+  const float* W_r;   // [d,3]
+  const float* b_r;   // [3] or null
+  float* G;           // [B*H, S, 3] or null
+  int32_t* idx;       // [B*H*Tq] or null
+  int BH, Tq, S, d;
+  bool bf16;
+};
+hipError_t launch_route(const RouteArgs& a, hipStream_t st);
+
+struct FwdArgs {
+  const void* Q;
+  const void* K[3];
+  const void* V[3];
+  const float* G;
+  void* O;
+  float* LSE;  // or null
+  int BH, Tq, S, d;
+  int len[3];
+  int causal;
+  float scale;
+};
+hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t st);
+hipError_t launch_fwd_f32(const FwdArgs& a, hipStream_t st);
+
+struct DecodeArgs {
+  const void* q;
+  const void* k_new[3];
+  const void* v_new[3];
+  void* Kc[3];
+  void* Vc[3];
+  float* Gc;
+  const float* W_r;
+  const float* b_r;
+  void* O;
+  float* LSE;
+  int32_t* idx;
+  int BH, d;
+  int cap[3], capG;
+  int len[3];   // AFTER the append
+  int j_new;    // slot of the new token
+  int S;        // j_new + 1
+  int n_splits;
+  float scale;
+  bool bf16;
+  float* partial;  // workspace [BH, n_splits, d + 2]
+};
+hipError_t launch_decode(const DecodeArgs& a, hipStream_t st);
+int decode_auto_splits(int BH, int S);
+constexpr int kMaxSplits = 64;
+
+struct BwdArgs {
+  const void* dO;
+  const void* Q;
+  const void* K[3];
+  const void* V[3];
+  const float* G;
+  const void* O;
+  const float* LSE;
+  const float* W_r;  // or null
+  void* dQ;
+  void* dK[3];
+  void* dV[3];
+  float* dW_r;
+  float* db_r;
+  int BH, Tq, S, d;
+  int len[3];
+  int causal;
+  float scale;
+  void* workspace;
+};
+hipError_t launch_bwd_bf16(const BwdArgs& a, hipStream_t st);
+size_t bwd_workspace_bytes(int BH, int Tq, int S, int d);
+
+}  // namespace mka

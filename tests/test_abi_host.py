@@ -1,0 +1,134 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments with a status before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def m():
+    import paper_2603_20586_amd as mod
+
+    if not os.path.exists(mod.lib_path()):
+        from paper_2603_20586_amd.build import build_library
+
+        build_library(verbose=False)
+    mod.lib()
+    return mod
+
+
+def test_every_declared_symbol_is_exported(m):
+    hdr = open(os.path.join(ROOT, "include", "mka.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(mka_[a-z_0-9]+)\s*\(", hdr))
+    assert {"mka_route", "mka_fused_attn_fwd", "mka_fused_attn_decode", "mka_fused_attn_bwd",
+            "mka_workspace_bytes", "mka_status_string", "mka_version"} <= names
+    L = m.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert L.mka_version() >= 100
+
+
+def test_status_strings(m):
+    for code, word in [(0, "OK"), (1, "NULL"), (2, "SHAPE"), (3, "DTYPE"), (4, "ALIGN"),
+                       (5, "WORKSPACE"), (6, "UNSUPPORTED"), (7, "LAUNCH")]:
+        assert word in m.status_string(code)
+
+
+def _shape(m, **kw):
+    from paper_2603_20586_amd.binding import MkaShape
+
+    s = MkaShape()
+    s.B, s.H, s.Tq, s.S, s.d = 1, 2, 16, 16, 64
+    s.len[0] = s.len[1] = s.len[2] = 16
+    s.dtype, s.causal, s.scale = 1, 1, 0.125
+    for k, v in kw.items():
+        if k == "len":
+            for i in range(3):
+                s.len[i] = v[i]
+        else:
+            setattr(s, k, v)
+    return s
+
+
+FAKE = 0x10000  # 16-byte aligned, never dereferenced: validation fails first
+
+
+def _fwd(m, s, Q=FAKE, K=(FAKE, FAKE, FAKE), V=(FAKE, FAKE, FAKE), W=FAKE, G=FAKE, O=FAKE):
+    from paper_2603_20586_amd.binding import _P3
+
+    k3, v3 = _P3(*K), _P3(*V)
+    return m.lib().mka_fused_attn_fwd(Q, ctypes.byref(k3), ctypes.byref(v3), W, None, G, O, None,
+                                      None, ctypes.byref(s), None, 0, None)
+
+
+def test_fwd_rejects_bad_arguments_before_launch(m):
+    assert _fwd(m, _shape(m, dtype=7)) == 3
+    assert _fwd(m, _shape(m, Tq=32, S=16)) == 2          # S < Tq
+    assert _fwd(m, _shape(m, B=-1)) == 2
+    assert _fwd(m, _shape(m, len=(17, 0, 0))) == 2        # len > S
+    assert _fwd(m, _shape(m, d=96)) == 6
+    assert _fwd(m, _shape(m, scale=-1.0)) == 6
+    assert _fwd(m, _shape(m, scale=float("nan"))) == 6
+    assert _fwd(m, _shape(m), Q=None) == 1
+    assert _fwd(m, _shape(m), G=None) == 1
+    assert _fwd(m, _shape(m), Q=FAKE + 2) == 4
+    assert _fwd(m, _shape(m), K=(FAKE + 8, FAKE, FAKE)) == 4
+    # a valid problem with no rows is a no-op
+    assert _fwd(m, _shape(m, B=0)) == 0
+    assert _fwd(m, _shape(m, Tq=0, S=0, len=(0, 0, 0))) == 0
+
+
+def test_route_and_bwd_reject_bad_arguments(m):
+    from paper_2603_20586_amd.binding import _P3
+
+    L = m.lib()
+    s = _shape(m)
+    assert L.mka_route(None, FAKE, None, FAKE, None, ctypes.byref(s), None) == 1
+    assert L.mka_route(FAKE, None, None, FAKE, None, ctypes.byref(s), None) == 1
+    assert L.mka_route(FAKE, FAKE, None, FAKE, None, None, None) == 1
+    assert L.mka_route(FAKE, FAKE, None, FAKE + 4, None, ctypes.byref(s), None) == 4
+    p3 = _P3(FAKE, FAKE, FAKE)
+    args = lambda shp, ws, wsb: L.mka_fused_attn_bwd(  # noqa: E731
+        FAKE, FAKE, ctypes.byref(p3), ctypes.byref(p3), FAKE, FAKE, FAKE, FAKE, FAKE,
+        ctypes.byref(p3), ctypes.byref(p3), FAKE, FAKE, ctypes.byref(shp), ws, wsb, None)
+    assert args(_shape(m, dtype=0), FAKE, 1 << 30) == 6   # f32 backward not provided
+    assert args(_shape(m), None, 0) == 5                  # workspace required
+    assert args(_shape(m), FAKE, 16) == 5
+    assert m.mka_workspace_bytes(3, _shape(m)) > 0
+    assert m.mka_workspace_bytes(1, _shape(m)) == 0
+
+
+def test_decode_rejects_bad_arguments(m):
+    from paper_2603_20586_amd.binding import MkaDecodeShape, _P3
+
+    L = m.lib()
+
+    def call(len3=(8, 8, 8), cap=(16, 8, 8), capG=16, knew=(FAKE, None, None), ws=FAKE << 4,
+             wsb=1 << 30, **kw):
+        s = MkaDecodeShape()
+        s.B, s.H, s.d, s.capG, s.dtype, s.n_splits, s.scale = 1, 2, 64, capG, 1, 0, 0.125
+        for i in range(3):
+            s.cap[i] = cap[i]
+        for k, v in kw.items():
+            setattr(s, k, v)
+        ln = (ctypes.c_int32 * 3)(*len3)
+        kn = _P3(*knew)
+        kc = _P3(FAKE, FAKE, FAKE)
+        rc = L.mka_fused_attn_decode(FAKE, ctypes.byref(kn), ctypes.byref(kn), ctypes.byref(kc),
+                                     ctypes.byref(kc), FAKE, ctypes.byref(ln), FAKE, None, FAKE,
+                                     None, None, ctypes.byref(s), ws, wsb, None)
+        return rc, list(ln)
+
+    assert call(knew=(None, None, None))[0] == 2          # nothing appended
+    assert call(len3=(8, 7, 8), knew=(FAKE, FAKE, None))[0] == 2   # level 2 lags: cannot rejoin
+    assert call(cap=(8, 8, 8))[0] == 2                    # level 1 cache full
+    assert call(capG=8)[0] == 2                           # gate cache full
+    assert call(ws=None, wsb=0)[0] == 5
+    assert call(d=100)[0] == 6
+    rc, ln = call(dtype=9)
+    assert rc == 3 and ln == [8, 8, 8]                    # lengths untouched on error

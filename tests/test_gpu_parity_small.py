@@ -1,0 +1,197 @@
+"""GPU parity: HIP path vs the fp64 oracle, element by element, on small seeded cases that
+still span several tiles and ragged tails.  All calls go through the C ABI (via the binding)."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from util import BF16_ATOL, F32_RTOL, GATE_ATOL, announce, cpu_list, max_abs, rel_err, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mka():
+    import paper_2603_20586_amd as m
+
+    assert torch.cuda.is_available()
+    m.lib()
+    return m
+
+
+def _oracle_fwd(oracle, inp, S, len3, causal, G_prev=None):
+    return oracle.fwd_routed(inp["Q"].cpu(), cpu_list(inp["K"]), cpu_list(inp["V"]), inp["W_r"].cpu(),
+                             inp["b_r"].cpu(), G_prev=G_prev, len3=len3, causal=causal,
+                             tau=inp["scale"])
+
+
+# ------------------------------------------------------------------ router
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("B,H,Tq,S", [(1, 1, 1, 1), (2, 3, 77, 77), (1, 2, 130, 200)])
+def test_route(mka, oracle, dtype, d, B, H, Tq, S):
+    announce(f"route {dtype} d={d} B={B} H={H} Tq={Tq} S={S}")
+    inp = si.prefill_inputs(B, H, Tq, S, d, dtype=dtype, seed=11, device="cuda")
+    W = inp["W_r"] * 20.0  # spread the logits so that the argmax is not always a near-tie
+    b = torch.tensor([0.1, -0.2, 0.05], device="cuda")
+    Gprev = torch.rand((B, H, S, 3), device="cuda")
+    G, idx = mka.mka_route(inp["Q"], W, b, S=S, G=Gprev.clone())
+    torch.cuda.synchronize()
+    Gref, idxref = oracle.route(inp["Q"].cpu(), W.cpu(), b.cpu(), S=S, G_prev=Gprev.cpu())
+    np.testing.assert_array_equal(idx.cpu().numpy(), idxref)  # bit-exact argmax
+    assert max_abs(G, Gref) <= GATE_ATOL
+    # rows of older slots untouched
+    assert torch.equal(G[:, :, :S - Tq], Gprev[:, :, :S - Tq])
+
+
+def test_route_exact_ties_go_to_lowest_level(mka):
+    announce("route ties")
+    Q = torch.randn((1, 2, 50, 64), device="cuda").bfloat16()
+    W = torch.zeros((64, 3), device="cuda")
+    G, idx = mka.mka_route(Q, W, None)
+    assert torch.all(idx == 0)
+    assert torch.all(G == torch.tensor(1.0 / 3.0, dtype=torch.float32))
+
+
+# ------------------------------------------------------------------ forward, f32
+def test_fwd_f32_tiny_config(mka, oracle):
+    """Config C1: B=1 H=2 d=64 Tq=128 causal, Q pre-scaled by 1/sqrt(64), scale 1, seed 0."""
+    announce("fwd f32 C1")
+    inp, cfg = si.config_inputs("C1", device="cuda")
+    O, LSE, G, idx = mka.mka_fused_attn_fwd(inp["Q"], inp["K"], inp["V"], inp["W_r"], inp["b_r"],
+                                            causal=True, scale=inp["scale"])
+    torch.cuda.synchronize()
+    Oref, LSEref, Gref, idxref = _oracle_fwd(oracle, inp, 128, None, True)
+    assert rel_err(O, Oref) <= F32_RTOL
+    assert rel_err(LSE, LSEref) <= F32_RTOL
+    assert max_abs(G, Gref) <= GATE_ATOL
+    np.testing.assert_array_equal(idx.cpu().numpy(), idxref)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("Tq,S,causal,len3", [
+    (100, 100, True, None), (70, 150, True, None), (33, 97, False, None),
+    (65, 65, True, [65, 40, 0]), (1, 1, True, None)])
+def test_fwd_f32_shapes(mka, oracle, d, Tq, S, causal, len3):
+    announce(f"fwd f32 d={d} Tq={Tq} S={S} causal={causal} len={len3}")
+    inp = si.prefill_inputs(2, 2, Tq, S, d, dtype="f32", seed=5, device="cuda")
+    Gprev = torch.softmax(torch.randn((2, 2, S, 3), device="cuda"), -1)
+    O, LSE, G, idx = mka.mka_fused_attn_fwd(inp["Q"], inp["K"], inp["V"], inp["W_r"], inp["b_r"],
+                                            G=Gprev.clone(), len3=len3, causal=causal,
+                                            scale=inp["scale"])
+    torch.cuda.synchronize()
+    Oref, LSEref, Gref, idxref = _oracle_fwd(oracle, inp, S, len3, causal, G_prev=Gprev.cpu())
+    assert rel_err(O, Oref) <= F32_RTOL
+    assert rel_err(LSE, LSEref) <= F32_RTOL
+    assert max_abs(G, Gref) <= GATE_ATOL
+    np.testing.assert_array_equal(idx.cpu().numpy(), idxref)
+
+
+# ------------------------------------------------------------------ forward, bf16 MFMA
+@pytest.mark.parametrize("d", [128, 64])
+@pytest.mark.parametrize("Tq,S,causal,len3", [
+    (300, 300, True, None),      # several q tiles and kv tiles, ragged both ways
+    (128, 128, True, None),      # exactly one q tile
+    (130, 333, True, None),      # cache prefix, bottom-right mask
+    (200, 260, False, None),     # non-causal
+    (257, 257, True, [257, 100, 0]),  # absent levels
+    (1, 1, True, None), (1, 70, True, None)])
+def test_fwd_bf16_shapes(mka, oracle, d, Tq, S, causal, len3):
+    announce(f"fwd bf16 d={d} Tq={Tq} S={S} causal={causal} len={len3}")
+    inp = si.prefill_inputs(2, 2, Tq, S, d, dtype="bf16", seed=7, device="cuda")
+    W = inp["W_r"] * 10.0  # visibly non-uniform gates
+    inp["W_r"] = W
+    Gprev = torch.softmax(torch.randn((2, 2, S, 3), device="cuda"), -1)
+    O, LSE, G, idx = mka.mka_fused_attn_fwd(inp["Q"], inp["K"], inp["V"], W, inp["b_r"],
+                                            G=Gprev.clone(), len3=len3, causal=causal,
+                                            scale=inp["scale"])
+    torch.cuda.synchronize()
+    Oref, LSEref, Gref, idxref = _oracle_fwd(oracle, inp, S, len3, causal, G_prev=Gprev.cpu())
+    assert max_abs(G, Gref) <= GATE_ATOL
+    np.testing.assert_array_equal(idx.cpu().numpy(), idxref)
+    assert max_abs(O, Oref) <= BF16_ATOL, max_abs(O, Oref)
+    assert max_abs(LSE, LSEref) <= BF16_ATOL
+
+
+def test_fwd_bf16_given_gates_no_router(mka, oracle):
+    announce("fwd bf16 given gates")
+    inp = si.prefill_inputs(1, 2, 150, 150, 128, dtype="bf16", seed=8, device="cuda")
+    G = torch.softmax(torch.randn((1, 2, 150, 3), device="cuda") * 2, -1)
+    O, LSE, G2, idx = mka.mka_fused_attn_fwd(inp["Q"], inp["K"], inp["V"], None, None, G=G.clone(),
+                                             causal=True, scale=inp["scale"])
+    torch.cuda.synchronize()
+    assert idx is None and torch.equal(G, G2)
+    Oref, LSEref = oracle.fwd(inp["Q"].cpu(), cpu_list(inp["K"]), cpu_list(inp["V"]), G.cpu(),
+                              causal=True, tau=inp["scale"])
+    assert max_abs(O, Oref) <= BF16_ATOL
+
+
+def test_fwd_bf16_one_hot_gates_equal_plain_attention(mka):
+    """Property that needs no oracle: with a +1000 bias on one level the result is standard
+    causal attention over that memory (here: torch's own SDPA on the GPU in f32)."""
+    announce("fwd bf16 one-hot")
+    inp = si.prefill_inputs(1, 2, 200, 200, 128, dtype="bf16", seed=9, device="cuda")
+    W = torch.zeros_like(inp["W_r"])
+    b = torch.tensor([0.0, 1000.0, 0.0], device="cuda")
+    O, LSE, G, idx = mka.mka_fused_attn_fwd(inp["Q"], inp["K"], inp["V"], W, b, causal=True,
+                                            scale=inp["scale"])
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        inp["Q"].float(), inp["K"][1].float(), inp["V"][1].float(), is_causal=True,
+        scale=inp["scale"])
+    assert torch.all(idx == 1)
+    assert float((O.float() - ref).abs().max()) <= BF16_ATOL
+
+
+# ------------------------------------------------------------------ decode
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 128), ("f32", 64)])
+@pytest.mark.parametrize("n_splits", [0, 1, 3])
+def test_decode_steps(mka, oracle, dtype, d, n_splits):
+    announce(f"decode {dtype} d={d} n_splits={n_splits}")
+    B, H, S0, steps = 2, 3, 777, 3
+    c = si.decode_caches(B, H, d, S0, cap_extra=steps, dtype=dtype, seed=21, device="cuda")
+    Kc_o = [to_np(x).copy() for x in c["Kc"]]
+    Vc_o = [to_np(x).copy() for x in c["Vc"]]
+    Gc_o = to_np(c["Gc"]).copy()
+    len_g, len_o = list(c["len"]), list(c["len"])
+    tol = (lambda x, r: max_abs(x, r) <= BF16_ATOL) if dtype == "bf16" else \
+        (lambda x, r: rel_err(x, r) <= F32_RTOL)
+    for step in range(steps):
+        q, k1, v1 = si.decode_step_inputs(B, H, d, step, dtype=dtype, seed=21, device="cuda")
+        O, LSE, idx = mka.mka_fused_attn_decode(q, [k1, None, None], [v1, None, None], c["Kc"],
+                                                c["Vc"], c["Gc"], len_g, c["W_r"], c["b_r"],
+                                                scale=c["scale"], n_splits=n_splits)
+        torch.cuda.synchronize()
+        Oref, LSEref, idxref = oracle.decode(q.cpu(), [k1.cpu(), None, None],
+                                             [v1.cpu(), None, None], Kc_o, Vc_o, Gc_o, len_o,
+                                             c["W_r"].cpu(), c["b_r"].cpu(), tau=c["scale"])
+        assert len_g == len_o == [S0 + step + 1, S0, S0]
+        np.testing.assert_array_equal(idx.cpu().numpy(), idxref)
+        assert tol(O, Oref), (step, max_abs(O, Oref))
+        assert tol(LSE, LSEref[:, :, 0])
+        assert max_abs(c["Gc"], Gc_o) <= GATE_ATOL
+        assert np.array_equal(to_np(c["Kc"][0]), Kc_o[0])  # appended entries, bit for bit
+
+
+def test_decode_equals_last_prefill_row(mka):
+    """Property: a decode step over caches filled by a prefill == the prefill's last row."""
+    announce("decode vs prefill row")
+    B, H, d, S = 1, 4, 128, 500
+    inp = si.prefill_inputs(B, H, S, S, d, dtype="bf16", seed=31, device="cuda")
+    O, LSE, G, idx = mka.mka_fused_attn_fwd(inp["Q"], inp["K"], inp["V"], inp["W_r"], inp["b_r"],
+                                            causal=True, scale=inp["scale"])
+    Kc = [k.clone() for k in inp["K"]]
+    Vc = [v.clone() for v in inp["V"]]
+    Gc = G.clone()
+    Gc[:, :, S - 1] = 0
+    len3 = [S - 1, S - 1, S - 1]
+    last = slice(S - 1, S)
+    Od, LSEd, idxd = mka.mka_fused_attn_decode(
+        inp["Q"][:, :, last].contiguous(), [k[:, :, last].contiguous() for k in inp["K"]],
+        [v[:, :, last].contiguous() for v in inp["V"]], Kc, Vc, Gc, len3, inp["W_r"], inp["b_r"],
+        scale=inp["scale"])
+    torch.cuda.synchronize()
+    assert len3 == [S, S, S]
+    assert torch.equal(Gc, G)
+    assert torch.equal(idxd, idx[:, :, -1])
+    assert float((Od.float() - O[:, :, last].float()).abs().max()) <= BF16_ATOL
+    assert float((LSEd - LSE[:, :, -1]).abs().max()) <= 1e-2
