@@ -1,0 +1,53 @@
+// Route-fusion of one 16-byte chunk (8 bf16) of a slot's three memory rows (paper: Alg. 2
+// step 6, Xf = sum_l lam_l * L_l, applied to projected K/V rows): f32 math, caller rounds once.
+//
+// Loads are issued unconditionally so that a caller can batch many of them before the first
+// use.  FULL = every level is present at the slot (interior tiles): no predicates at all.
+// Otherwise the address of an absent entry is redirected to row 0 of the same (b,h) block,
+// which always exists, and the loaded bits are replaced by zero — never multiplied by a zero
+// gate, so stale NaN/Inf bits in unused cache rows cannot leak into the result.
+#pragma once
+#include "mka_dev.h"
+
+namespace mka {
+
+struct Raw3 {
+  uint4 a, b, c;
+};
+
+// base: element offset of row 0 of this (b,h) block; eoff: element offset of the wanted chunk.
+template <bool FULL>
+__device__ __forceinline__ Raw3 load_raw3(const bf16* __restrict__ P0, const bf16* __restrict__ P1,
+                                          const bf16* __restrict__ P2, long base_chunk, long eoff,
+                                          bool p0, bool p1, bool p2) {
+  Raw3 r;
+  if constexpr (FULL) {
+    r.a = *reinterpret_cast<const uint4*>(P0 + eoff);
+    r.b = *reinterpret_cast<const uint4*>(P1 + eoff);
+    r.c = *reinterpret_cast<const uint4*>(P2 + eoff);
+  } else {
+    r.a = *reinterpret_cast<const uint4*>(P0 + (p0 ? eoff : base_chunk));
+    r.b = *reinterpret_cast<const uint4*>(P1 + (p1 ? eoff : base_chunk));
+    r.c = *reinterpret_cast<const uint4*>(P2 + (p2 ? eoff : base_chunk));
+    const uint4 z = make_uint4(0, 0, 0, 0);
+    if (!p0) r.a = z;
+    if (!p1) r.b = z;
+    if (!p2) r.c = z;
+  }
+  return r;
+}
+
+__device__ __forceinline__ void fuse8(const Raw3& r, float g0, float g1, float g2, float* out) {
+  float f[8];
+  unpack8(r.a, f);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) out[e] = g0 * f[e];
+  unpack8(r.b, f);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) out[e] = fmaf(g1, f[e], out[e]);
+  unpack8(r.c, f);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) out[e] = fmaf(g2, f[e], out[e]);
+}
+
+}  // namespace mka

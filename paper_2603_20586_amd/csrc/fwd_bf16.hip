@@ -17,6 +17,7 @@
 // The rows of the Kf tile are fed to the MFMA in an order that swaps bits 2 and 3 of the row
 // index; this makes the 8 P values a lane packs for one PV k-step belong to 8 consecutive
 // slots, i.e. one 16-byte LDS read of Vf^T.
+#include "fuse_tile.h"
 #include "mka_dev.h"
 #include "mka_internal.h"
 
@@ -30,8 +31,81 @@ __device__ __forceinline__ int swap23(int i) {
   return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1);
 }
 
+
+// Fuse one KV tile of BC slots into LDS: Kf row-major (row stride KSTR), Vf transposed (row
+// stride VSTR).  K work item = (row, 16-byte chunk); V work item = (4 consecutive slots, chunk),
+// so that a thread can emit 8-byte transposed writes.  All global loads of a thread are issued
+// before the first use.
+template <int D, int NT, bool FULL>
+__device__ __forceinline__ void fuse_tile(const bf16* __restrict__ K0, const bf16* __restrict__ K1,
+                                          const bf16* __restrict__ K2, const bf16* __restrict__ V0,
+                                          const bf16* __restrict__ V1, const bf16* __restrict__ V2,
+                                          const float* __restrict__ Gb, long kvbase, int j0, int S,
+                                          int len0, int len1, int len2, bf16* sK, bf16* sVT) {
+  constexpr int KSTR = D + 8, VSTR = BC + 8, CPR = D / 8;
+  constexpr int KITEMS = BC * CPR, VITEMS = (BC / 4) * CPR;
+  constexpr int KPT = (KITEMS + NT - 1) / NT, VPT = (VITEMS + NT - 1) / NT;
+  const int tid = threadIdx.x;
+  Raw3 kr[KPT];
+  float kg[KPT][3];
+#pragma unroll
+  for (int i = 0; i < KPT; ++i) {
+    const int it = tid + i * NT;
+    const int row = (it / CPR) % BC, cc = it % CPR;  // % BC keeps a surplus thread in range
+    const int j = j0 + row;
+    const int jc = FULL ? j : (j < S ? j : S - 1);
+    const bool in = FULL || j < S;
+    kr[i] = load_raw3<FULL>(K0, K1, K2, kvbase + cc * 8, kvbase + (long)jc * D + cc * 8,
+                            in && j < len0, in && j < len1, in && j < len2);
+    kg[i][0] = Gb[jc * 3 + 0]; kg[i][1] = Gb[jc * 3 + 1]; kg[i][2] = Gb[jc * 3 + 2];
+  }
+  Raw3 vr[VPT][4];
+  float vg[VPT][4][3];
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    const int it = tid + i * NT;
+    const int sg = (it / CPR) % (BC / 4), cc = it % CPR;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + sg * 4 + u;
+      const int jc = FULL ? j : (j < S ? j : S - 1);
+      const bool in = FULL || j < S;
+      vr[i][u] = load_raw3<FULL>(V0, V1, V2, kvbase + cc * 8, kvbase + (long)jc * D + cc * 8,
+                                 in && j < len0, in && j < len1, in && j < len2);
+      vg[i][u][0] = Gb[jc * 3 + 0]; vg[i][u][1] = Gb[jc * 3 + 1]; vg[i][u][2] = Gb[jc * 3 + 2];
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < KPT; ++i) {
+    const int it = tid + i * NT;
+    if (KITEMS % NT == 0 || it < KITEMS) {
+      const int row = it / CPR, cc = it % CPR;
+      float acc[8];
+      fuse8(kr[i], kg[i][0], kg[i][1], kg[i][2], acc);
+      *reinterpret_cast<uint4*>(&sK[row * KSTR + cc * 8]) = pack8(acc);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    const int it = tid + i * NT;
+    if (VITEMS % NT == 0 || it < VITEMS) {
+      const int sg = it / CPR, cc = it % CPR;
+      float vf[4][8];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) fuse8(vr[i][u], vg[i][u][0], vg[i][u][1], vg[i][u][2], vf[u]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        uint2 w;
+        w.x = pack_bf16x2(vf[0][e], vf[1][e]);
+        w.y = pack_bf16x2(vf[2][e], vf[3][e]);
+        *reinterpret_cast<uint2*>(&sVT[(cc * 8 + e) * VSTR + sg * 4]) = w;
+      }
+    }
+  }
+}
+
 template <int D, int NW>
-__global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(
+__global__ __launch_bounds__(NW * 64, 8 / NW) void fwd_bf16_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K0, const bf16* __restrict__ K1,
     const bf16* __restrict__ K2, const bf16* __restrict__ V0, const bf16* __restrict__ V1,
     const bf16* __restrict__ V2, const float* __restrict__ G, bf16* __restrict__ O,
@@ -41,7 +115,6 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(
   constexpr int BR = NW * 32;
   constexpr int KSTR = D + 8;       // bf16 elements per Kf row in LDS (16-byte pad)
   constexpr int VSTR = BC + 8;      // bf16 elements per Vf^T row in LDS
-  constexpr int CPR = D / 8;        // 16-byte chunks per K/V row
   constexpr int KK = D / 16;        // MFMA k-steps over d
   constexpr int DB = D / 32;        // 32-row blocks of O^T
   __shared__ __attribute__((aligned(16))) bf16 sK[BC * KSTR];
@@ -83,73 +156,12 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(
   for (int jt = 0; jt < ntiles; ++jt) {
     const int j0 = jt * BC;
     __syncthreads();  // all waves are done reading the previous tile
-    // ---- fuse K: thread -> (row, 16-byte chunk)
-    for (int it = tid; it < BC * CPR; it += NT) {
-      const int row = it / CPR, cc = it % CPR;
-      const int j = j0 + row;
-      float acc[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-      if (j < S) {
-        const long eoff = kvbase + (long)j * D + cc * 8;
-        const float g0 = Gb[j * 3 + 0], g1 = Gb[j * 3 + 1], g2 = Gb[j * 3 + 2];
-        float f[8];
-        if (j < len0) {
-          unpack8(*reinterpret_cast<const uint4*>(K0 + eoff), f);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) acc[e] = g0 * f[e];
-        }
-        if (j < len1) {
-          unpack8(*reinterpret_cast<const uint4*>(K1 + eoff), f);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) acc[e] = fmaf(g1, f[e], acc[e]);
-        }
-        if (j < len2) {
-          unpack8(*reinterpret_cast<const uint4*>(K2 + eoff), f);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) acc[e] = fmaf(g2, f[e], acc[e]);
-        }
-      }
-      *reinterpret_cast<uint4*>(&sK[row * KSTR + cc * 8]) = pack8(acc);
-    }
-    // ---- fuse V: thread -> (group of 4 slots, 16-byte chunk); written transposed
-    for (int it = tid; it < (BC / 4) * CPR; it += NT) {
-      const int sg = it / CPR, cc = it % CPR;
-      float vf[4][8];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int j = j0 + sg * 4 + u;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) vf[u][e] = 0.f;
-        if (j < S) {
-          const long eoff = kvbase + (long)j * D + cc * 8;
-          const float g0 = Gb[j * 3 + 0], g1 = Gb[j * 3 + 1], g2 = Gb[j * 3 + 2];
-          float f[8];
-          if (j < len0) {
-            unpack8(*reinterpret_cast<const uint4*>(V0 + eoff), f);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) vf[u][e] = g0 * f[e];
-          }
-          if (j < len1) {
-            unpack8(*reinterpret_cast<const uint4*>(V1 + eoff), f);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) vf[u][e] = fmaf(g1, f[e], vf[u][e]);
-          }
-          if (j < len2) {
-            unpack8(*reinterpret_cast<const uint4*>(V2 + eoff), f);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) vf[u][e] = fmaf(g2, f[e], vf[u][e]);
-          }
-        }
-      }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        uint2 w;
-        w.x = pack_bf16x2(vf[0][e], vf[1][e]);
-        w.y = pack_bf16x2(vf[2][e], vf[3][e]);
-        *reinterpret_cast<uint2*>(&sVT[(cc * 8 + e) * VSTR + sg * 4]) = w;
-      }
-    }
+    // ---- fuse K and V of this tile into LDS (interior tiles take the predicate-free path)
+    const bool full = (j0 + BC <= len0) && (j0 + BC <= len1) && (j0 + BC <= len2);
+    if (full)
+      fuse_tile<D, NT, true>(K0, K1, K2, V0, V1, V2, Gb, kvbase, j0, S, len0, len1, len2, sK, sVT);
+    else
+      fuse_tile<D, NT, false>(K0, K1, K2, V0, V1, V2, Gb, kvbase, j0, S, len0, len1, len2, sK, sVT);
     __syncthreads();
 
     // ---- S^T = Kf Q^T   (two blocks of 32 slots)
@@ -245,15 +257,26 @@ __global__ __launch_bounds__(NW * 64, 2) void fwd_bf16_kernel(
 
 hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t st) {
   if (a.BH == 0 || a.Tq == 0) return hipSuccess;
-  constexpr int NW = 4;
+  constexpr int NW = 8;
   const int n_qtiles = (a.Tq + NW * 32 - 1) / (NW * 32);
   const long nblocks = (long)n_qtiles * a.BH;
   const float c = a.scale * kLog2e;
+  // a level without memory is given another level's (same-shaped) buffer and length 0: the
+  // kernel then never uses what it reads from it
+  const void* Kp[3];
+  const void* Vp[3];
+  const void* anyK = a.K[0] ? a.K[0] : (a.K[1] ? a.K[1] : a.K[2]);
+  const void* anyV = a.V[0] ? a.V[0] : (a.V[1] ? a.V[1] : a.V[2]);
+  if (!anyK || !anyV) return hipErrorInvalidValue;
+  for (int l = 0; l < 3; ++l) {
+    Kp[l] = a.K[l] ? a.K[l] : anyK;
+    Vp[l] = a.V[l] ? a.V[l] : anyV;
+  }
 #define MKA_FWD(D)                                                                              \
   hipLaunchKernelGGL((fwd_bf16_kernel<D, NW>), dim3((unsigned)nblocks), dim3(NW * 64), 0, st,  \
-                     (const bf16*)a.Q, (const bf16*)a.K[0], (const bf16*)a.K[1],                \
-                     (const bf16*)a.K[2], (const bf16*)a.V[0], (const bf16*)a.V[1],             \
-                     (const bf16*)a.V[2], a.G, (bf16*)a.O, a.LSE, a.Tq, a.S, a.len[0], a.len[1], \
+                     (const bf16*)a.Q, (const bf16*)Kp[0], (const bf16*)Kp[1],                  \
+                     (const bf16*)Kp[2], (const bf16*)Vp[0], (const bf16*)Vp[1],               \
+                     (const bf16*)Vp[2], a.G, (bf16*)a.O, a.LSE, a.Tq, a.S, a.len[0], a.len[1], \
                      a.len[2], a.causal, c, a.scale, n_qtiles)
   if (a.d == 128) MKA_FWD(128); else MKA_FWD(64);
 #undef MKA_FWD

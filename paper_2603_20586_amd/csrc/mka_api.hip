@@ -108,6 +108,7 @@ mka_status mka_fused_attn_fwd(const void* Q, const void* const K[3], const void*
     a.V[l] = present ? V[l] : nullptr;
     a.len[l] = present ? shape->len[l] : 0;
   }
+  if (!a.K[0] && !a.K[1] && !a.K[2]) return MKA_ERR_NULL;  // at least one memory level
   if (empty) return MKA_OK;
   hipStream_t hs = (hipStream_t)stream;
   const int BH = shape->B * shape->H;
