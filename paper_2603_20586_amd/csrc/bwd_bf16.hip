@@ -1,7 +1,549 @@
-// placeholder, replaced below
+// Backward of route-fused attention, bf16 MFMA path.  The paper prints no backward; this is
+// the chain rule through Alg. 2 steps 5-9 (router -> route-fusion -> causal softmax attention):
+//   D[t]     = dO[t].O[t]
+//   P[t,j]   = exp(tau Q[t].Kf[j] - LSE[t])            (recomputed, never stored)
+//   dVf[j]   = sum_t P[t,j] dO[t]          dP[t,j] = dO[t].Vf[j]
+//   dS[t,j]  = P[t,j] (dP[t,j] - D[t])
+//   dKf[j]   = tau sum_t dS[t,j] Q[t]      dQ[t]   = tau sum_j dS[t,j] Kf[j]
+//   dK_l[j]  = G[j,l] dKf[j]               dV_l[j] = G[j,l] dVf[j]          (un-fusion)
+//   dlam[j,l]= dKf[j].K_l[j] + dVf[j].V_l[j]
+//   dg[j,l]  = G[j,l] (dlam[j,l] - sum_m G[j,m] dlam[j,m])                   (softmax Jacobian)
+//   dQ[t]   += sum_l dg[j(t),l] W_r[:,l]   dW_r = sum Q[t]^T dg   db_r = sum dg   (new slots only)
+//
+// Launch sequence:
+//   prep    D = rowsum(dO*O); zero the f32 dQ accumulator
+//   main    one workgroup owns 128 KV slots (4 waves x 32 slots): fuses its Kf/Vf ONCE, keeps
+//           them as MFMA B operands in registers, then walks over the query tiles that can see
+//           it.  Per tile: S = Q Kf^T and dP = dO Vf^T (A = Q / dO rows from LDS), P and dS in
+//           registers, dVf^T += dO^T P and dKf^T += Q^T dS (A = transposed tiles from LDS, B = P /
+//           dS straight from the accumulator layout), dS goes through LDS once so that
+//           dQ^T = Kf^T dS^T can contract over all 128 slots; dQ is accumulated in f32 with
+//           atomics.  Epilogue: un-fusion, dlam, dg.
+//   finish  dQ = tau*acc + dg W_r^T -> bf16; per-workgroup partial sums of Q^T dg and dg
+//   reduce  fixed-order sum of the partials -> dW_r, db_r   (deterministic)
+#include "fuse_tile.h"
 #include "mka_dev.h"
 #include "mka_internal.h"
+
 namespace mka {
-size_t bwd_workspace_bytes(int BH, int Tq, int S, int d) { (void)BH; (void)Tq; (void)S; (void)d; return 256; }
-hipError_t launch_bwd_bf16(const BwdArgs& a, hipStream_t st) { (void)a; (void)st; return hipErrorNotSupported; }
+
+namespace {
+
+constexpr int BCB = 128;  // slots per workgroup of the main kernel
+constexpr int FIN_ROWS = 256;  // rows per workgroup of the finish kernel
+
+__device__ __forceinline__ int swap23(int i) {
+  return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1);
 }
+
+// ------------------------------------------------------------------ prep
+template <int D>
+__global__ __launch_bounds__(256) void bwd_prep_kernel(const bf16* __restrict__ dO,
+                                                       const bf16* __restrict__ O,
+                                                       float* __restrict__ Dvec,
+                                                       float* __restrict__ dQacc, long rows) {
+  constexpr int CPR = D / 8;
+  const long item = (long)blockIdx.x * 256 + threadIdx.x;
+  const long row = item / CPR;
+  const int cc = (int)(item % CPR);
+  float part = 0.f;
+  if (row < rows) {
+    float a[8], b[8];
+    unpack8(*reinterpret_cast<const uint4*>(dO + row * D + cc * 8), a);
+    unpack8(*reinterpret_cast<const uint4*>(O + row * D + cc * 8), b);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part = fmaf(a[e], b[e], part);
+    float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+    *reinterpret_cast<float4*>(dQacc + row * D + cc * 8) = z;
+    *reinterpret_cast<float4*>(dQacc + row * D + cc * 8 + 4) = z;
+  }
+  part = group_sum<CPR>(part);  // CPR consecutive lanes hold one row
+  if (row < rows && cc == 0) Dvec[row] = part;
+}
+
+// ------------------------------------------------------------------ main
+template <int D, int TB>
+struct BwdSmem {
+  static constexpr int BR = 32 * TB;
+  static constexpr int RSTR = D + 8;     // row-major Q / dO tiles
+  static constexpr int TSTR = BR + 8;    // transposed Q / dO tiles
+  static constexpr int SSTR = BCB + 8;   // dS tile, Kf^T
+  static constexpr int OFF_Q = 0;
+  static constexpr int OFF_DO = OFF_Q + BR * RSTR;
+  static constexpr int OFF_QT = OFF_DO + BR * RSTR;
+  static constexpr int OFF_DOT = OFF_QT + D * TSTR;
+  static constexpr int OFF_DS = OFF_DOT + D * TSTR;
+  static constexpr int LOOP_END = OFF_DS + BR * SSTR;
+  // set-up only: row-major Kf and Vf of the workgroup's 128 slots
+  static constexpr int OFF_KROW = 0;
+  static constexpr int OFF_VROW = BCB * RSTR;
+  static constexpr int SETUP_END = 2 * BCB * RSTR;
+  static constexpr int OFF_KT = LOOP_END > SETUP_END ? LOOP_END : SETUP_END;  // persistent Kf^T
+  static constexpr int TOTAL = OFF_KT + D * SSTR;  // bf16 elements
+};
+
+template <int D, int TB>
+__global__ __launch_bounds__(256, 1) void bwd_main_kernel(
+    const bf16* __restrict__ dO, const bf16* __restrict__ Q, const bf16* __restrict__ K0,
+    const bf16* __restrict__ K1, const bf16* __restrict__ K2, const bf16* __restrict__ V0,
+    const bf16* __restrict__ V1, const bf16* __restrict__ V2, const float* __restrict__ G,
+    const float* __restrict__ LSE, const float* __restrict__ Dvec, bf16* __restrict__ dK0,
+    bf16* __restrict__ dK1, bf16* __restrict__ dK2, bf16* __restrict__ dV0, bf16* __restrict__ dV1,
+    bf16* __restrict__ dV2, float* __restrict__ dQacc, float* __restrict__ dgate, int Tq, int S,
+    int len0, int len1, int len2, int causal, float c, float tau, int n_kvtiles) {
+  using L = BwdSmem<D, TB>;
+  constexpr int BR = L::BR, RSTR = L::RSTR, TSTR = L::TSTR, SSTR = L::SSTR;
+  constexpr int CPR = D / 8, KK = D / 16, DB = D / 32, NT = 256;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16* smem = reinterpret_cast<bf16*>(smem_raw);
+  bf16* sQ = smem + L::OFF_Q;
+  bf16* sdO = smem + L::OFF_DO;
+  bf16* sQT = smem + L::OFF_QT;
+  bf16* sdOT = smem + L::OFF_DOT;
+  bf16* sdS = smem + L::OFF_DS;
+  bf16* sKT = smem + L::OFF_KT;
+  float* sL = reinterpret_cast<float*>(smem + L::TOTAL);  // [BR] LSE in log2 units
+  float* sDv = sL + BR;                                   // [BR] D
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
+  const int jt = (int)(blockIdx.x % n_kvtiles);  // tile 0 sees every row: heaviest first
+  const long bh = blockIdx.x / n_kvtiles;
+  const int J0 = jt * BCB;
+  const int off = S - Tq;
+  const long kvbase = bh * (long)S * D;
+  const long qbase = bh * (long)Tq * D;
+  const float* Gb = G + bh * (long)S * 3;
+  const int jmine = J0 + 32 * wave + li;  // the slot this lane owns in S / dP / dVf^T / dKf^T
+
+  // ---- set-up: fuse the 128 slots once.  Item = (4 consecutive slots, 16-byte chunk).
+  {
+    bf16* sKrow = smem + L::OFF_KROW;
+    bf16* sVrow = smem + L::OFF_VROW;
+    const bool full = (J0 + BCB <= len0) && (J0 + BCB <= len1) && (J0 + BCB <= len2);
+    for (int it = tid; it < (BCB / 4) * CPR; it += NT) {
+      const int sg = it / CPR, cc = it % CPR;
+      float kf[4][8], vf[4][8];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int j = J0 + sg * 4 + u;
+        const int jc = j < S ? j : S - 1;
+        const bool in = j < S;
+        const long eoff = kvbase + (long)jc * D + cc * 8;
+        const float g0 = Gb[jc * 3 + 0], g1 = Gb[jc * 3 + 1], g2 = Gb[jc * 3 + 2];
+        Raw3 rk, rv;
+        if (full) {
+          rk = load_raw3<true>(K0, K1, K2, 0, eoff, true, true, true);
+          rv = load_raw3<true>(V0, V1, V2, 0, eoff, true, true, true);
+        } else {
+          rk = load_raw3<false>(K0, K1, K2, kvbase + cc * 8, eoff, in && j < len0, in && j < len1,
+                                in && j < len2);
+          rv = load_raw3<false>(V0, V1, V2, kvbase + cc * 8, eoff, in && j < len0, in && j < len1,
+                                in && j < len2);
+        }
+        fuse8(rk, g0, g1, g2, kf[u]);
+        fuse8(rv, g0, g1, g2, vf[u]);
+        *reinterpret_cast<uint4*>(&sKrow[(sg * 4 + u) * RSTR + cc * 8]) = pack8(kf[u]);
+        *reinterpret_cast<uint4*>(&sVrow[(sg * 4 + u) * RSTR + cc * 8]) = pack8(vf[u]);
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        uint2 w;
+        w.x = pack_bf16x2(kf[0][e], kf[1][e]);
+        w.y = pack_bf16x2(kf[2][e], kf[3][e]);
+        *reinterpret_cast<uint2*>(&sKT[(cc * 8 + e) * SSTR + sg * 4]) = w;
+      }
+    }
+  }
+  __syncthreads();
+  bf16x8 kreg[KK], vreg[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    kreg[kk] = *reinterpret_cast<const bf16x8*>(smem + L::OFF_KROW + (32 * wave + li) * RSTR + 16 * kk + 8 * g);
+    vreg[kk] = *reinterpret_cast<const bf16x8*>(smem + L::OFF_VROW + (32 * wave + li) * RSTR + 16 * kk + 8 * g);
+  }
+
+  f32x16 dVacc[DB], dKacc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dVacc[db][r] = 0.f; dKacc[db][r] = 0.f; }
+
+  // first query tile that can see slot J0 (rows t with t + off >= J0)
+  int t_first = 0;
+  if (causal && J0 - off > 0) t_first = J0 - off;
+  const int n_qt = (Tq + BR - 1) / BR;
+
+  for (int qt = t_first / BR; qt < n_qt; ++qt) {
+    const int t0 = qt * BR;
+    __syncthreads();  // previous tile fully consumed (also guards the set-up buffers)
+    // ---- load the Q and dO tiles: item = (4 consecutive rows, chunk); row-major + transposed
+    for (int it = tid; it < (BR / 4) * CPR; it += NT) {
+      const int rg = it / CPR, cc = it % CPR;
+      uint4 q4[4], o4[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int t = t0 + rg * 4 + u;
+        q4[u] = make_uint4(0, 0, 0, 0);
+        o4[u] = q4[u];
+        if (t < Tq) {
+          q4[u] = *reinterpret_cast<const uint4*>(Q + qbase + (long)t * D + cc * 8);
+          o4[u] = *reinterpret_cast<const uint4*>(dO + qbase + (long)t * D + cc * 8);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        *reinterpret_cast<uint4*>(&sQ[(rg * 4 + u) * RSTR + cc * 8]) = q4[u];
+        *reinterpret_cast<uint4*>(&sdO[(rg * 4 + u) * RSTR + cc * 8]) = o4[u];
+      }
+      // transpose 4 rows x 8 columns of 16-bit values: column e of the 4 rows -> one 8-byte word
+      const uint32_t* qw[4] = {&q4[0].x, &q4[1].x, &q4[2].x, &q4[3].x};
+      const uint32_t* ow[4] = {&o4[0].x, &o4[1].x, &o4[2].x, &o4[3].x};
+#pragma unroll
+      for (int e2 = 0; e2 < 4; ++e2) {  // dword e2 holds columns 2*e2, 2*e2+1
+        uint2 lo, hi, lo2, hi2;
+        lo.x = (qw[0][e2] & 0xffffu) | (qw[1][e2] << 16);
+        lo.y = (qw[2][e2] & 0xffffu) | (qw[3][e2] << 16);
+        hi.x = (qw[0][e2] >> 16) | (qw[1][e2] & 0xffff0000u);
+        hi.y = (qw[2][e2] >> 16) | (qw[3][e2] & 0xffff0000u);
+        lo2.x = (ow[0][e2] & 0xffffu) | (ow[1][e2] << 16);
+        lo2.y = (ow[2][e2] & 0xffffu) | (ow[3][e2] << 16);
+        hi2.x = (ow[0][e2] >> 16) | (ow[1][e2] & 0xffff0000u);
+        hi2.y = (ow[2][e2] >> 16) | (ow[3][e2] & 0xffff0000u);
+        *reinterpret_cast<uint2*>(&sQT[(cc * 8 + 2 * e2) * TSTR + rg * 4]) = lo;
+        *reinterpret_cast<uint2*>(&sQT[(cc * 8 + 2 * e2 + 1) * TSTR + rg * 4]) = hi;
+        *reinterpret_cast<uint2*>(&sdOT[(cc * 8 + 2 * e2) * TSTR + rg * 4]) = lo2;
+        *reinterpret_cast<uint2*>(&sdOT[(cc * 8 + 2 * e2 + 1) * TSTR + rg * 4]) = hi2;
+      }
+    }
+    if (tid < BR) {
+      const int t = t0 + tid;
+      // rows past the end get LSE = +inf, hence P = 0
+      sL[tid] = t < Tq ? LSE[bh * (long)Tq + t] * kLog2e : INFINITY;
+      sDv[tid] = t < Tq ? Dvec[bh * (long)Tq + t] : 0.f;
+    }
+    __syncthreads();
+
+    // ---- S, dP, P, dS per block of 32 rows
+    bf16x8 pP[TB][2], pdS[TB][2];
+    const bool need_mask = (J0 + BCB > S) || (causal && (J0 + BCB - 1 > t0 + off));
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb) {
+      f32x16 sacc, pacc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
+      const int arow = (32 * tb + swap23(li)) * RSTR + 8 * g;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const bf16x8 aq = *reinterpret_cast<const bf16x8*>(sQ + arow + 16 * kk);
+        sacc = mfma32(aq, kreg[kk], sacc);
+      }
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const bf16x8 ao = *reinterpret_cast<const bf16x8*>(sdO + arow + 16 * kk);
+        pacc = mfma32(ao, vreg[kk], pacc);
+      }
+      // register r <-> row t0 + 32 tb + 16 (r/8) + 8 g + r%8, column jmine
+      float p[16], ds[16];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int tl = 32 * tb + 16 * h + 8 * g;
+        const float4 l0 = *reinterpret_cast<const float4*>(&sL[tl]);
+        const float4 l1 = *reinterpret_cast<const float4*>(&sL[tl + 4]);
+        const float4 d0 = *reinterpret_cast<const float4*>(&sDv[tl]);
+        const float4 d1 = *reinterpret_cast<const float4*>(&sDv[tl + 4]);
+        const float lv[8] = {l0.x, l0.y, l0.z, l0.w, l1.x, l1.y, l1.z, l1.w};
+        const float dv[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int r = 8 * h + u;
+          float pv = fast_exp2(fmaf(sacc[r], c, -lv[u]));
+          if (need_mask) {
+            const int t = t0 + tl + u;
+            const bool vis = (jmine < S) && (!causal || jmine <= t + off);
+            pv = vis ? pv : 0.f;
+          }
+          p[r] = pv;
+          ds[r] = pv * (pacc[r] - dv[u]);
+        }
+      }
+      pP[tb][0] = __builtin_bit_cast(bf16x8, pack8(&p[0]));
+      pP[tb][1] = __builtin_bit_cast(bf16x8, pack8(&p[8]));
+      pdS[tb][0] = __builtin_bit_cast(bf16x8, pack8(&ds[0]));
+      pdS[tb][1] = __builtin_bit_cast(bf16x8, pack8(&ds[8]));
+      // dS through LDS, row = query row, column = slot (for the dQ contraction over slots)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int tl = 32 * tb + 16 * (r >> 3) + 8 * g + (r & 7);
+        sdS[tl * SSTR + 32 * wave + li] = (bf16)ds[r];
+      }
+    }
+    // ---- dVf^T += dO^T P ; dKf^T += Q^T dS     (k-step = 16 query rows)
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      const int arow = (32 * db + li) * TSTR + 8 * g;
+#pragma unroll
+      for (int ks = 0; ks < 2 * TB; ++ks) {
+        const bf16x8 ao = *reinterpret_cast<const bf16x8*>(sdOT + arow + 16 * ks);
+        dVacc[db] = mfma32(ao, pP[ks >> 1][ks & 1], dVacc[db]);
+        const bf16x8 aq = *reinterpret_cast<const bf16x8*>(sQT + arow + 16 * ks);
+        dKacc[db] = mfma32(aq, pdS[ks >> 1][ks & 1], dKacc[db]);
+      }
+    }
+    __syncthreads();  // every wave's slice of dS is in LDS
+    // ---- dQ^T[d, t] = sum_j Kf^T[d, j] dS[t, j]; work unit = (32-wide d slice, 32-row block)
+    for (int unit = wave; unit < DB * TB; unit += 4) {
+      const int sl = unit % DB, tb = unit / DB;
+      f32x16 qacc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) qacc[r] = 0.f;
+      const int arow = (32 * sl + li) * SSTR + 8 * g;
+      const int brow = (32 * tb + li) * SSTR + 8 * g;
+#pragma unroll
+      for (int ks = 0; ks < BCB / 16; ++ks) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(sKT + arow + 16 * ks);
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(sdS + brow + 16 * ks);
+        qacc = mfma32(a, b, qacc);
+      }
+      const int t = t0 + 32 * tb + li;
+      if (t < Tq) {
+        float* dst = dQacc + qbase + (long)t * D + 32 * sl + 4 * g;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) atomicAdd(dst + 8 * (r >> 2) + (r & 3), qacc[r]);
+      }
+    }
+  }
+
+  // ---- epilogue: this lane owns slot jmine and the d indices 32 db + 8 q4 + 4 g + (0..3)
+  if (jmine < S) {
+    const float g3[3] = {Gb[jmine * 3 + 0], Gb[jmine * 3 + 1], Gb[jmine * 3 + 2]};
+    const bf16* Kp[3] = {K0, K1, K2};
+    const bf16* Vp[3] = {V0, V1, V2};
+    bf16* dKp[3] = {dK0, dK1, dK2};
+    bf16* dVp[3] = {dV0, dV1, dV2};
+    const int len[3] = {len0, len1, len2};
+    float dlam[3] = {0.f, 0.f, 0.f};
+    const long rowoff = kvbase + (long)jmine * D;
+#pragma unroll
+    for (int l = 0; l < 3; ++l) {
+      const bool present = jmine < len[l];
+      const float gk = present ? g3[l] * tau : 0.f;  // dKf carries the factor tau
+      const float gv = present ? g3[l] : 0.f;
+      float acc = 0.f;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const long o = rowoff + 32 * db + 8 * q4 + 4 * g;
+          const float k0 = dKacc[db][4 * q4 + 0], k1 = dKacc[db][4 * q4 + 1];
+          const float k2 = dKacc[db][4 * q4 + 2], k3 = dKacc[db][4 * q4 + 3];
+          const float v0 = dVacc[db][4 * q4 + 0], v1 = dVacc[db][4 * q4 + 1];
+          const float v2 = dVacc[db][4 * q4 + 2], v3 = dVacc[db][4 * q4 + 3];
+          if (dKp[l]) {
+            uint2 w;
+            w.x = pack_bf16x2(gk * k0, gk * k1);
+            w.y = pack_bf16x2(gk * k2, gk * k3);
+            *reinterpret_cast<uint2*>(dKp[l] + o) = w;
+          }
+          if (dVp[l]) {
+            uint2 w;
+            w.x = pack_bf16x2(gv * v0, gv * v1);
+            w.y = pack_bf16x2(gv * v2, gv * v3);
+            *reinterpret_cast<uint2*>(dVp[l] + o) = w;
+          }
+          if (present) {
+            const uint2 kw = *reinterpret_cast<const uint2*>(Kp[l] + o);
+            const uint2 vw = *reinterpret_cast<const uint2*>(Vp[l] + o);
+            acc = fmaf(k0, bf16lo(kw.x), acc); acc = fmaf(k1, bf16hi(kw.x), acc);
+            acc = fmaf(k2, bf16lo(kw.y), acc); acc = fmaf(k3, bf16hi(kw.y), acc);
+            float av = 0.f;
+            av = fmaf(v0, bf16lo(vw.x), av); av = fmaf(v1, bf16hi(vw.x), av);
+            av = fmaf(v2, bf16lo(vw.y), av); av = fmaf(v3, bf16hi(vw.y), av);
+            dlam[l] = dlam[l] + av;
+          }
+        }
+      dlam[l] = fmaf(acc, tau, dlam[l]);
+    }
+    // the other half of the row's d indices lives in lane^32 (same slot: both are < S)
+#pragma unroll
+    for (int l = 0; l < 3; ++l) dlam[l] += xor32(dlam[l]);
+    const int t = jmine - off;
+    if (dgate && t >= 0 && g == 0) {
+      const float mean = g3[0] * dlam[0] + g3[1] * dlam[1] + g3[2] * dlam[2];
+      float* out = dgate + (bh * (long)Tq + t) * 3;
+#pragma unroll
+      for (int l = 0; l < 3; ++l) out[l] = g3[l] * (dlam[l] - mean);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ finish
+// dQ = tau * acc + dg W_r^T, and per-workgroup partial sums of Q^T dg and dg in a fixed order.
+template <int D>
+__global__ __launch_bounds__(256) void bwd_finish_kernel(
+    const float* __restrict__ dQacc, const float* __restrict__ dgate, const bf16* __restrict__ Q,
+    const float* __restrict__ W_r, bf16* __restrict__ dQ, float* __restrict__ dWpart, long rows,
+    float tau) {
+  constexpr int CPR = D / 8, RL = 256 / CPR;  // row lanes per workgroup
+  __shared__ float sW[D * 3];
+  __shared__ float sPart[RL][D * 3 + 3];
+  const int tid = threadIdx.x, cc = tid % CPR, rl = tid / CPR;
+  const bool route = (W_r != nullptr);
+  if (route)
+    for (int i = tid; i < D * 3; i += 256) sW[i] = W_r[i];
+  __syncthreads();
+  float wacc[8][3];
+  float bacc[3] = {0.f, 0.f, 0.f};
+#pragma unroll
+  for (int e = 0; e < 8; ++e) wacc[e][0] = wacc[e][1] = wacc[e][2] = 0.f;
+  const long row0 = (long)blockIdx.x * FIN_ROWS;
+  for (int i = rl; i < FIN_ROWS; i += RL) {
+    const long row = row0 + i;
+    if (row >= rows) break;
+    const float4 a0 = *reinterpret_cast<const float4*>(dQacc + row * D + cc * 8);
+    const float4 a1 = *reinterpret_cast<const float4*>(dQacc + row * D + cc * 8 + 4);
+    float o[8] = {a0.x * tau, a0.y * tau, a0.z * tau, a0.w * tau,
+                  a1.x * tau, a1.y * tau, a1.z * tau, a1.w * tau};
+    if (route) {
+      const float dg0 = dgate[row * 3 + 0], dg1 = dgate[row * 3 + 1], dg2 = dgate[row * 3 + 2];
+      float q[8];
+      unpack8(*reinterpret_cast<const uint4*>(Q + row * D + cc * 8), q);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int k = cc * 8 + e;
+        o[e] += dg0 * sW[k * 3 + 0] + dg1 * sW[k * 3 + 1] + dg2 * sW[k * 3 + 2];
+        wacc[e][0] = fmaf(q[e], dg0, wacc[e][0]);
+        wacc[e][1] = fmaf(q[e], dg1, wacc[e][1]);
+        wacc[e][2] = fmaf(q[e], dg2, wacc[e][2]);
+      }
+      if (cc == 0) { bacc[0] += dg0; bacc[1] += dg1; bacc[2] += dg2; }
+    }
+    *reinterpret_cast<uint4*>(dQ + row * D + cc * 8) = pack8(o);
+  }
+  if (!route) return;
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+#pragma unroll
+    for (int l = 0; l < 3; ++l) sPart[rl][(cc * 8 + e) * 3 + l] = wacc[e][l];
+  if (cc == 0)
+#pragma unroll
+    for (int l = 0; l < 3; ++l) sPart[rl][D * 3 + l] = bacc[l];
+  __syncthreads();
+  for (int i = tid; i < D * 3 + 3; i += 256) {
+    float s = 0.f;
+    for (int r = 0; r < RL; ++r) s += sPart[r][i];  // fixed order
+    dWpart[(long)blockIdx.x * (D * 3 + 3) + i] = s;
+  }
+}
+
+// Fixed-order sum of the per-workgroup partials (two levels so that the chain stays short).
+__global__ __launch_bounds__(256) void bwd_reduce_kernel(const float* __restrict__ dWpart,
+                                                         int nparts, int width,
+                                                         float* __restrict__ dW_r,
+                                                         float* __restrict__ db_r) {
+  __shared__ float sred[256];
+  const int i = blockIdx.x;  // one output element per workgroup
+  float s = 0.f;
+  for (int p = threadIdx.x; p < nparts; p += 256) s += dWpart[(long)p * width + i];
+  sred[threadIdx.x] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t = 0.f;
+    for (int k = 0; k < 256; ++k) t += sred[k];
+    if (i < width - 3) {
+      if (dW_r) dW_r[i] = t;
+    } else if (db_r) {
+      db_r[i - (width - 3)] = t;
+    }
+  }
+}
+
+size_t a256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+struct BwdWs {
+  size_t off_dq, off_d, off_dg, off_part, total;
+  int nparts;
+};
+BwdWs carve(int BH, int Tq, int d) {
+  BwdWs w;
+  const size_t rows = (size_t)BH * Tq;
+  w.nparts = (int)((rows + FIN_ROWS - 1) / FIN_ROWS);
+  w.off_dq = 0;
+  w.off_d = a256(rows * d * sizeof(float));
+  w.off_dg = w.off_d + a256(rows * sizeof(float));
+  w.off_part = w.off_dg + a256(rows * 3 * sizeof(float));
+  w.total = w.off_part + a256((size_t)w.nparts * (d * 3 + 3) * sizeof(float));
+  return w;
+}
+
+template <int D>
+hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
+  constexpr int TB = 2;
+  using L = BwdSmem<D, TB>;
+  const BwdWs w = carve(a.BH, a.Tq, D);
+  unsigned char* ws = static_cast<unsigned char*>(a.workspace);
+  float* dQacc = reinterpret_cast<float*>(ws + w.off_dq);
+  float* Dvec = reinterpret_cast<float*>(ws + w.off_d);
+  float* dgate = a.W_r ? reinterpret_cast<float*>(ws + w.off_dg) : nullptr;
+  float* dWpart = reinterpret_cast<float*>(ws + w.off_part);
+  const long rows = (long)a.BH * a.Tq;
+  constexpr int CPR = D / 8;
+
+  hipLaunchKernelGGL((bwd_prep_kernel<D>), dim3((unsigned)((rows * CPR + 255) / 256)), dim3(256),
+                     0, st, (const bf16*)a.dO, (const bf16*)a.O, Dvec, dQacc, rows);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+
+  // a level without memory borrows another level's buffer and has length 0 (never used)
+  const void* Kp[3];
+  const void* Vp[3];
+  const void* anyK = a.K[0] ? a.K[0] : (a.K[1] ? a.K[1] : a.K[2]);
+  const void* anyV = a.V[0] ? a.V[0] : (a.V[1] ? a.V[1] : a.V[2]);
+  if (!anyK || !anyV) return hipErrorInvalidValue;
+  for (int l = 0; l < 3; ++l) {
+    Kp[l] = a.K[l] ? a.K[l] : anyK;
+    Vp[l] = a.V[l] ? a.V[l] : anyV;
+  }
+  const int n_kvtiles = (a.S + BCB - 1) / BCB;
+  const size_t smem = (size_t)L::TOTAL * sizeof(bf16) + 2 * L::BR * sizeof(float);
+  static bool attr_set = false;
+  if (!attr_set) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_main_kernel<D, TB>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((bwd_main_kernel<D, TB>), dim3((unsigned)((long)n_kvtiles * a.BH)),
+                     dim3(256), smem, st, (const bf16*)a.dO, (const bf16*)a.Q,
+                     (const bf16*)Kp[0], (const bf16*)Kp[1], (const bf16*)Kp[2],
+                     (const bf16*)Vp[0], (const bf16*)Vp[1], (const bf16*)Vp[2], a.G, a.LSE, Dvec,
+                     (bf16*)a.dK[0], (bf16*)a.dK[1], (bf16*)a.dK[2], (bf16*)a.dV[0],
+                     (bf16*)a.dV[1], (bf16*)a.dV[2], dQacc, dgate, a.Tq, a.S, a.len[0], a.len[1],
+                     a.len[2], a.causal, a.scale * kLog2e, a.scale, n_kvtiles);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+
+  hipLaunchKernelGGL((bwd_finish_kernel<D>), dim3(w.nparts), dim3(256), 0, st, dQacc, dgate,
+                     (const bf16*)a.Q, a.W_r, (bf16*)a.dQ, dWpart, rows, a.scale);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (a.W_r && (a.dW_r || a.db_r)) {
+    hipLaunchKernelGGL(bwd_reduce_kernel, dim3(D * 3 + 3), dim3(256), 0, st, dWpart, w.nparts,
+                       D * 3 + 3, a.dW_r, a.db_r);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+}  // namespace
+
+size_t bwd_workspace_bytes(int BH, int Tq, int S, int d) {
+  (void)S;
+  return carve(BH, Tq, d).total;
+}
+
+hipError_t launch_bwd_bf16(const BwdArgs& a, hipStream_t st) {
+  if (a.BH == 0 || a.Tq == 0) return hipSuccess;
+  return a.d == 128 ? launch_bwd_t<128>(a, st) : launch_bwd_t<64>(a, st);
+}
+
+}  // namespace mka

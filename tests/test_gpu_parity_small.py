@@ -195,3 +195,74 @@ def test_decode_equals_last_prefill_row(mka):
     assert torch.equal(idxd, idx[:, :, -1])
     assert float((Od.float() - O[:, :, last].float()).abs().max()) <= BF16_ATOL
     assert float((LSEd - LSE[:, :, -1]).abs().max()) <= 1e-2
+
+
+# ------------------------------------------------------------------ backward, bf16 MFMA
+def _check_bwd(mka, oracle, inp, S, len3, causal, Gprev=None, use_router=True):
+    W = inp["W_r"] if use_router else None
+    if use_router:
+        O, LSE, G, idx = mka.mka_fused_attn_fwd(
+            inp["Q"], inp["K"], inp["V"], W, inp["b_r"],
+            G=None if Gprev is None else Gprev.clone(), len3=len3, causal=causal,
+            scale=inp["scale"])
+        Gref, _ = oracle.route(inp["Q"].cpu(), W.cpu(), inp["b_r"].cpu(), S=S,
+                               G_prev=None if Gprev is None else Gprev.cpu())
+    else:
+        G = Gprev.clone()
+        O, LSE, _, _ = mka.mka_fused_attn_fwd(inp["Q"], inp["K"], inp["V"], None, None, G=G,
+                                              len3=len3, causal=causal, scale=inp["scale"])
+        Gref = Gprev.cpu()
+    g = mka.mka_fused_attn_bwd(inp["dO"], inp["Q"], inp["K"], inp["V"], G, O, LSE, W, len3=len3,
+                               causal=causal, scale=inp["scale"])
+    torch.cuda.synchronize()
+    ref = oracle.bwd(inp["dO"].cpu(), inp["Q"].cpu(), cpu_list(inp["K"]), cpu_list(inp["V"]), Gref,
+                     inp["W_r"].cpu() if use_router else None, len3=len3, causal=causal,
+                     tau=inp["scale"])
+    errs = {"dQ": max_abs(g["dQ"], ref["dQ"])}
+    for l in range(3):
+        errs[f"dK{l}"] = max_abs(g["dK"][l], ref["dK"][l])
+        errs[f"dV{l}"] = max_abs(g["dV"][l], ref["dV"][l])
+    for k, v in errs.items():
+        assert v <= BF16_ATOL, (k, v, errs)
+    if use_router:
+        # the router gradients sum B*H*Tq rows, so their size grows with the problem: they are
+        # judged on the scale-normalised error max|x-r| / max|r|
+        assert rel_err(g["dW_r"], ref["dW_r"]) <= BF16_ATOL, rel_err(g["dW_r"], ref["dW_r"])
+        assert max_abs(g["db_r"], ref["db_r"]) <= BF16_ATOL * max(1.0, float(np.abs(ref["dW_r"]).max()))
+    return errs
+
+
+@pytest.mark.parametrize("d", [128, 64])
+@pytest.mark.parametrize("Tq,S,causal,len3", [
+    (200, 200, True, None),          # two kv tiles, ragged tails
+    (130, 333, True, None),          # cache prefix: only the last 130 slots have router grads
+    (150, 190, False, None),         # non-causal
+    (257, 257, True, [257, 100, 0]),  # absent levels: zero gradients there
+    (1, 1, True, None), (64, 128, True, None)])
+def test_bwd_bf16_shapes(mka, oracle, d, Tq, S, causal, len3):
+    announce(f"bwd bf16 d={d} Tq={Tq} S={S} causal={causal} len={len3}")
+    inp = si.prefill_inputs(2, 2, Tq, S, d, dtype="bf16", seed=13, device="cuda", with_dO=True)
+    inp["W_r"] = inp["W_r"] * 10.0
+    Gprev = torch.softmax(torch.randn((2, 2, S, 3), device="cuda"), -1)
+    _check_bwd(mka, oracle, inp, S, len3, causal, Gprev=Gprev)
+
+
+def test_bwd_bf16_given_gates_no_router(mka, oracle):
+    announce("bwd bf16 given gates")
+    inp = si.prefill_inputs(1, 2, 140, 140, 128, dtype="bf16", seed=14, device="cuda", with_dO=True)
+    G = torch.softmax(torch.randn((1, 2, 140, 3), device="cuda") * 2, -1)
+    _check_bwd(mka, oracle, inp, 140, None, True, Gprev=G, use_router=False)
+
+
+def test_bwd_absent_level_gradients_are_zero(mka):
+    announce("bwd absent level zero grads")
+    inp = si.prefill_inputs(1, 1, 100, 100, 128, dtype="bf16", seed=15, device="cuda", with_dO=True)
+    len3 = [100, 37, 0]
+    O, LSE, G, _ = mka.mka_fused_attn_fwd(inp["Q"], inp["K"], inp["V"], inp["W_r"], inp["b_r"],
+                                          len3=len3, causal=True, scale=inp["scale"])
+    g = mka.mka_fused_attn_bwd(inp["dO"], inp["Q"], inp["K"], inp["V"], G, O, LSE, inp["W_r"],
+                               len3=len3, causal=True, scale=inp["scale"])
+    torch.cuda.synchronize()
+    assert torch.all(g["dK"][2] == 0) and torch.all(g["dV"][2] == 0)
+    assert torch.all(g["dK"][1][:, :, 37:] == 0) and torch.all(g["dV"][1][:, :, 37:] == 0)
+    assert float(g["dV"][1][:, :, :37].abs().max()) > 0
