@@ -132,12 +132,12 @@ __global__ __launch_bounds__(256, 1) void bwd_main_kernel(
         const float g0 = Gb[jc * 3 + 0], g1 = Gb[jc * 3 + 1], g2 = Gb[jc * 3 + 2];
         Raw3 rk, rv;
         if (full) {
-          rk = load_raw3<true>(K0, K1, K2, 0, eoff, true, true, true);
-          rv = load_raw3<true>(V0, V1, V2, 0, eoff, true, true, true);
+          rk = load_raw3<true, long>(K0, K1, K2, 0, eoff, true, true, true);
+          rv = load_raw3<true, long>(V0, V1, V2, 0, eoff, true, true, true);
         } else {
-          rk = load_raw3<false>(K0, K1, K2, kvbase + cc * 8, eoff, in && j < len0, in && j < len1,
+          rk = load_raw3<false, long>(K0, K1, K2, kvbase + cc * 8, eoff, in && j < len0, in && j < len1,
                                 in && j < len2);
-          rv = load_raw3<false>(V0, V1, V2, kvbase + cc * 8, eoff, in && j < len0, in && j < len1,
+          rv = load_raw3<false, long>(V0, V1, V2, kvbase + cc * 8, eoff, in && j < len0, in && j < len1,
                                 in && j < len2);
         }
         fuse8(rk, g0, g1, g2, kf[u]);
@@ -290,25 +290,29 @@ __global__ __launch_bounds__(256, 1) void bwd_main_kernel(
       }
     }
     __syncthreads();  // every wave's slice of dS is in LDS
-    // ---- dQ^T[d, t] = sum_j Kf^T[d, j] dS[t, j]; work unit = (32-wide d slice, 32-row block)
+    // ---- dQ[t, d] = sum_j dS[t, j] Kf[j, d]; work unit = (32-row block, 32-wide d slice).
+    // A = dS rows, B = Kf^T rows: in the accumulator a lane then owns ONE column d and the 32
+    // lanes of a half-wave cover 32 consecutive d, so each atomic instruction adds two full
+    // 128-byte lines.
     for (int unit = wave; unit < DB * TB; unit += 4) {
       const int sl = unit % DB, tb = unit / DB;
       f32x16 qacc;
 #pragma unroll
       for (int r = 0; r < 16; ++r) qacc[r] = 0.f;
-      const int arow = (32 * sl + li) * SSTR + 8 * g;
-      const int brow = (32 * tb + li) * SSTR + 8 * g;
+      const int arow = (32 * tb + li) * SSTR + 8 * g;
+      const int brow = (32 * sl + li) * SSTR + 8 * g;
 #pragma unroll
       for (int ks = 0; ks < BCB / 16; ++ks) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(sKT + arow + 16 * ks);
-        const bf16x8 b = *reinterpret_cast<const bf16x8*>(sdS + brow + 16 * ks);
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(sdS + arow + 16 * ks);
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(sKT + brow + 16 * ks);
         qacc = mfma32(a, b, qacc);
       }
-      const int t = t0 + 32 * tb + li;
-      if (t < Tq) {
-        float* dst = dQacc + qbase + (long)t * D + 32 * sl + 4 * g;
+      // register r <-> row t0 + 32 tb + 8 (r/4) + 4 g + r%4, column 32 sl + li
+      float* dst = dQacc + qbase + 32 * sl + li;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) atomicAdd(dst + 8 * (r >> 2) + (r & 3), qacc[r]);
+      for (int r = 0; r < 16; ++r) {
+        const int t = t0 + 32 * tb + 8 * (r >> 2) + 4 * g + (r & 3);
+        if (t < Tq) atomicAdd(dst + (long)t * D, qacc[r]);
       }
     }
   }

@@ -15,10 +15,12 @@ struct Raw3 {
   uint4 a, b, c;
 };
 
-// base: element offset of row 0 of this (b,h) block; eoff: element offset of the wanted chunk.
-template <bool FULL>
+// base_chunk: element offset of the same chunk in row 0 of this (b,h) block; eoff: element
+// offset of the wanted chunk.  OFF is int when the pointers already address the (b,h) block
+// (lets the compiler use scalar-base + 32-bit-offset addressing), long otherwise.
+template <bool FULL, typename OFF>
 __device__ __forceinline__ Raw3 load_raw3(const bf16* __restrict__ P0, const bf16* __restrict__ P1,
-                                          const bf16* __restrict__ P2, long base_chunk, long eoff,
+                                          const bf16* __restrict__ P2, OFF base_chunk, OFF eoff,
                                           bool p0, bool p1, bool p2) {
   Raw3 r;
   if constexpr (FULL) {

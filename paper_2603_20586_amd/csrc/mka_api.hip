@@ -21,6 +21,7 @@ mka_status check_shape(const mka_shape* s, bool* empty) {
     if (s->len[l] < 0 || s->len[l] > s->S) return MKA_ERR_SHAPE;
   if (s->d != 64 && s->d != 128) return MKA_ERR_UNSUPPORTED;
   if (!(s->scale >= 0.f) || isinf(s->scale)) return MKA_ERR_UNSUPPORTED;
+  if ((long long)s->S * s->d >= 0x7fffffffLL) return MKA_ERR_UNSUPPORTED;  // 32-bit offsets per head
   const long long bh = (long long)s->B * s->H;
   if (bh > 0x7fffffffLL / 4096) return MKA_ERR_UNSUPPORTED;  // grid index must fit
   if (bh * (long long)((s->Tq + 31) / 32) > 0x7fffffffLL) return MKA_ERR_UNSUPPORTED;
