@@ -18,8 +18,11 @@
 //     so the rescale by exp2(c (m_old - m_new)) is a per-lane scalar.
 // Vf is written to LDS transposed ([d][slot]) with the slot order permuted (bits 2 and 3 of the
 // slot index swapped) so that the 8 P values a lane packs for one PV k-step pair with ONE
-// 16-byte read, and with the 16-byte blocks of a row XOR-swizzled by (d/8)%8 so that the
-// transposed 8-byte writes spread over all banks.
+// 16-byte read, and with its ROWS permuted: head-dim index d = 8 cc + e lives in LDS row
+// e * (D/8) + cc.  A 16-lane read group then touches 16 consecutive rows (conflict-free with
+// the 144-byte row stride) and a 16-lane write group (8 chunks x 2 halves) covers every bank
+// once.  The O^T accumulator rows follow the same permutation; the epilogue undoes it while
+// transposing O through LDS for coalesced 16-byte stores.
 #include "fuse_tile.h"
 #include "mka_dev.h"
 #include "mka_internal.h"
@@ -89,7 +92,9 @@ __device__ __forceinline__ void fuse_store_k(const HalfRaw& x, bf16* sK, int tg)
 }
 
 // V work item = (4 consecutive slots, one 16-byte chunk).  Thread bits: [2:0] chunk low bits,
-// [3] slot-group bit 1, [4] slot-group bit 0, [6:5] slot-group bits 3:2, [7] chunk bit 3.
+// [3] slot-group bit 1 (selects the 8-byte half of a 16-byte column block), [4] slot-group bit 0,
+// [6:5] slot-group bits 3:2, [7] chunk bit 3.  A 16-lane LDS write group is then 8 chunks x 2
+// halves, which (with the row permutation of the Vf^T tile) covers every bank exactly once.
 template <int D>
 __device__ __forceinline__ void v_item(int tg, int& sg, int& cc, bool& active) {
   constexpr int CPR = D / 8;
@@ -133,11 +138,11 @@ __device__ __forceinline__ void fuse_store_v(const HalfRaw& x, bf16* sVT, int tg
   const int blk = col >> 3, half = (col >> 2) & 1;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    const int d = cc * 8 + e;
+    const int prow = e * (D / 8) + cc;  // LDS row of head-dim index d = 8 cc + e
     uint2 w;
     w.x = pack_bf16x2(vf[0][e], vf[1][e]);
     w.y = pack_bf16x2(vf[2][e], vf[3][e]);
-    *reinterpret_cast<uint2*>(&sVT[d * VSTR + 8 * (blk ^ (cc & 7)) + 4 * half]) = w;
+    *reinterpret_cast<uint2*>(&sVT[prow * VSTR + 8 * blk + 4 * half]) = w;
   }
 }
 
@@ -199,11 +204,9 @@ __device__ __forceinline__ void compute_tile(const bf16* sK, const bf16* sVT,
     // O^T += Vf^T P^T: k-step ks covers columns 16 ks .. 16 ks + 15 of the Vf^T tile
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
-      const int d = 32 * db + li;
-      const bf16* vrow = &sVT[d * VSTR];
-      const int sw = (d >> 3) & 7;
-      const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(vrow + 8 * ((4 * sb + 0 + g) ^ sw));
-      const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(vrow + 8 * ((4 * sb + 2 + g) ^ sw));
+      const bf16* vrow = &sVT[(32 * db + li) * VSTR];  // LDS rows: see the row permutation
+      const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(vrow + 8 * (4 * sb + 0 + g));
+      const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(vrow + 8 * (4 * sb + 2 + g));
       oacc[db] = mfma32(a0, p0, oacc[db]);
       oacc[db] = mfma32(a1, p1, oacc[db]);
     }
@@ -216,7 +219,7 @@ __global__ __launch_bounds__(FW_NW * 64, 1) void fwd_bf16_kernel(
     const bf16* __restrict__ K2, const bf16* __restrict__ V0, const bf16* __restrict__ V1,
     const bf16* __restrict__ V2, const float* __restrict__ G, bf16* __restrict__ O,
     float* __restrict__ LSE, int Tq, int S, int len0, int len1, int len2, int causal, float c,
-    float tau, int n_qtiles) {
+    float tau, int n_qtiles, int BH) {
   using L = FwdSmem<D>;
   constexpr int BR = FW_NW * 32, BC = FW_BC;
   constexpr int KK = D / 16, DB = D / 32;
@@ -226,9 +229,14 @@ __global__ __launch_bounds__(FW_NW * 64, 1) void fwd_bf16_kernel(
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
   const bool grpV = wave >= 4;  // waves 4-7 fuse the V half, waves 0-3 the K half
   const int tg = tid & (FW_NG - 1);
-  // heavy (late) query tiles first so that the causal tail is short
-  const int qt = n_qtiles - 1 - (int)(blockIdx.x % n_qtiles);
-  const long bh = blockIdx.x / n_qtiles;
+  // Workgroups are handed to the 8 XCDs round-robin by block index.  All query tiles of one
+  // (batch, head) are given to ONE XCD (block index = 8 * slot + xcd), so that the workgroups
+  // that stream the same K/V tiles share that XCD's L2; within a head the heavy (late) query
+  // tiles go first so that the causal tail is short.
+  const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3);
+  const int qt = n_qtiles - 1 - slot % n_qtiles;
+  const long bh = (long)(slot / n_qtiles) * 8 + xcd;
+  if (bh >= BH) return;  // the head count need not be a multiple of 8
   const int off = S - Tq;
   const int tw0 = qt * BR + wave * 32;  // first row of this wave
   const int tq = tw0 + li;              // this lane's row
@@ -314,21 +322,31 @@ __global__ __launch_bounds__(FW_NW * 64, 1) void fwd_bf16_kernel(
     __syncthreads();  // tile jt+1 is complete in LDS; buffer jt&1 may be overwritten next
   }
 
-  // ---- epilogue: normalise and store this lane's row
+  // ---- epilogue: normalise, transpose O^T through LDS (tile buffers are free after the last
+  // barrier), store rows with coalesced 16-byte writes
   lsum += xor32(lsum);
-  if (tq < Tq) {
+  {
+    constexpr int OSTR = D + 8, CPR = D / 8;
+    bf16* sO = smem + wave * (32 * OSTR);
     const float inv = 1.f / lsum;
-    bf16* orow = O + (bh * (long)Tq + tq) * D;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        uint2 w;
-        w.x = pack_bf16x2(oacc[db][4 * q4 + 0] * inv, oacc[db][4 * q4 + 1] * inv);
-        w.y = pack_bf16x2(oacc[db][4 * q4 + 2] * inv, oacc[db][4 * q4 + 3] * inv);
-        *reinterpret_cast<uint2*>(orow + 32 * db + 8 * q4 + 4 * g) = w;
+      for (int r = 0; r < 16; ++r) {
+        const int prow = 32 * db + 8 * (r >> 2) + 4 * g + (r & 3);  // accumulator row
+        const int d = 8 * (prow % CPR) + prow / CPR;               // head-dim index it holds
+        sO[li * OSTR + d] = (bf16)(oacc[db][r] * inv);
       }
-    if (LSE && g == 0) LSE[bh * (long)Tq + tq] = m * tau + __logf(lsum);
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 32 * CPR / 64; ++i) {
+      const int item = lane + 64 * i;
+      const int row = item / CPR, ch = item % CPR;
+      const uint4 v = *reinterpret_cast<const uint4*>(&sO[row * OSTR + ch * 8]);
+      if (tw0 + row < Tq)
+        *reinterpret_cast<uint4*>(O + (bh * (long)Tq + tw0 + row) * D + ch * 8) = v;
+    }
+    if (LSE && g == 0 && tq < Tq) LSE[bh * (long)Tq + tq] = m * tau + __logf(lsum);
   }
 }
 
@@ -337,7 +355,7 @@ static hipError_t launch_fwd_t(const FwdArgs& a, const void* const Kp[3], const 
                                hipStream_t st) {
   constexpr int BR = FW_NW * 32;
   const int n_qtiles = (a.Tq + BR - 1) / BR;
-  const long nblocks = (long)n_qtiles * a.BH;
+  const long nblocks = (long)n_qtiles * ((a.BH + 7) / 8) * 8;
   const size_t smem = (size_t)FwdSmem<D>::TOTAL * sizeof(bf16);
   static bool attr_set = false;
   if (!attr_set) {
@@ -350,7 +368,7 @@ static hipError_t launch_fwd_t(const FwdArgs& a, const void* const Kp[3], const 
                      (const bf16*)a.Q, (const bf16*)Kp[0], (const bf16*)Kp[1], (const bf16*)Kp[2],
                      (const bf16*)Vp[0], (const bf16*)Vp[1], (const bf16*)Vp[2], a.G, (bf16*)a.O,
                      a.LSE, a.Tq, a.S, a.len[0], a.len[1], a.len[2], a.causal,
-                     a.scale * kLog2e, a.scale, n_qtiles);
+                     a.scale * kLog2e, a.scale, n_qtiles, a.BH);
   return hipGetLastError();
 }
 
