@@ -82,6 +82,19 @@ struct BwdSmem {
   static constexpr int TOTAL = OFF_KT + D * SSTR;  // bf16 elements
 };
 
+// Work item of the Q / dO tile load = (4 consecutive rows, one 16-byte chunk).  Thread bits:
+// [2:0] chunk low bits, [3] row-group bit 0 (selects the 8-byte half of a 16-byte column block
+// of the transposed tiles), [6:4] row-group bits 3:1, [7] chunk bit 3.  With the transposed
+// tiles' ROWS permuted (head-dim index d = 8 cc + e lives in LDS row e * (D/8) + cc) a 16-lane
+// write group covers every bank once and a 16-lane MFMA read group touches 16 consecutive rows.
+template <int D>
+__device__ __forceinline__ void qtile_item(int tid, int& rg, int& cc, bool& active) {
+  rg = ((tid >> 3) & 1) | (((tid >> 4) & 7) << 1);
+  cc = (tid & 7) | ((tid >> 7) << 3);
+  active = cc < D / 8;
+  if (!active) cc = 0;
+}
+
 template <int D, int TB>
 __global__ __launch_bounds__(256, 1) void bwd_main_kernel(
     const bf16* __restrict__ dO, const bf16* __restrict__ Q, const bf16* __restrict__ K0,
@@ -90,10 +103,11 @@ __global__ __launch_bounds__(256, 1) void bwd_main_kernel(
     const float* __restrict__ LSE, const float* __restrict__ Dvec, bf16* __restrict__ dK0,
     bf16* __restrict__ dK1, bf16* __restrict__ dK2, bf16* __restrict__ dV0, bf16* __restrict__ dV1,
     bf16* __restrict__ dV2, float* __restrict__ dQacc, float* __restrict__ dgate, int Tq, int S,
-    int len0, int len1, int len2, int causal, float c, float tau, int n_kvtiles) {
+    int len0, int len1, int len2, int causal, float c, float tau, int n_kvtiles, int BH) {
   using L = BwdSmem<D, TB>;
   constexpr int BR = L::BR, RSTR = L::RSTR, TSTR = L::TSTR, SSTR = L::SSTR;
   constexpr int CPR = D / 8, KK = D / 16, DB = D / 32, NT = 256;
+  static_assert(TB == 2, "the tile-load mapping assumes 64-row query tiles");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16* smem = reinterpret_cast<bf16*>(smem_raw);
   bf16* sQ = smem + L::OFF_Q;
@@ -106,13 +120,22 @@ __global__ __launch_bounds__(256, 1) void bwd_main_kernel(
   float* sDv = sL + BR;                                   // [BR] D
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
-  const int jt = (int)(blockIdx.x % n_kvtiles);  // tile 0 sees every row: heaviest first
-  const long bh = blockIdx.x / n_kvtiles;
+  // all KV tiles of one (batch, head) run on ONE XCD (block index = 8 * slot + xcd): they share
+  // the head's Q / dO tiles and dQ accumulator rows in that XCD's L2.  Tile 0 sees every query
+  // row, so ascending tile order is heaviest first.
+  const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3);
+  const int jt = slot % n_kvtiles;
+  const long bh = (long)(slot / n_kvtiles) * 8 + xcd;
+  if (bh >= BH) return;
   const int J0 = jt * BCB;
   const int off = S - Tq;
   const long kvbase = bh * (long)S * D;
   const long qbase = bh * (long)Tq * D;
   const float* Gb = G + bh * (long)S * 3;
+  const bf16* Qb = Q + qbase;
+  const bf16* dOb = dO + qbase;
+  const float* LSEb = LSE + bh * (long)Tq;
+  const float* Dvb = Dvec + bh * (long)Tq;
   const int jmine = J0 + 32 * wave + li;  // the slot this lane owns in S / dP / dVf^T / dKf^T
 
   // ---- set-up: fuse the 128 slots once.  Item = (4 consecutive slots, 16-byte chunk).
@@ -135,10 +158,10 @@ __global__ __launch_bounds__(256, 1) void bwd_main_kernel(
           rk = load_raw3<true, long>(K0, K1, K2, 0, eoff, true, true, true);
           rv = load_raw3<true, long>(V0, V1, V2, 0, eoff, true, true, true);
         } else {
-          rk = load_raw3<false, long>(K0, K1, K2, kvbase + cc * 8, eoff, in && j < len0, in && j < len1,
-                                in && j < len2);
-          rv = load_raw3<false, long>(V0, V1, V2, kvbase + cc * 8, eoff, in && j < len0, in && j < len1,
-                                in && j < len2);
+          rk = load_raw3<false, long>(K0, K1, K2, kvbase + cc * 8, eoff, in && j < len0,
+                                      in && j < len1, in && j < len2);
+          rv = load_raw3<false, long>(V0, V1, V2, kvbase + cc * 8, eoff, in && j < len0,
+                                      in && j < len1, in && j < len2);
         }
         fuse8(rk, g0, g1, g2, kf[u]);
         fuse8(rv, g0, g1, g2, vf[u]);
@@ -172,28 +195,44 @@ __global__ __launch_bounds__(256, 1) void bwd_main_kernel(
   int t_first = 0;
   if (causal && J0 - off > 0) t_first = J0 - off;
   const int n_qt = (Tq + BR - 1) / BR;
+  const int qt0 = t_first / BR;
 
-  for (int qt = t_first / BR; qt < n_qt; ++qt) {
+  // ---- register prefetch of the next Q / dO tile (and its LSE, D rows)
+  int rg, ccq;
+  bool qactive;
+  qtile_item<D>(tid, rg, ccq, qactive);
+  uint4 q4[4], o4[4];
+  float lse_n = 0.f, dv_n = 0.f;
+  auto prefetch = [&](int qt) {
+    const int t0 = qt * BR;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int t = t0 + rg * 4 + u;
+      q4[u] = make_uint4(0, 0, 0, 0);
+      o4[u] = q4[u];
+      if (t < Tq) {
+        q4[u] = *reinterpret_cast<const uint4*>(Qb + t * D + ccq * 8);
+        o4[u] = *reinterpret_cast<const uint4*>(dOb + t * D + ccq * 8);
+      }
+    }
+    if (tid < BR) {
+      const int t = t0 + tid;
+      // rows past the end get LSE = +inf, hence P = 0
+      lse_n = t < Tq ? LSEb[t] * kLog2e : INFINITY;
+      dv_n = t < Tq ? Dvb[t] : 0.f;
+    }
+  };
+  prefetch(qt0);
+
+  for (int qt = qt0; qt < n_qt; ++qt) {
     const int t0 = qt * BR;
     __syncthreads();  // previous tile fully consumed (also guards the set-up buffers)
-    // ---- load the Q and dO tiles: item = (4 consecutive rows, chunk); row-major + transposed
-    for (int it = tid; it < (BR / 4) * CPR; it += NT) {
-      const int rg = it / CPR, cc = it % CPR;
-      uint4 q4[4], o4[4];
+    // ---- registers -> LDS: row-major tiles and transposed tiles
+    if (qactive) {
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        const int t = t0 + rg * 4 + u;
-        q4[u] = make_uint4(0, 0, 0, 0);
-        o4[u] = q4[u];
-        if (t < Tq) {
-          q4[u] = *reinterpret_cast<const uint4*>(Q + qbase + (long)t * D + cc * 8);
-          o4[u] = *reinterpret_cast<const uint4*>(dO + qbase + (long)t * D + cc * 8);
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        *reinterpret_cast<uint4*>(&sQ[(rg * 4 + u) * RSTR + cc * 8]) = q4[u];
-        *reinterpret_cast<uint4*>(&sdO[(rg * 4 + u) * RSTR + cc * 8]) = o4[u];
+        *reinterpret_cast<uint4*>(&sQ[(rg * 4 + u) * RSTR + ccq * 8]) = q4[u];
+        *reinterpret_cast<uint4*>(&sdO[(rg * 4 + u) * RSTR + ccq * 8]) = o4[u];
       }
       // transpose 4 rows x 8 columns of 16-bit values: column e of the 4 rows -> one 8-byte word
       const uint32_t* qw[4] = {&q4[0].x, &q4[1].x, &q4[2].x, &q4[3].x};
@@ -209,18 +248,18 @@ __global__ __launch_bounds__(256, 1) void bwd_main_kernel(
         lo2.y = (ow[2][e2] & 0xffffu) | (ow[3][e2] << 16);
         hi2.x = (ow[0][e2] >> 16) | (ow[1][e2] & 0xffff0000u);
         hi2.y = (ow[2][e2] >> 16) | (ow[3][e2] & 0xffff0000u);
-        *reinterpret_cast<uint2*>(&sQT[(cc * 8 + 2 * e2) * TSTR + rg * 4]) = lo;
-        *reinterpret_cast<uint2*>(&sQT[(cc * 8 + 2 * e2 + 1) * TSTR + rg * 4]) = hi;
-        *reinterpret_cast<uint2*>(&sdOT[(cc * 8 + 2 * e2) * TSTR + rg * 4]) = lo2;
-        *reinterpret_cast<uint2*>(&sdOT[(cc * 8 + 2 * e2 + 1) * TSTR + rg * 4]) = hi2;
+        const int p0 = (2 * e2) * CPR + ccq, p1 = (2 * e2 + 1) * CPR + ccq;  // permuted rows
+        *reinterpret_cast<uint2*>(&sQT[p0 * TSTR + rg * 4]) = lo;
+        *reinterpret_cast<uint2*>(&sQT[p1 * TSTR + rg * 4]) = hi;
+        *reinterpret_cast<uint2*>(&sdOT[p0 * TSTR + rg * 4]) = lo2;
+        *reinterpret_cast<uint2*>(&sdOT[p1 * TSTR + rg * 4]) = hi2;
       }
     }
     if (tid < BR) {
-      const int t = t0 + tid;
-      // rows past the end get LSE = +inf, hence P = 0
-      sL[tid] = t < Tq ? LSE[bh * (long)Tq + t] * kLog2e : INFINITY;
-      sDv[tid] = t < Tq ? Dvec[bh * (long)Tq + t] : 0.f;
+      sL[tid] = lse_n;
+      sDv[tid] = dv_n;
     }
+    if (qt + 1 < n_qt) prefetch(qt + 1);  // lands while this tile is being processed
     __syncthreads();
 
     // ---- S, dP, P, dS per block of 32 rows
@@ -277,7 +316,8 @@ __global__ __launch_bounds__(256, 1) void bwd_main_kernel(
         sdS[tl * SSTR + 32 * wave + li] = (bf16)ds[r];
       }
     }
-    // ---- dVf^T += dO^T P ; dKf^T += Q^T dS     (k-step = 16 query rows)
+    // ---- dVf^T += dO^T P ; dKf^T += Q^T dS     (k-step = 16 query rows; accumulator row m of
+    // block db is LDS row 32 db + m, i.e. head-dim index 8 (p % CPR) + p / CPR)
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
       const int arow = (32 * db + li) * TSTR + 8 * g;
@@ -317,65 +357,84 @@ __global__ __launch_bounds__(256, 1) void bwd_main_kernel(
     }
   }
 
-  // ---- epilogue: this lane owns slot jmine and the d indices 32 db + 8 q4 + 4 g + (0..3)
-  if (jmine < S) {
-    const float g3[3] = {Gb[jmine * 3 + 0], Gb[jmine * 3 + 1], Gb[jmine * 3 + 2]};
-    const bf16* Kp[3] = {K0, K1, K2};
-    const bf16* Vp[3] = {V0, V1, V2};
-    bf16* dKp[3] = {dK0, dK1, dK2};
-    bf16* dVp[3] = {dV0, dV1, dV2};
-    const int len[3] = {len0, len1, len2};
-    float dlam[3] = {0.f, 0.f, 0.f};
-    const long rowoff = kvbase + (long)jmine * D;
+  // ---- epilogue.  dKf^T then dVf^T go through LDS as f32 [slot][d] so that the un-fusion
+  // (dK_l = G_l tau dKf, dV_l = G_l dVf) is written with coalesced 16-byte stores and the gate
+  // gradients dlam_l = dKf.K_l + dVf.V_l are formed from coalesced 16-byte loads.
+  // Item = (slot, 16-byte chunk): 16 consecutive lanes hold one slot's row.
+  constexpr int ESTR = D + 4;                 // f32 per staged row
+  constexpr int NITEM = BCB * CPR / NT;       // items per thread
+  static_assert((size_t)BCB * ESTR * 4 <= (size_t)L::TOTAL * 2, "staging tile must fit");
+  float* sE = reinterpret_cast<float*>(smem_raw);
+  const int ecc = tid % CPR, erow0 = tid / CPR;
+  constexpr int ERS = NT / CPR;               // slots covered per pass
+  float dlam[NITEM][3];
 #pragma unroll
-    for (int l = 0; l < 3; ++l) {
-      const bool present = jmine < len[l];
-      const float gk = present ? g3[l] * tau : 0.f;  // dKf carries the factor tau
-      const float gv = present ? g3[l] : 0.f;
-      float acc = 0.f;
+  for (int i = 0; i < NITEM; ++i) dlam[i][0] = dlam[i][1] = dlam[i][2] = 0.f;
+  const bf16* Kp[3] = {K0, K1, K2};
+  const bf16* Vp[3] = {V0, V1, V2};
+  bf16* dKp[3] = {dK0, dK1, dK2};
+  bf16* dVp[3] = {dV0, dV1, dV2};
+  const int len[3] = {len0, len1, len2};
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+  for (int pass = 0; pass < 2; ++pass) {
+    __syncthreads();  // LDS free (main loop done / previous pass consumed)
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          const long o = rowoff + 32 * db + 8 * q4 + 4 * g;
-          const float k0 = dKacc[db][4 * q4 + 0], k1 = dKacc[db][4 * q4 + 1];
-          const float k2 = dKacc[db][4 * q4 + 2], k3 = dKacc[db][4 * q4 + 3];
-          const float v0 = dVacc[db][4 * q4 + 0], v1 = dVacc[db][4 * q4 + 1];
-          const float v2 = dVacc[db][4 * q4 + 2], v3 = dVacc[db][4 * q4 + 3];
-          if (dKp[l]) {
-            uint2 w;
-            w.x = pack_bf16x2(gk * k0, gk * k1);
-            w.y = pack_bf16x2(gk * k2, gk * k3);
-            *reinterpret_cast<uint2*>(dKp[l] + o) = w;
-          }
-          if (dVp[l]) {
-            uint2 w;
-            w.x = pack_bf16x2(gv * v0, gv * v1);
-            w.y = pack_bf16x2(gv * v2, gv * v3);
-            *reinterpret_cast<uint2*>(dVp[l] + o) = w;
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int prow = 32 * db + 8 * (r >> 2) + 4 * g + (r & 3);
+        const int d = 8 * (prow % CPR) + prow / CPR;
+        sE[(32 * wave + li) * ESTR + d] = pass == 0 ? dKacc[db][r] * tau : dVacc[db][r];
+      }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NITEM; ++i) {
+      const int sl = erow0 + ERS * i;
+      const int j = J0 + sl;
+      if (j < S) {
+        const float4 a0 = *reinterpret_cast<const float4*>(&sE[sl * ESTR + ecc * 8]);
+        const float4 a1 = *reinterpret_cast<const float4*>(&sE[sl * ESTR + ecc * 8 + 4]);
+        const float v[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+        const long o = kvbase + (long)j * D + ecc * 8;
+#pragma unroll
+        for (int l = 0; l < 3; ++l) {
+          const bool present = j < len[l];
+          const float gl = present ? Gb[j * 3 + l] : 0.f;
+          bf16* dst = pass == 0 ? dKp[l] : dVp[l];
+          if (dst) {
+            float o8[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o8[e] = gl * v[e];
+            *reinterpret_cast<uint4*>(dst + o) = pack8(o8);
           }
           if (present) {
-            const uint2 kw = *reinterpret_cast<const uint2*>(Kp[l] + o);
-            const uint2 vw = *reinterpret_cast<const uint2*>(Vp[l] + o);
-            acc = fmaf(k0, bf16lo(kw.x), acc); acc = fmaf(k1, bf16hi(kw.x), acc);
-            acc = fmaf(k2, bf16lo(kw.y), acc); acc = fmaf(k3, bf16hi(kw.y), acc);
-            float av = 0.f;
-            av = fmaf(v0, bf16lo(vw.x), av); av = fmaf(v1, bf16hi(vw.x), av);
-            av = fmaf(v2, bf16lo(vw.y), av); av = fmaf(v3, bf16hi(vw.y), av);
-            dlam[l] = dlam[l] + av;
+            float x[8];
+            unpack8(*reinterpret_cast<const uint4*>((pass == 0 ? Kp[l] : Vp[l]) + o), x);
+            float acc = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc = fmaf(v[e], x[e], acc);
+            dlam[i][l] += acc;
           }
         }
-      dlam[l] = fmaf(acc, tau, dlam[l]);
+      }
     }
-    // the other half of the row's d indices lives in lane^32 (same slot: both are < S)
+  }
+  if (dgate) {
 #pragma unroll
-    for (int l = 0; l < 3; ++l) dlam[l] += xor32(dlam[l]);
-    const int t = jmine - off;
-    if (dgate && t >= 0 && g == 0) {
-      const float mean = g3[0] * dlam[0] + g3[1] * dlam[1] + g3[2] * dlam[2];
-      float* out = dgate + (bh * (long)Tq + t) * 3;
-#pragma unroll
-      for (int l = 0; l < 3; ++l) out[l] = g3[l] * (dlam[l] - mean);
+    for (int i = 0; i < NITEM; ++i) {
+      float d0 = group_sum<CPR>(dlam[i][0]);
+      float d1 = group_sum<CPR>(dlam[i][1]);
+      float d2 = group_sum<CPR>(dlam[i][2]);
+      const int j = J0 + erow0 + ERS * i;
+      const int t = j - off;
+      if (j < S && t >= 0 && ecc == 0) {
+        const float g0 = Gb[j * 3 + 0], g1 = Gb[j * 3 + 1], g2 = Gb[j * 3 + 2];
+        const float mean = g0 * d0 + g1 * d1 + g2 * d2;
+        float* out = dgate + (bh * (long)Tq + t) * 3;
+        out[0] = g0 * (d0 - mean);
+        out[1] = g1 * (d1 - mean);
+        out[2] = g2 * (d2 - mean);
+      }
     }
   }
 }
@@ -516,13 +575,13 @@ hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((bwd_main_kernel<D, TB>), dim3((unsigned)((long)n_kvtiles * a.BH)),
+  hipLaunchKernelGGL((bwd_main_kernel<D, TB>), dim3((unsigned)((long)n_kvtiles * ((a.BH + 7) / 8) * 8)),
                      dim3(256), smem, st, (const bf16*)a.dO, (const bf16*)a.Q,
                      (const bf16*)Kp[0], (const bf16*)Kp[1], (const bf16*)Kp[2],
                      (const bf16*)Vp[0], (const bf16*)Vp[1], (const bf16*)Vp[2], a.G, a.LSE, Dvec,
                      (bf16*)a.dK[0], (bf16*)a.dK[1], (bf16*)a.dK[2], (bf16*)a.dV[0],
                      (bf16*)a.dV[1], (bf16*)a.dV[2], dQacc, dgate, a.Tq, a.S, a.len[0], a.len[1],
-                     a.len[2], a.causal, a.scale * kLog2e, a.scale, n_kvtiles);
+                     a.len[2], a.causal, a.scale * kLog2e, a.scale, n_kvtiles, a.BH);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
 
