@@ -44,6 +44,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--quick", action="store_true", help="skip the larger workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB elementwise copy (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not provided "
@@ -260,6 +262,27 @@ def main():
                                   "unit": "GB/s", "frac": gbps / PEAK_HBM_GBPS, "traffic": None}
         del cc, ws4
         torch.cuda.empty_cache()
+
+    if args.calibrate_copy:
+        # plain copy of known size: reads 1 GiB, writes 1 GiB (scales rocprofv3 FETCH/WRITE_SIZE)
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+
+    # HBM traffic per launch measured offline with rocprofv3 --pmc (see profiles/); filled in
+    # from the committed summary when present
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
+            traffic = json.load(f)
+        for key, r in rooflines.items():
+            t = traffic.get(key)
+            if t is not None:
+                r["traffic"] = t
+    except (OSError, ValueError):
+        pass
 
     # dominant kernel of the step = the one with the largest share of the step time
     dom = "C2_bwd" if ms_bwd >= ms_fwd else "C2_fwd"

@@ -12,13 +12,15 @@
 //
 // Launch sequence:
 //   prep    D = rowsum(dO*O); zero the f32 dQ accumulator
-//   main    one workgroup owns 128 KV slots (4 waves x 32 slots): fuses its Kf/Vf ONCE, keeps
-//           them as MFMA B operands in registers, then walks over the query tiles that can see
-//           it.  Per tile: S = Q Kf^T and dP = dO Vf^T (A = Q / dO rows from LDS), P and dS in
-//           registers, dVf^T += dO^T P and dKf^T += Q^T dS (A = transposed tiles from LDS, B = P /
-//           dS straight from the accumulator layout), dS goes through LDS once so that
-//           dQ^T = Kf^T dS^T can contract over all 128 slots; dQ is accumulated in f32 with
-//           atomics.  Epilogue: un-fusion, dlam, dg.
+//   main    one workgroup owns 128 KV slots (four blocks of 32): fuses its Kf/Vf ONCE, keeps them
+//           as MFMA B operands in registers, then walks over the 32-row query tiles that can
+//           see it.  Two waves per slot block: one computes S -> P -> dVf^T += dO^T P, the other
+//           S, dP -> dS -> dKf^T += Q^T dS (A operands = Q / dO rows and transposed tiles from
+//           LDS, B = P / dS straight from the accumulator layout).  dS goes through LDS once so
+//           that dQ = dS Kf can contract over all 128 slots; dQ is accumulated in f32 with
+//           atomics.  Query tiles are double-buffered in LDS and the loop has one barrier per
+//           tile: staging of tile i+1, the MFMA work of tile i and the dQ contraction of tile
+//           i-1 share a phase.  Epilogue: un-fusion, dlam, dg through LDS, coalesced accesses.
 //   finish  dQ = tau*acc + dg W_r^T -> bf16; per-workgroup partial sums of Q^T dg and dg
 //   reduce  fixed-order sum of the partials -> dW_r, db_r   (deterministic)
 #include "fuse_tile.h"
@@ -62,18 +64,20 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(const bf16* __restrict__ 
 }
 
 // ------------------------------------------------------------------ main
-template <int D, int TB>
+template <int D>
 struct BwdSmem {
-  static constexpr int BR = 32 * TB;
+  static constexpr int BR = 32;          // query rows per tile
   static constexpr int RSTR = D + 8;     // row-major Q / dO tiles
   static constexpr int TSTR = BR + 8;    // transposed Q / dO tiles
   static constexpr int SSTR = BCB + 8;   // dS tile, Kf^T
+  static constexpr int QBUF = BR * RSTR, TBUF = D * TSTR, SBUF = BR * SSTR;
+  // every per-tile array is double-buffered (index b = 0, 1)
   static constexpr int OFF_Q = 0;
-  static constexpr int OFF_DO = OFF_Q + BR * RSTR;
-  static constexpr int OFF_QT = OFF_DO + BR * RSTR;
-  static constexpr int OFF_DOT = OFF_QT + D * TSTR;
-  static constexpr int OFF_DS = OFF_DOT + D * TSTR;
-  static constexpr int LOOP_END = OFF_DS + BR * SSTR;
+  static constexpr int OFF_DO = OFF_Q + 2 * QBUF;
+  static constexpr int OFF_QT = OFF_DO + 2 * QBUF;
+  static constexpr int OFF_DOT = OFF_QT + 2 * TBUF;
+  static constexpr int OFF_DS = OFF_DOT + 2 * TBUF;
+  static constexpr int LOOP_END = OFF_DS + 2 * SBUF;
   // set-up only: row-major Kf and Vf of the workgroup's 128 slots
   static constexpr int OFF_KROW = 0;
   static constexpr int OFF_VROW = BCB * RSTR;
@@ -82,21 +86,22 @@ struct BwdSmem {
   static constexpr int TOTAL = OFF_KT + D * SSTR;  // bf16 elements
 };
 
-// Work item of the Q / dO tile load = (4 consecutive rows, one 16-byte chunk).  Thread bits:
-// [2:0] chunk low bits, [3] row-group bit 0 (selects the 8-byte half of a 16-byte column block
-// of the transposed tiles), [6:4] row-group bits 3:1, [7] chunk bit 3.  With the transposed
-// tiles' ROWS permuted (head-dim index d = 8 cc + e lives in LDS row e * (D/8) + cc) a 16-lane
-// write group covers every bank once and a 16-lane MFMA read group touches 16 consecutive rows.
+// Work item of the Q / dO tile load = (4 consecutive rows, one 16-byte chunk), 128 items per
+// tensor.  Thread bits: [2:0] chunk low bits, [3] row-group bit 0 (selects the 8-byte half of a
+// 16-byte column block of the transposed tiles), [5:4] row-group bits 2:1, [6] chunk bit 3.
+// With the transposed tiles' ROWS permuted (head-dim index d = 8 cc + e lives in LDS row
+// e * (D/8) + cc) a 16-lane write group covers every bank once and a 16-lane MFMA read group
+// touches 16 consecutive rows.
 template <int D>
-__device__ __forceinline__ void qtile_item(int tid, int& rg, int& cc, bool& active) {
-  rg = ((tid >> 3) & 1) | (((tid >> 4) & 7) << 1);
-  cc = (tid & 7) | ((tid >> 7) << 3);
+__device__ __forceinline__ void qtile_item(int t, int& rg, int& cc, bool& active) {
+  rg = ((t >> 3) & 1) | (((t >> 4) & 3) << 1);
+  cc = (t & 7) | (((t >> 6) & 1) << 3);
   active = cc < D / 8;
   if (!active) cc = 0;
 }
 
-template <int D, int TB>
-__global__ __launch_bounds__(256, 1) void bwd_main_kernel(
+template <int D>
+__global__ __launch_bounds__(512, 1) void bwd_main_kernel(
     const bf16* __restrict__ dO, const bf16* __restrict__ Q, const bf16* __restrict__ K0,
     const bf16* __restrict__ K1, const bf16* __restrict__ K2, const bf16* __restrict__ V0,
     const bf16* __restrict__ V1, const bf16* __restrict__ V2, const float* __restrict__ G,
@@ -104,22 +109,23 @@ __global__ __launch_bounds__(256, 1) void bwd_main_kernel(
     bf16* __restrict__ dK1, bf16* __restrict__ dK2, bf16* __restrict__ dV0, bf16* __restrict__ dV1,
     bf16* __restrict__ dV2, float* __restrict__ dQacc, float* __restrict__ dgate, int Tq, int S,
     int len0, int len1, int len2, int causal, float c, float tau, int n_kvtiles, int BH) {
-  using L = BwdSmem<D, TB>;
+  using L = BwdSmem<D>;
   constexpr int BR = L::BR, RSTR = L::RSTR, TSTR = L::TSTR, SSTR = L::SSTR;
-  constexpr int CPR = D / 8, KK = D / 16, DB = D / 32, NT = 256;
-  static_assert(TB == 2, "the tile-load mapping assumes 64-row query tiles");
+  constexpr int CPR = D / 8, KK = D / 16, DB = D / 32, NT = 512;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16* smem = reinterpret_cast<bf16*>(smem_raw);
-  bf16* sQ = smem + L::OFF_Q;
-  bf16* sdO = smem + L::OFF_DO;
-  bf16* sQT = smem + L::OFF_QT;
-  bf16* sdOT = smem + L::OFF_DOT;
-  bf16* sdS = smem + L::OFF_DS;
   bf16* sKT = smem + L::OFF_KT;
-  float* sL = reinterpret_cast<float*>(smem + L::TOTAL);  // [BR] LSE in log2 units
-  float* sDv = sL + BR;                                   // [BR] D
+  float* sL = reinterpret_cast<float*>(smem + L::TOTAL);  // [2][BR] LSE in log2 units
+  float* sDv = sL + 2 * BR;                               // [2][BR] D
 
+  // 8 waves = 2 per SIMD.  Waves 0-3 (role V) and 4-7 (role K) each own the same four blocks
+  // of 32 slots: role V computes S -> P -> dVf^T, role K computes S, dP -> dS -> dKf^T and
+  // publishes dS.  S is computed by both; in exchange a wave holds one accumulator set instead
+  // of two, which is what lets two waves share a SIMD and hide each other's LDS / MFMA latency.
+  // Role V waves also stage the next query tile and run the dQ contraction of the previous one.
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
+  const bool roleK = wave >= 4;
+  const int sw = wave & 3;  // slot block of this wave
   // all KV tiles of one (batch, head) run on ONE XCD (block index = 8 * slot + xcd): they share
   // the head's Q / dO tiles and dQ accumulator rows in that XCD's L2.  Tile 0 sees every query
   // row, so ascending tile order is heaviest first.
@@ -132,11 +138,9 @@ __global__ __launch_bounds__(256, 1) void bwd_main_kernel(
   const long kvbase = bh * (long)S * D;
   const long qbase = bh * (long)Tq * D;
   const float* Gb = G + bh * (long)S * 3;
-  const bf16* Qb = Q + qbase;
-  const bf16* dOb = dO + qbase;
   const float* LSEb = LSE + bh * (long)Tq;
   const float* Dvb = Dvec + bh * (long)Tq;
-  const int jmine = J0 + 32 * wave + li;  // the slot this lane owns in S / dP / dVf^T / dKf^T
+  const int jmine = J0 + 32 * sw + li;  // the slot this lane owns in S / dP / dVf^T / dKf^T
 
   // ---- set-up: fuse the 128 slots once.  Item = (4 consecutive slots, 16-byte chunk).
   {
@@ -178,18 +182,19 @@ __global__ __launch_bounds__(256, 1) void bwd_main_kernel(
     }
   }
   __syncthreads();
+  // B operands held in registers for the whole kernel: Kf rows (both roles), Vf rows (role K)
   bf16x8 kreg[KK], vreg[KK];
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) {
-    kreg[kk] = *reinterpret_cast<const bf16x8*>(smem + L::OFF_KROW + (32 * wave + li) * RSTR + 16 * kk + 8 * g);
-    vreg[kk] = *reinterpret_cast<const bf16x8*>(smem + L::OFF_VROW + (32 * wave + li) * RSTR + 16 * kk + 8 * g);
+    kreg[kk] = *reinterpret_cast<const bf16x8*>(smem + L::OFF_KROW + (32 * sw + li) * RSTR + 16 * kk + 8 * g);
+    vreg[kk] = *reinterpret_cast<const bf16x8*>(smem + (roleK ? L::OFF_VROW : L::OFF_KROW) + (32 * sw + li) * RSTR + 16 * kk + 8 * g);
   }
-
-  f32x16 dVacc[DB], dKacc[DB];
+  // one accumulator set per wave: dVf^T (role V) or dKf^T (role K)
+  f32x16 acc[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { dVacc[db][r] = 0.f; dKacc[db][r] = 0.f; }
+    for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
 
   // first query tile that can see slot J0 (rows t with t + off >= J0)
   int t_first = 0;
@@ -197,22 +202,23 @@ __global__ __launch_bounds__(256, 1) void bwd_main_kernel(
   const int n_qt = (Tq + BR - 1) / BR;
   const int qt0 = t_first / BR;
 
-  // ---- register prefetch of the next Q / dO tile (and its LSE, D rows)
+  // ---- staging of query tiles: threads 0-127 carry Q, threads 128-255 carry dO (role V waves)
   int rg, ccq;
   bool qactive;
-  qtile_item<D>(tid, rg, ccq, qactive);
-  uint4 q4[4], o4[4];
+  qtile_item<D>(tid & 127, rg, ccq, qactive);
+  qactive = qactive && tid < 256;
+  const bool stage_dO = tid >= 128;
+  const bf16* Xb = (stage_dO ? dO : Q) + qbase;
+  uint4 x4[4];
   float lse_n = 0.f, dv_n = 0.f;
-  auto prefetch = [&](int qt) {
+  auto prefetch = [&](int qt) {  // global -> registers
     const int t0 = qt * BR;
+    if (qactive) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int t = t0 + rg * 4 + u;
-      q4[u] = make_uint4(0, 0, 0, 0);
-      o4[u] = q4[u];
-      if (t < Tq) {
-        q4[u] = *reinterpret_cast<const uint4*>(Qb + t * D + ccq * 8);
-        o4[u] = *reinterpret_cast<const uint4*>(dOb + t * D + ccq * 8);
+      for (int u = 0; u < 4; ++u) {
+        const int t = t0 + rg * 4 + u;
+        x4[u] = make_uint4(0, 0, 0, 0);
+        if (t < Tq) x4[u] = *reinterpret_cast<const uint4*>(Xb + t * D + ccq * 8);
       }
     }
     if (tid < BR) {
@@ -222,145 +228,151 @@ __global__ __launch_bounds__(256, 1) void bwd_main_kernel(
       dv_n = t < Tq ? Dvb[t] : 0.f;
     }
   };
-  prefetch(qt0);
-
-  for (int qt = qt0; qt < n_qt; ++qt) {
-    const int t0 = qt * BR;
-    __syncthreads();  // previous tile fully consumed (also guards the set-up buffers)
-    // ---- registers -> LDS: row-major tiles and transposed tiles
+  auto stage = [&](int buf) {  // registers -> LDS: row-major tile and transposed tile
     if (qactive) {
+      bf16* sX = smem + (stage_dO ? L::OFF_DO : L::OFF_Q) + buf * L::QBUF;
+      bf16* sXT = smem + (stage_dO ? L::OFF_DOT : L::OFF_QT) + buf * L::TBUF;
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        *reinterpret_cast<uint4*>(&sQ[(rg * 4 + u) * RSTR + ccq * 8]) = q4[u];
-        *reinterpret_cast<uint4*>(&sdO[(rg * 4 + u) * RSTR + ccq * 8]) = o4[u];
-      }
-      // transpose 4 rows x 8 columns of 16-bit values: column e of the 4 rows -> one 8-byte word
-      const uint32_t* qw[4] = {&q4[0].x, &q4[1].x, &q4[2].x, &q4[3].x};
-      const uint32_t* ow[4] = {&o4[0].x, &o4[1].x, &o4[2].x, &o4[3].x};
+      for (int u = 0; u < 4; ++u)
+        *reinterpret_cast<uint4*>(&sX[(rg * 4 + u) * RSTR + ccq * 8]) = x4[u];
+      const uint32_t* xw[4] = {&x4[0].x, &x4[1].x, &x4[2].x, &x4[3].x};
 #pragma unroll
       for (int e2 = 0; e2 < 4; ++e2) {  // dword e2 holds columns 2*e2, 2*e2+1
-        uint2 lo, hi, lo2, hi2;
-        lo.x = (qw[0][e2] & 0xffffu) | (qw[1][e2] << 16);
-        lo.y = (qw[2][e2] & 0xffffu) | (qw[3][e2] << 16);
-        hi.x = (qw[0][e2] >> 16) | (qw[1][e2] & 0xffff0000u);
-        hi.y = (qw[2][e2] >> 16) | (qw[3][e2] & 0xffff0000u);
-        lo2.x = (ow[0][e2] & 0xffffu) | (ow[1][e2] << 16);
-        lo2.y = (ow[2][e2] & 0xffffu) | (ow[3][e2] << 16);
-        hi2.x = (ow[0][e2] >> 16) | (ow[1][e2] & 0xffff0000u);
-        hi2.y = (ow[2][e2] >> 16) | (ow[3][e2] & 0xffff0000u);
+        uint2 lo, hi;
+        lo.x = (xw[0][e2] & 0xffffu) | (xw[1][e2] << 16);
+        lo.y = (xw[2][e2] & 0xffffu) | (xw[3][e2] << 16);
+        hi.x = (xw[0][e2] >> 16) | (xw[1][e2] & 0xffff0000u);
+        hi.y = (xw[2][e2] >> 16) | (xw[3][e2] & 0xffff0000u);
         const int p0 = (2 * e2) * CPR + ccq, p1 = (2 * e2 + 1) * CPR + ccq;  // permuted rows
-        *reinterpret_cast<uint2*>(&sQT[p0 * TSTR + rg * 4]) = lo;
-        *reinterpret_cast<uint2*>(&sQT[p1 * TSTR + rg * 4]) = hi;
-        *reinterpret_cast<uint2*>(&sdOT[p0 * TSTR + rg * 4]) = lo2;
-        *reinterpret_cast<uint2*>(&sdOT[p1 * TSTR + rg * 4]) = hi2;
+        *reinterpret_cast<uint2*>(&sXT[p0 * TSTR + rg * 4]) = lo;
+        *reinterpret_cast<uint2*>(&sXT[p1 * TSTR + rg * 4]) = hi;
       }
     }
     if (tid < BR) {
-      sL[tid] = lse_n;
-      sDv[tid] = dv_n;
+      sL[buf * BR + tid] = lse_n;
+      sDv[buf * BR + tid] = dv_n;
     }
-    if (qt + 1 < n_qt) prefetch(qt + 1);  // lands while this tile is being processed
-    __syncthreads();
-
-    // ---- S, dP, P, dS per block of 32 rows
-    bf16x8 pP[TB][2], pdS[TB][2];
-    const bool need_mask = (J0 + BCB > S) || (causal && (J0 + BCB - 1 > t0 + off));
-#pragma unroll
-    for (int tb = 0; tb < TB; ++tb) {
-      f32x16 sacc, pacc;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
-      const int arow = (32 * tb + swap23(li)) * RSTR + 8 * g;
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const bf16x8 aq = *reinterpret_cast<const bf16x8*>(sQ + arow + 16 * kk);
-        sacc = mfma32(aq, kreg[kk], sacc);
-      }
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const bf16x8 ao = *reinterpret_cast<const bf16x8*>(sdO + arow + 16 * kk);
-        pacc = mfma32(ao, vreg[kk], pacc);
-      }
-      // register r <-> row t0 + 32 tb + 16 (r/8) + 8 g + r%8, column jmine
-      float p[16], ds[16];
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int tl = 32 * tb + 16 * h + 8 * g;
-        const float4 l0 = *reinterpret_cast<const float4*>(&sL[tl]);
-        const float4 l1 = *reinterpret_cast<const float4*>(&sL[tl + 4]);
-        const float4 d0 = *reinterpret_cast<const float4*>(&sDv[tl]);
-        const float4 d1 = *reinterpret_cast<const float4*>(&sDv[tl + 4]);
-        const float lv[8] = {l0.x, l0.y, l0.z, l0.w, l1.x, l1.y, l1.z, l1.w};
-        const float dv[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int r = 8 * h + u;
-          float pv = fast_exp2(fmaf(sacc[r], c, -lv[u]));
-          if (need_mask) {
-            const int t = t0 + tl + u;
-            const bool vis = (jmine < S) && (!causal || jmine <= t + off);
-            pv = vis ? pv : 0.f;
-          }
-          p[r] = pv;
-          ds[r] = pv * (pacc[r] - dv[u]);
-        }
-      }
-      pP[tb][0] = __builtin_bit_cast(bf16x8, pack8(&p[0]));
-      pP[tb][1] = __builtin_bit_cast(bf16x8, pack8(&p[8]));
-      pdS[tb][0] = __builtin_bit_cast(bf16x8, pack8(&ds[0]));
-      pdS[tb][1] = __builtin_bit_cast(bf16x8, pack8(&ds[8]));
-      // dS through LDS, row = query row, column = slot (for the dQ contraction over slots)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int tl = 32 * tb + 16 * (r >> 3) + 8 * g + (r & 7);
-        sdS[tl * SSTR + 32 * wave + li] = (bf16)ds[r];
-      }
-    }
-    // ---- dVf^T += dO^T P ; dKf^T += Q^T dS     (k-step = 16 query rows; accumulator row m of
-    // block db is LDS row 32 db + m, i.e. head-dim index 8 (p % CPR) + p / CPR)
-#pragma unroll
-    for (int db = 0; db < DB; ++db) {
-      const int arow = (32 * db + li) * TSTR + 8 * g;
-#pragma unroll
-      for (int ks = 0; ks < 2 * TB; ++ks) {
-        const bf16x8 ao = *reinterpret_cast<const bf16x8*>(sdOT + arow + 16 * ks);
-        dVacc[db] = mfma32(ao, pP[ks >> 1][ks & 1], dVacc[db]);
-        const bf16x8 aq = *reinterpret_cast<const bf16x8*>(sQT + arow + 16 * ks);
-        dKacc[db] = mfma32(aq, pdS[ks >> 1][ks & 1], dKacc[db]);
-      }
-    }
-    __syncthreads();  // every wave's slice of dS is in LDS
-    // ---- dQ[t, d] = sum_j dS[t, j] Kf[j, d]; work unit = (32-row block, 32-wide d slice).
-    // A = dS rows, B = Kf^T rows: in the accumulator a lane then owns ONE column d and the 32
-    // lanes of a half-wave cover 32 consecutive d, so each atomic instruction adds two full
-    // 128-byte lines.
-    for (int unit = wave; unit < DB * TB; unit += 4) {
-      const int sl = unit % DB, tb = unit / DB;
+  };
+  // dQ[t, d] = sum_j dS[t, j] Kf[j, d] for one finished tile; work unit = 32-wide d slice, one per
+  // role V wave.  A = dS rows, B = Kf^T rows: in the accumulator a lane owns ONE column d and the
+  // 32 lanes of a half-wave cover 32 consecutive d, so each atomic adds two full 128-byte lines.
+  auto dq_tile = [&](int t0, int buf) {
+    if (wave < DB) {
+      const bf16* sdS = smem + L::OFF_DS + buf * L::SBUF;
       f32x16 qacc;
 #pragma unroll
       for (int r = 0; r < 16; ++r) qacc[r] = 0.f;
-      const int arow = (32 * tb + li) * SSTR + 8 * g;
-      const int brow = (32 * sl + li) * SSTR + 8 * g;
+      const int arow = li * SSTR + 8 * g;
+      const int brow = (32 * wave + li) * SSTR + 8 * g;
 #pragma unroll
       for (int ks = 0; ks < BCB / 16; ++ks) {
         const bf16x8 a = *reinterpret_cast<const bf16x8*>(sdS + arow + 16 * ks);
         const bf16x8 b = *reinterpret_cast<const bf16x8*>(sKT + brow + 16 * ks);
         qacc = mfma32(a, b, qacc);
       }
-      // register r <-> row t0 + 32 tb + 8 (r/4) + 4 g + r%4, column 32 sl + li
-      float* dst = dQacc + qbase + 32 * sl + li;
+      // register r <-> row t0 + 8 (r/4) + 4 g + r%4, column 32 wave + li
+      float* dst = dQacc + qbase + 32 * wave + li;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int t = t0 + 32 * tb + 8 * (r >> 2) + 4 * g + (r & 3);
+        const int t = t0 + 8 * (r >> 2) + 4 * g + (r & 3);
         if (t < Tq) atomicAdd(dst + (long)t * D, qacc[r]);
       }
     }
-  }
+  };
 
-  // ---- epilogue.  dKf^T then dVf^T go through LDS as f32 [slot][d] so that the un-fusion
-  // (dK_l = G_l tau dKf, dV_l = G_l dVf) is written with coalesced 16-byte stores and the gate
-  // gradients dlam_l = dKf.K_l + dVf.V_l are formed from coalesced 16-byte loads.
-  // Item = (slot, 16-byte chunk): 16 consecutive lanes hold one slot's row.
+  // prologue: first tile into buffer 0 (the set-up buffers are dead after this barrier)
+  prefetch(qt0);
+  __syncthreads();
+  stage(0);
+  if (qt0 + 1 < n_qt) prefetch(qt0 + 1);
+  __syncthreads();
+
+  // ---- main loop: ONE barrier per tile.  In the same phase the workgroup stages tile i+1 into
+  // the other buffer, does the S/dP/dV/dK work of tile i and the dQ contraction of tile i-1.
+  int it = 0;
+  for (int qt = qt0; qt < n_qt; ++qt, ++it) {
+    const int t0 = qt * BR, cur = it & 1;
+    if (qt + 1 < n_qt) {
+      stage(cur ^ 1);
+      if (qt + 2 < n_qt) prefetch(qt + 2);
+    }
+    const bf16* sQ = smem + L::OFF_Q + cur * L::QBUF;
+    const bf16* sdO = smem + L::OFF_DO + cur * L::QBUF;
+    bf16* sdS = smem + L::OFF_DS + cur * L::SBUF;
+    const bool need_mask = (J0 + BCB > S) || (causal && (J0 + BCB - 1 > t0 + off));
+    f32x16 sacc, pacc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
+    const int arow = swap23(li) * RSTR + 8 * g;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const bf16x8 aq = *reinterpret_cast<const bf16x8*>(sQ + arow + 16 * kk);
+      sacc = mfma32(aq, kreg[kk], sacc);
+    }
+    if (roleK) {
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const bf16x8 ao = *reinterpret_cast<const bf16x8*>(sdO + arow + 16 * kk);
+        pacc = mfma32(ao, vreg[kk], pacc);
+      }
+    }
+    // register r <-> row t0 + 16 (r/8) + 8 g + r%8, column jmine
+    float v[16];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int tl = 16 * h + 8 * g;
+      const float4 l0 = *reinterpret_cast<const float4*>(&sL[cur * BR + tl]);
+      const float4 l1 = *reinterpret_cast<const float4*>(&sL[cur * BR + tl + 4]);
+      const float lv[8] = {l0.x, l0.y, l0.z, l0.w, l1.x, l1.y, l1.z, l1.w};
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int r = 8 * h + u;
+        float pv = fast_exp2(fmaf(sacc[r], c, -lv[u]));
+        if (need_mask) {
+          const int t = t0 + tl + u;
+          const bool vis = (jmine < S) && (!causal || jmine <= t + off);
+          pv = vis ? pv : 0.f;
+        }
+        v[r] = pv;
+      }
+      if (roleK) {
+        const float4 d0 = *reinterpret_cast<const float4*>(&sDv[cur * BR + tl]);
+        const float4 d1 = *reinterpret_cast<const float4*>(&sDv[cur * BR + tl + 4]);
+        const float dv[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[8 * h + u] *= (pacc[8 * h + u] - dv[u]);  // dS
+      }
+    }
+    const bf16x8 pB0 = __builtin_bit_cast(bf16x8, pack8(&v[0]));
+    const bf16x8 pB1 = __builtin_bit_cast(bf16x8, pack8(&v[8]));
+    if (roleK) {
+      // dS through LDS, row = query row, column = slot (for the dQ contraction over slots)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int tl = 16 * (r >> 3) + 8 * g + (r & 7);
+        sdS[tl * SSTR + 32 * sw + li] = (bf16)v[r];
+      }
+    }
+    // ---- role V: dVf^T += dO^T P ; role K: dKf^T += Q^T dS   (k-step = 16 query rows;
+    // accumulator row m of block db is LDS row 32 db + m = head-dim index 8 (p % CPR) + p / CPR)
+    {
+      const bf16* sAT = smem + (roleK ? L::OFF_QT : L::OFF_DOT) + cur * L::TBUF;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const bf16* ar = sAT + (32 * db + li) * TSTR + 8 * g;
+        acc[db] = mfma32(*reinterpret_cast<const bf16x8*>(ar), pB0, acc[db]);
+        acc[db] = mfma32(*reinterpret_cast<const bf16x8*>(ar + 16), pB1, acc[db]);
+      }
+    }
+    if (it > 0) dq_tile(t0 - BR, cur ^ 1);  // previous tile's dS is complete since the last barrier
+    __syncthreads();
+  }
+  if (it > 0) dq_tile((n_qt - 1) * BR, (it - 1) & 1);
+
+  // ---- epilogue.  dKf^T (held by role K) then dVf^T (role V) go through LDS as f32 [slot][d] so
+  // that the un-fusion (dK_l = G_l tau dKf, dV_l = G_l dVf) is written with coalesced 16-byte
+  // stores and the gate gradients dlam_l = dKf.K_l + dVf.V_l are formed from coalesced 16-byte
+  // loads.  Item = (slot, 16-byte chunk): CPR consecutive lanes hold one slot's row.
   constexpr int ESTR = D + 4;                 // f32 per staged row
   constexpr int NITEM = BCB * CPR / NT;       // items per thread
   static_assert((size_t)BCB * ESTR * 4 <= (size_t)L::TOTAL * 2, "staging tile must fit");
@@ -378,14 +390,17 @@ __global__ __launch_bounds__(256, 1) void bwd_main_kernel(
 #pragma unroll
   for (int pass = 0; pass < 2; ++pass) {
     __syncthreads();  // LDS free (main loop done / previous pass consumed)
+    if (roleK == (pass == 0)) {
+      const float f = pass == 0 ? tau : 1.f;  // dKf carries the factor tau
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+      for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int prow = 32 * db + 8 * (r >> 2) + 4 * g + (r & 3);
-        const int d = 8 * (prow % CPR) + prow / CPR;
-        sE[(32 * wave + li) * ESTR + d] = pass == 0 ? dKacc[db][r] * tau : dVacc[db][r];
-      }
+        for (int r = 0; r < 16; ++r) {
+          const int prow = 32 * db + 8 * (r >> 2) + 4 * g + (r & 3);
+          const int d = 8 * (prow % CPR) + prow / CPR;
+          sE[(32 * sw + li) * ESTR + d] = acc[db][r] * f;
+        }
+    }
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < NITEM; ++i) {
@@ -410,10 +425,10 @@ __global__ __launch_bounds__(256, 1) void bwd_main_kernel(
           if (present) {
             float x[8];
             unpack8(*reinterpret_cast<const uint4*>((pass == 0 ? Kp[l] : Vp[l]) + o), x);
-            float acc = 0.f;
+            float a = 0.f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc = fmaf(v[e], x[e], acc);
-            dlam[i][l] += acc;
+            for (int e = 0; e < 8; ++e) a = fmaf(v[e], x[e], a);
+            dlam[i][l] += a;
           }
         }
       }
@@ -422,9 +437,9 @@ __global__ __launch_bounds__(256, 1) void bwd_main_kernel(
   if (dgate) {
 #pragma unroll
     for (int i = 0; i < NITEM; ++i) {
-      float d0 = group_sum<CPR>(dlam[i][0]);
-      float d1 = group_sum<CPR>(dlam[i][1]);
-      float d2 = group_sum<CPR>(dlam[i][2]);
+      const float d0 = group_sum<CPR>(dlam[i][0]);
+      const float d1 = group_sum<CPR>(dlam[i][1]);
+      const float d2 = group_sum<CPR>(dlam[i][2]);
       const int j = J0 + erow0 + ERS * i;
       const int t = j - off;
       if (j < S && t >= 0 && ecc == 0) {
@@ -540,8 +555,7 @@ BwdWs carve(int BH, int Tq, int d) {
 
 template <int D>
 hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
-  constexpr int TB = 2;
-  using L = BwdSmem<D, TB>;
+  using L = BwdSmem<D>;
   const BwdWs w = carve(a.BH, a.Tq, D);
   unsigned char* ws = static_cast<unsigned char*>(a.workspace);
   float* dQacc = reinterpret_cast<float*>(ws + w.off_dq);
@@ -567,16 +581,16 @@ hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
     Vp[l] = a.V[l] ? a.V[l] : anyV;
   }
   const int n_kvtiles = (a.S + BCB - 1) / BCB;
-  const size_t smem = (size_t)L::TOTAL * sizeof(bf16) + 2 * L::BR * sizeof(float);
+  const size_t smem = (size_t)L::TOTAL * sizeof(bf16) + 4 * L::BR * sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_main_kernel<D, TB>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_main_kernel<D>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((bwd_main_kernel<D, TB>), dim3((unsigned)((long)n_kvtiles * ((a.BH + 7) / 8) * 8)),
-                     dim3(256), smem, st, (const bf16*)a.dO, (const bf16*)a.Q,
+  hipLaunchKernelGGL((bwd_main_kernel<D>), dim3((unsigned)((long)n_kvtiles * ((a.BH + 7) / 8) * 8)),
+                     dim3(512), smem, st, (const bf16*)a.dO, (const bf16*)a.Q,
                      (const bf16*)Kp[0], (const bf16*)Kp[1], (const bf16*)Kp[2],
                      (const bf16*)Vp[0], (const bf16*)Vp[1], (const bf16*)Vp[2], a.G, a.LSE, Dvec,
                      (bf16*)a.dK[0], (bf16*)a.dK[1], (bf16*)a.dK[2], (bf16*)a.dV[0],

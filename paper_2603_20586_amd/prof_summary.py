@@ -1,0 +1,71 @@
+"""Turn rocprofv3 CSV output into the short text summaries kept under profiles/.
+
+    python -m paper_2603_20586_amd.prof_summary stats  <kernel_stats.csv>  <out.txt>  "<command>"
+    python -m paper_2603_20586_amd.prof_summary pmc    <counter_collection.csv> <out.txt> "<command>"
+
+`stats`: per-kernel calls / average / total time.  `pmc`: per-kernel average of every counter in
+the file; for FETCH_SIZE / WRITE_SIZE (KiB per dispatch) it also prints the value scaled by what
+the same counter reads for the 1 GiB calibration copy that `bench.py --calibrate-copy` runs
+(factor = 2^20 KiB / measured KiB of that copy), i.e. an estimate of true HBM bytes.
+"""
+from __future__ import annotations
+
+import collections
+import csv
+import subprocess
+import sys
+
+
+def short(name: str) -> str:
+    if name.startswith("_Z"):
+        try:
+            name = subprocess.run(["c++filt", name], capture_output=True, text=True).stdout.strip()
+        except OSError:
+            pass
+    name = name.replace("(anonymous namespace)::", "")
+    return name.split("(")[0][:80]
+
+
+def stats(src, dst, cmd):
+    rows = list(csv.DictReader(open(src)))
+    out = [f"# rocprofv3 kernel-trace summary", f"# command: {cmd}",
+           "# kernel | calls | avg_us | total_ms | pct", ""]
+    for r in rows[:14]:
+        out.append(f"{short(r['Name'])} | {r['Calls']} | {float(r['AverageNs']) / 1e3:.1f} | "
+                   f"{float(r['TotalDurationNs']) / 1e6:.2f} | {float(r['Percentage']):.2f}")
+    open(dst, "w").write("\n".join(out) + "\n")
+
+
+def pmc(src, dst, cmd):
+    rows = list(csv.DictReader(open(src)))
+    acc = collections.defaultdict(lambda: collections.defaultdict(list))
+    for r in rows:
+        acc[short(r["Kernel_Name"])][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    copy_kib = {}
+    for k, v in acc.items():
+        if "elementwise" in k and "CUDAFunctor_add" in k or "add" in k.lower() and "elementwise" in k:
+            for c, xs in v.items():
+                big = [x for x in xs if x > 5e5]  # the 1 GiB calibration launches
+                if big:
+                    copy_kib[c] = sum(big) / len(big)
+    out = ["# rocprofv3 --pmc summary (average per dispatch)", f"# command: {cmd}"]
+    for c, x in copy_kib.items():
+        out.append(f"# calibration copy (reads 1 GiB, writes 1 GiB): {c} = {x:.0f} KiB "
+                   f"-> factor {1048576.0 / x:.4f}")
+    out += ["# kernel | counter | dispatches | avg | scaled_MB (FETCH/WRITE only)", ""]
+    for k, v in sorted(acc.items()):
+        if "mka::" not in k:
+            continue
+        for c, xs in sorted(v.items()):
+            avg = sum(xs) / len(xs)
+            scaled = ""
+            if c in copy_kib and c in ("FETCH_SIZE", "WRITE_SIZE"):
+                scaled = f"{avg * (1048576.0 / copy_kib[c]) * 1024 / 1e6:.1f}"
+            out.append(f"{k} | {c} | {len(xs)} | {avg:.4g} | {scaled}")
+    open(dst, "w").write("\n".join(out) + "\n")
+
+
+if __name__ == "__main__":
+    mode, src, dst, cmd = sys.argv[1], sys.argv[2], sys.argv[3], sys.argv[4]
+    (stats if mode == "stats" else pmc)(src, dst, cmd)
+    print(open(dst).read())
