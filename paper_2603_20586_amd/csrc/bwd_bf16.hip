@@ -202,12 +202,16 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   const int n_qt = (Tq + BR - 1) / BR;
   const int qt0 = t_first / BR;
 
-  // ---- staging of query tiles: threads 0-127 carry Q, threads 128-255 carry dO (role V waves)
+  // ---- staging of query tiles is done by the role K waves (threads 256-383 carry Q, threads
+  // 384-511 carry dO, threads 256-287 the LSE / D rows): the role V waves issue the dQ atomics,
+  // and a wave that waits for its prefetched loads would also wait for its own older atomics.
   int rg, ccq;
   bool qactive;
   qtile_item<D>(tid & 127, rg, ccq, qactive);
-  qactive = qactive && tid < 256;
-  const bool stage_dO = tid >= 128;
+  qactive = qactive && tid >= 256;
+  const bool stage_dO = tid >= 384;
+  const bool stage_row = tid >= 256 && tid < 256 + BR;
+  const int srow = tid - 256;
   const bf16* Xb = (stage_dO ? dO : Q) + qbase;
   uint4 x4[4];
   float lse_n = 0.f, dv_n = 0.f;
@@ -221,8 +225,8 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
         if (t < Tq) x4[u] = *reinterpret_cast<const uint4*>(Xb + t * D + ccq * 8);
       }
     }
-    if (tid < BR) {
-      const int t = t0 + tid;
+    if (stage_row) {
+      const int t = t0 + srow;
       // rows past the end get LSE = +inf, hence P = 0
       lse_n = t < Tq ? LSEb[t] * kLog2e : INFINITY;
       dv_n = t < Tq ? Dvb[t] : 0.f;
@@ -248,9 +252,9 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
         *reinterpret_cast<uint2*>(&sXT[p1 * TSTR + rg * 4]) = hi;
       }
     }
-    if (tid < BR) {
-      sL[buf * BR + tid] = lse_n;
-      sDv[buf * BR + tid] = dv_n;
+    if (stage_row) {
+      sL[buf * BR + srow] = lse_n;
+      sDv[buf * BR + srow] = dv_n;
     }
   };
   // dQ[t, d] = sum_j dS[t, j] Kf[j, d] for one finished tile; work unit = 32-wide d slice, one per
@@ -325,17 +329,20 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
       const float4 l1 = *reinterpret_cast<const float4*>(&sL[cur * BR + tl + 4]);
       const float lv[8] = {l0.x, l0.y, l0.z, l0.w, l1.x, l1.y, l1.z, l1.w};
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int r = 8 * h + u;
-        float pv = fast_exp2(fmaf(sacc[r], c, -lv[u]));
-        if (need_mask) {
-          const int t = t0 + tl + u;
-          const bool vis = (jmine < S) && (!causal || jmine <= t + off);
-          pv = vis ? pv : 0.f;
-        }
-        v[r] = pv;
+      for (int u = 0; u < 8; ++u) v[8 * h + u] = fast_exp2(fmaf(sacc[8 * h + u], c, -lv[u]));
+    }
+    if (need_mask) {  // diagonal and tail tiles only (uniform branch, outside the hot path)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int t = t0 + 16 * (r >> 3) + 8 * g + (r & 7);
+        const bool vis = (jmine < S) && (!causal || jmine <= t + off);
+        v[r] = vis ? v[r] : 0.f;
       }
-      if (roleK) {
+    }
+    if (roleK) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int tl = 16 * h + 8 * g;
         const float4 d0 = *reinterpret_cast<const float4*>(&sDv[cur * BR + tl]);
         const float4 d1 = *reinterpret_cast<const float4*>(&sDv[cur * BR + tl + 4]);
         const float dv[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
