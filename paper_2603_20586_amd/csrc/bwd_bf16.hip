@@ -275,11 +275,16 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
         qacc = mfma32(a, b, qacc);
       }
       // register r <-> row t0 + 8 (r/4) + 4 g + r%4, column 32 wave + li
-      float* dst = dQacc + qbase + 32 * wave + li;
+      float* dst = dQacc + qbase + (long)(t0 + 4 * g) * D + 32 * wave + li;
+      if (t0 + BR <= Tq) {  // whole tile in range: constant offsets from one base, no tests
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int t = t0 + 8 * (r >> 2) + 4 * g + (r & 3);
-        if (t < Tq) atomicAdd(dst + (long)t * D, qacc[r]);
+        for (int r = 0; r < 16; ++r) atomicAdd(dst + (8 * (r >> 2) + (r & 3)) * D, qacc[r]);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int t = t0 + 8 * (r >> 2) + 4 * g + (r & 3);
+          if (t < Tq) atomicAdd(dst + (8 * (r >> 2) + (r & 3)) * D, qacc[r]);
+        }
       }
     }
   };
