@@ -219,7 +219,7 @@ __global__ __launch_bounds__(FW_NW * 64, 1) void fwd_bf16_kernel(
     const bf16* __restrict__ K2, const bf16* __restrict__ V0, const bf16* __restrict__ V1,
     const bf16* __restrict__ V2, const float* __restrict__ G, bf16* __restrict__ O,
     float* __restrict__ LSE, int Tq, int S, int len0, int len1, int len2, int causal, float c,
-    float tau, int n_qtiles, int BH) {
+    float tau, int n_qtiles, int BH, int interleave) {
   using L = FwdSmem<D>;
   constexpr int BR = FW_NW * 32, BC = FW_BC;
   constexpr int KK = D / 16, DB = D / 32;
@@ -231,11 +231,19 @@ __global__ __launch_bounds__(FW_NW * 64, 1) void fwd_bf16_kernel(
   const int tg = tid & (FW_NG - 1);
   // Workgroups are handed to the 8 XCDs round-robin by block index.  All query tiles of one
   // (batch, head) are given to ONE XCD (block index = 8 * slot + xcd), so that the workgroups
-  // that stream the same K/V tiles share that XCD's L2; within a head the heavy (late) query
-  // tiles go first so that the causal tail is short.
+  // that stream the same K/V tiles share that XCD's L2; heavy (late) query tiles go first so
+  // that the causal tail is short.
   const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3);
-  const int qt = n_qtiles - 1 - slot % n_qtiles;
-  const long bh = (long)(slot / n_qtiles) * 8 + xcd;
+  int qt, hl;
+  if (interleave) {  // small grids: heaviest tiles of ALL the XCD's heads first (shorter tail)
+    const int hpx = (BH + 7) / 8;
+    qt = n_qtiles - 1 - slot / hpx;
+    hl = slot % hpx;
+  } else {           // large grids: one head after the other (best L2 reuse of its K/V tiles)
+    qt = n_qtiles - 1 - slot % n_qtiles;
+    hl = slot / n_qtiles;
+  }
+  const long bh = (long)hl * 8 + xcd;
   if (bh >= BH) return;  // the head count need not be a multiple of 8
   const int off = S - Tq;
   const int tw0 = qt * BR + wave * 32;  // first row of this wave
@@ -356,6 +364,8 @@ static hipError_t launch_fwd_t(const FwdArgs& a, const void* const Kp[3], const 
   constexpr int BR = FW_NW * 32;
   const int n_qtiles = (a.Tq + BR - 1) / BR;
   const long nblocks = (long)n_qtiles * ((a.BH + 7) / 8) * 8;
+  // at most 4 workgroups per compute unit (256 CUs): the causal tail dominates, interleave heads
+  const int interleave = nblocks <= 4 * 256 ? 1 : 0;
   const size_t smem = (size_t)FwdSmem<D>::TOTAL * sizeof(bf16);
   static bool attr_set = false;
   if (!attr_set) {
@@ -368,7 +378,7 @@ static hipError_t launch_fwd_t(const FwdArgs& a, const void* const Kp[3], const 
                      (const bf16*)a.Q, (const bf16*)Kp[0], (const bf16*)Kp[1], (const bf16*)Kp[2],
                      (const bf16*)Vp[0], (const bf16*)Vp[1], (const bf16*)Vp[2], a.G, (bf16*)a.O,
                      a.LSE, a.Tq, a.S, a.len[0], a.len[1], a.len[2], a.causal,
-                     a.scale * kLog2e, a.scale, n_qtiles, a.BH);
+                     a.scale * kLog2e, a.scale, n_qtiles, a.BH, interleave);
   return hipGetLastError();
 }
 

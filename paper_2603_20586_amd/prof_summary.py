@@ -12,18 +12,25 @@ from __future__ import annotations
 
 import collections
 import csv
-import subprocess
+import re
 import sys
 
 
 def short(name: str) -> str:
-    if name.startswith("_Z"):
-        try:
-            name = subprocess.run(["c++filt", name], capture_output=True, text=True).stdout.strip()
-        except OSError:
-            pass
+    """Readable kernel name (c++filt does not know every mangling of the bf16 type)."""
+    m = re.match(r"_ZN3mka(?:12_GLOBAL__N_1)?(\d+)", name)
+    if m:
+        n = int(m.group(1))
+        start = m.end()
+        base = name[start:start + n]
+        t = re.match(r"I(.*?)E", name[start + n:])
+        tp = ""
+        if t:
+            tp = "<" + t.group(1).replace("DF16b", "bf16,").replace("Li", "").replace("E", ",") \
+                .replace("f", "f32,").strip(",") + ">"
+        return "mka::" + base + tp
     name = name.replace("(anonymous namespace)::", "")
-    return name.split("(")[0][:80]
+    return name.split("(")[0].replace("void ", "")[:80]
 
 
 def stats(src, dst, cmd):
@@ -40,20 +47,20 @@ def pmc(src, dst, cmd):
     rows = list(csv.DictReader(open(src)))
     acc = collections.defaultdict(lambda: collections.defaultdict(list))
     for r in rows:
-        acc[short(r["Kernel_Name"])][r["Counter_Name"]].append(float(r["Counter_Value"]))
+        key = (short(r["Kernel_Name"]), int(r["Grid_Size"]) // int(r["Workgroup_Size"]))
+        acc[key][r["Counter_Name"]].append(float(r["Counter_Value"]))
     copy_kib = {}
-    for k, v in acc.items():
-        if "elementwise" in k and "CUDAFunctor_add" in k or "add" in k.lower() and "elementwise" in k:
+    for (k, wgs), v in acc.items():
+        if "CUDAFunctorOnSelf_add" in k:  # the 1 GiB calibration copy of bench.py
             for c, xs in v.items():
-                big = [x for x in xs if x > 5e5]  # the 1 GiB calibration launches
-                if big:
-                    copy_kib[c] = sum(big) / len(big)
-    out = ["# rocprofv3 --pmc summary (average per dispatch)", f"# command: {cmd}"]
+                copy_kib[c] = sum(xs) / len(xs)
+    out = ["# rocprofv3 --pmc summary (average per dispatch, grouped by kernel and grid)",
+           f"# command: {cmd}"]
     for c, x in copy_kib.items():
         out.append(f"# calibration copy (reads 1 GiB, writes 1 GiB): {c} = {x:.0f} KiB "
                    f"-> factor {1048576.0 / x:.4f}")
-    out += ["# kernel | counter | dispatches | avg | scaled_MB (FETCH/WRITE only)", ""]
-    for k, v in sorted(acc.items()):
+    out += ["# kernel | workgroups | counter | dispatches | avg_KiB | scaled_MB", ""]
+    for (k, wgs), v in sorted(acc.items()):
         if "mka::" not in k:
             continue
         for c, xs in sorted(v.items()):
@@ -61,7 +68,7 @@ def pmc(src, dst, cmd):
             scaled = ""
             if c in copy_kib and c in ("FETCH_SIZE", "WRITE_SIZE"):
                 scaled = f"{avg * (1048576.0 / copy_kib[c]) * 1024 / 1e6:.1f}"
-            out.append(f"{k} | {c} | {len(xs)} | {avg:.4g} | {scaled}")
+            out.append(f"{k} | {wgs} | {c} | {len(xs)} | {avg:.5g} | {scaled}")
     open(dst, "w").write("\n".join(out) + "\n")
 
 
