@@ -213,33 +213,38 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   const bool stage_row = tid >= 256 && tid < 256 + BR;
   const int srow = tid - 256;
   const bf16* Xb = (stage_dO ? dO : Q) + qbase;
-  uint4 x4[4];
-  float lse_n = 0.f, dv_n = 0.f;
-  auto prefetch = [&](int qt) {  // global -> registers
+  // Two register sets: tile k+1 waits in one while tile k+2 is in flight into the other, so a
+  // load has two full iterations to arrive (the memory system is busy with the dQ atomics).
+  struct TileRegs {
+    uint4 x[4];
+    float lse, dv;
+  };
+  TileRegs setA = {}, setB = {};
+  auto prefetch = [&](TileRegs& r, int qt) {  // global -> registers
     const int t0 = qt * BR;
     if (qactive) {
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int t = t0 + rg * 4 + u;
-        x4[u] = make_uint4(0, 0, 0, 0);
-        if (t < Tq) x4[u] = *reinterpret_cast<const uint4*>(Xb + t * D + ccq * 8);
+        r.x[u] = make_uint4(0, 0, 0, 0);
+        if (t < Tq) r.x[u] = *reinterpret_cast<const uint4*>(Xb + t * D + ccq * 8);
       }
     }
     if (stage_row) {
       const int t = t0 + srow;
       // rows past the end get LSE = +inf, hence P = 0
-      lse_n = t < Tq ? LSEb[t] * kLog2e : INFINITY;
-      dv_n = t < Tq ? Dvb[t] : 0.f;
+      r.lse = t < Tq ? LSEb[t] * kLog2e : INFINITY;
+      r.dv = t < Tq ? Dvb[t] : 0.f;
     }
   };
-  auto stage = [&](int buf) {  // registers -> LDS: row-major tile and transposed tile
+  auto stage = [&](const TileRegs& r, int buf) {  // registers -> LDS: row-major + transposed tile
     if (qactive) {
       bf16* sX = smem + (stage_dO ? L::OFF_DO : L::OFF_Q) + buf * L::QBUF;
       bf16* sXT = smem + (stage_dO ? L::OFF_DOT : L::OFF_QT) + buf * L::TBUF;
 #pragma unroll
       for (int u = 0; u < 4; ++u)
-        *reinterpret_cast<uint4*>(&sX[(rg * 4 + u) * RSTR + ccq * 8]) = x4[u];
-      const uint32_t* xw[4] = {&x4[0].x, &x4[1].x, &x4[2].x, &x4[3].x};
+        *reinterpret_cast<uint4*>(&sX[(rg * 4 + u) * RSTR + ccq * 8]) = r.x[u];
+      const uint32_t* xw[4] = {&r.x[0].x, &r.x[1].x, &r.x[2].x, &r.x[3].x};
 #pragma unroll
       for (int e2 = 0; e2 < 4; ++e2) {  // dword e2 holds columns 2*e2, 2*e2+1
         uint2 lo, hi;
@@ -253,8 +258,8 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
       }
     }
     if (stage_row) {
-      sL[buf * BR + srow] = lse_n;
-      sDv[buf * BR + srow] = dv_n;
+      sL[buf * BR + srow] = r.lse;
+      sDv[buf * BR + srow] = r.dv;
     }
   };
   // dQ[t, d] = sum_j dS[t, j] Kf[j, d] for one finished tile; work unit = 32-wide d slice, one per
@@ -289,11 +294,13 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
     }
   };
 
-  // prologue: first tile into buffer 0 (the set-up buffers are dead after this barrier)
-  prefetch(qt0);
+  // prologue: tile 0 into buffer 0 (the set-up buffers are dead after the first barrier); tiles 1
+  // and 2 in flight.  Tile k lives in register set k & 1 (A for even k) and LDS buffer k & 1.
+  prefetch(setA, qt0);
+  if (qt0 + 1 < n_qt) prefetch(setB, qt0 + 1);
   __syncthreads();
-  stage(0);
-  if (qt0 + 1 < n_qt) prefetch(qt0 + 1);
+  stage(setA, 0);
+  if (qt0 + 2 < n_qt) prefetch(setA, qt0 + 2);
   __syncthreads();
 
   // ---- main loop: ONE barrier per tile.  In the same phase the workgroup stages tile i+1 into
@@ -302,8 +309,13 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   for (int qt = qt0; qt < n_qt; ++qt, ++it) {
     const int t0 = qt * BR, cur = it & 1;
     if (qt + 1 < n_qt) {
-      stage(cur ^ 1);
-      if (qt + 2 < n_qt) prefetch(qt + 2);
+      if (cur) {  // tile it+1 is even: set A
+        stage(setA, 0);
+        if (qt + 3 < n_qt) prefetch(setA, qt + 3);
+      } else {
+        stage(setB, 1);
+        if (qt + 3 < n_qt) prefetch(setB, qt + 3);
+      }
     }
     const bf16* sQ = smem + L::OFF_Q + cur * L::QBUF;
     const bf16* sdO = smem + L::OFF_DO + cur * L::QBUF;
