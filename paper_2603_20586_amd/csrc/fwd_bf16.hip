@@ -176,31 +176,44 @@ __device__ __forceinline__ void compute_tile(const bf16* sK, const bf16* sVT,
 #pragma unroll
     for (int r = 2; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
     mx = fmaxf(mx, xor32(mx));
-    const float m_new = fmaxf(m, mx);
-    // every row sees slot 0, so m_new is finite from the first sub-step that has a visible slot;
-    // a sub-step that is entirely masked for this row leaves m = -inf only before that
-    const bool dead = (m_new == -INFINITY);
-    const float alpha = (m == -INFINITY) ? 0.f : fast_exp2((m - m_new) * c);
-    const float mc = dead ? 0.f : m_new * c;
+    // Lazy max-shift: the reference m only moves when the row max has grown by more than 2^8
+    // in the exponent; until then P = exp2(c (s - m)) may exceed 1 (at most 256), which bf16 and
+    // the f32 sums hold without loss, and the rescale of the accumulators is skipped.  The
+    // recursion is unchanged (O and z are always relative to the same m), only m is stale.
+    // Every row sees slot 0, so m is finite after the first sub-step that has a visible slot.
+    const bool move = (mx - m) * c > 8.f || m == -INFINITY;
+    const float m_new = move ? mx : m;
+    const float alpha = move ? ((m == -INFINITY) ? 0.f : fast_exp2((m - m_new) * c)) : 1.f;
+    const float mc = (m_new == -INFINITY) ? 0.f : m_new * c;
     float p[16];
-    float psum = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       float e = fast_exp2(fmaf(sacc[r], c, -mc));
       if (MASK) e = (sacc[r] == -INFINITY) ? 0.f : e;  // also covers c == 0
       p[r] = e;
-      psum += e;
     }
+    const uint4 pk0 = pack8(&p[0]), pk1 = pack8(&p[8]);
+    const bf16x8 p0 = __builtin_bit_cast(bf16x8, pk0);
+    const bf16x8 p1 = __builtin_bit_cast(bf16x8, pk1);
+    // row sum of the bf16-rounded P (what the PV product uses), two values per instruction
+    const bf16x2 ones = {(bf16)1.f, (bf16)1.f};
+    float psum = 0.f;
+    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.x), ones, psum, false);
+    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.y), ones, psum, false);
+    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.z), ones, psum, false);
+    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.w), ones, psum, false);
+    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.x), ones, psum, false);
+    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.y), ones, psum, false);
+    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.z), ones, psum, false);
+    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.w), ones, psum, false);
     lsum = lsum * alpha + psum;
     m = m_new;
-    if (__any(alpha != 1.f)) {
+    if (__any(move)) {
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
     }
-    const bf16x8 p0 = __builtin_bit_cast(bf16x8, pack8(&p[0]));
-    const bf16x8 p1 = __builtin_bit_cast(bf16x8, pack8(&p[8]));
     // O^T += Vf^T P^T: k-step ks covers columns 16 ks .. 16 ks + 15 of the Vf^T tile
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
