@@ -39,6 +39,33 @@ __device__ __forceinline__ Raw3 load_raw3(const bf16* __restrict__ P0, const bf1
   return r;
 }
 
+// Same, addressed by 32-bit BYTE offsets from per-(b,h) base pointers that are uniform over the
+// wave: the compiler can then keep the bases in scalar registers and needs no 64-bit vector
+// address arithmetic per load.
+template <bool FULL>
+__device__ __forceinline__ Raw3 load_raw3_b(const bf16* __restrict__ P0, const bf16* __restrict__ P1,
+                                            const bf16* __restrict__ P2, unsigned base_b,
+                                            unsigned off_b, bool p0, bool p1, bool p2) {
+  const char* c0 = reinterpret_cast<const char*>(P0);
+  const char* c1 = reinterpret_cast<const char*>(P1);
+  const char* c2 = reinterpret_cast<const char*>(P2);
+  Raw3 r;
+  if constexpr (FULL) {
+    r.a = *reinterpret_cast<const uint4*>(c0 + off_b);
+    r.b = *reinterpret_cast<const uint4*>(c1 + off_b);
+    r.c = *reinterpret_cast<const uint4*>(c2 + off_b);
+  } else {
+    r.a = *reinterpret_cast<const uint4*>(c0 + (p0 ? off_b : base_b));
+    r.b = *reinterpret_cast<const uint4*>(c1 + (p1 ? off_b : base_b));
+    r.c = *reinterpret_cast<const uint4*>(c2 + (p2 ? off_b : base_b));
+    const uint4 z = make_uint4(0, 0, 0, 0);
+    if (!p0) r.a = z;
+    if (!p1) r.b = z;
+    if (!p2) r.c = z;
+  }
+  return r;
+}
+
 __device__ __forceinline__ void fuse8(const Raw3& r, float g0, float g1, float g2, float* out) {
   float f[8];
   unpack8(r.a, f);

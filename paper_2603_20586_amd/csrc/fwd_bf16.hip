@@ -72,9 +72,12 @@ __device__ __forceinline__ void load_k(HalfRaw& x, const bf16* __restrict__ K0,
     const int j = j0 + tg / CPR + RPP * i;
     const int jc = FULL ? j : (j < S ? j : S - 1);
     const bool in = FULL || j < S;
-    x.r[i] = load_raw3<FULL, int>(K0, K1, K2, cc * 8, jc * D + cc * 8, in && j < len0,
+    x.r[i] = load_raw3_b<FULL>(K0, K1, K2, (unsigned)(cc * 16), (unsigned)(jc * D + cc * 8) * 2u, in && j < len0,
                                   in && j < len1, in && j < len2);
-    x.g[i][0] = Gb[jc * 3 + 0]; x.g[i][1] = Gb[jc * 3 + 1]; x.g[i][2] = Gb[jc * 3 + 2];
+    const char* gp = reinterpret_cast<const char*>(Gb) + (unsigned)(jc * 12);
+    x.g[i][0] = *reinterpret_cast<const float*>(gp);
+    x.g[i][1] = *reinterpret_cast<const float*>(gp + 4);
+    x.g[i][2] = *reinterpret_cast<const float*>(gp + 8);
   }
 }
 
@@ -117,9 +120,12 @@ __device__ __forceinline__ void load_v(HalfRaw& x, const bf16* __restrict__ V0,
     const int j = j0 + sg * 4 + u;
     const int jc = FULL ? j : (j < S ? j : S - 1);
     const bool in = FULL || j < S;
-    x.r[u] = load_raw3<FULL, int>(V0, V1, V2, cc * 8, jc * D + cc * 8, in && j < len0,
+    x.r[u] = load_raw3_b<FULL>(V0, V1, V2, (unsigned)(cc * 16), (unsigned)(jc * D + cc * 8) * 2u, in && j < len0,
                                   in && j < len1, in && j < len2);
-    x.g[u][0] = Gb[jc * 3 + 0]; x.g[u][1] = Gb[jc * 3 + 1]; x.g[u][2] = Gb[jc * 3 + 2];
+    const char* gp = reinterpret_cast<const char*>(Gb) + (unsigned)(jc * 12);
+    x.g[u][0] = *reinterpret_cast<const float*>(gp);
+    x.g[u][1] = *reinterpret_cast<const float*>(gp + 4);
+    x.g[u][2] = *reinterpret_cast<const float*>(gp + 8);
   }
 }
 
