@@ -43,56 +43,25 @@ struct FwdSmem {
   static constexpr int VSTR = FW_BC + 8;   // bf16 per Vf^T row
   static constexpr int KSZ = FW_BC * KSTR;
   static constexpr int VSZ = D * VSTR;
-  static constexpr int BUF = KSZ + VSZ;    // one buffer: Kf then Vf^T
-  static constexpr int TOTAL = 2 * BUF;    // bf16 elements
+  static constexpr int VOFF = 2 * KSZ;     // two Kf buffers, then three Vf^T buffers
+  static constexpr int TOTAL = 2 * KSZ + 3 * VSZ;  // bf16 elements
 };
 
-// ---- raw (unfused) data of half a tile, prefetched into registers -------------------------
-// One register set serves both halves (a wave only ever holds one of them): up to 4 chunks of
-// three levels plus the gates of their slots.
-struct HalfRaw {
-  Raw3 r[4];
-  float g[4][3];
+// ---- staging: raw (unfused) data -> registers -> fused bf16 tile in LDS ----------------------
+// Waves 0-3 stage the K half of every tile, waves 4-7 the V half.  A thread's share of a half
+// tile is 4 work items ("quarters"), each one 16-byte chunk of the three levels plus the gates of
+// its slot.  Quarters are staged in PAIRS, one pair per half step of the MFMA loop: the pair's
+// raw data is loaded during one half step and fused during the next, cut into 8 slices that are
+// issued one by one behind the PV MFMAs, so that the VALU work runs in the shadow of the wave's
+// own matrix instructions and the global loads reach the memory pipeline a few at a time.
+struct PairRaw {
+  Raw3 r[2];
+  float g[2][3];
 };
-template <int D>
-struct KRaw {
-  static constexpr int N = FW_BC * (D / 8) / FW_NG;  // chunks per thread (4 for d=128, 2 for d=64)
+struct StageTmp {
+  float acc[2][8];  // running fused values of the two quarters of the pair (f32)
+  unsigned w[8];    // V: packed slots 0,1 of the item, kept until slots 2,3 are done
 };
-
-// tg = thread index inside the fusion group (0..255)
-template <int D, bool FULL>
-__device__ __forceinline__ void load_k(HalfRaw& x, const bf16* __restrict__ K0,
-                                       const bf16* __restrict__ K1, const bf16* __restrict__ K2,
-                                       const float* __restrict__ Gb, int j0, int S,
-                                       int len0, int len1, int len2, int tg) {
-  constexpr int CPR = D / 8, RPP = FW_NG / CPR;  // rows per pass
-  const int cc = tg % CPR;
-#pragma unroll
-  for (int i = 0; i < KRaw<D>::N; ++i) {
-    const int j = j0 + tg / CPR + RPP * i;
-    const int jc = FULL ? j : (j < S ? j : S - 1);
-    const bool in = FULL || j < S;
-    x.r[i] = load_raw3_b<FULL>(K0, K1, K2, (unsigned)(cc * 16), (unsigned)(jc * D + cc * 8) * 2u, in && j < len0,
-                                  in && j < len1, in && j < len2);
-    const char* gp = reinterpret_cast<const char*>(Gb) + (unsigned)(jc * 12);
-    x.g[i][0] = *reinterpret_cast<const float*>(gp);
-    x.g[i][1] = *reinterpret_cast<const float*>(gp + 4);
-    x.g[i][2] = *reinterpret_cast<const float*>(gp + 8);
-  }
-}
-
-template <int D>
-__device__ __forceinline__ void fuse_store_k(const HalfRaw& x, bf16* sK, int tg) {
-  constexpr int CPR = D / 8, RPP = FW_NG / CPR, KSTR = D + 8;
-  const int cc = tg % CPR;
-#pragma unroll
-  for (int i = 0; i < KRaw<D>::N; ++i) {
-    const int row = tg / CPR + RPP * i;
-    float acc[8];
-    fuse8(x.r[i], x.g[i][0], x.g[i][1], x.g[i][2], acc);
-    *reinterpret_cast<uint4*>(&sK[row * KSTR + cc * 8]) = pack8(acc);
-  }
-}
 
 // V work item = (4 consecutive slots, one 16-byte chunk).  Thread bits: [2:0] chunk low bits,
 // [3] slot-group bit 1 (selects the 8-byte half of a 16-byte column block), [4] slot-group bit 0,
@@ -107,129 +76,343 @@ __device__ __forceinline__ void v_item(int tg, int& sg, int& cc, bool& active) {
   if (!active) cc = 0;
 }
 
-template <int D, bool FULL>
-__device__ __forceinline__ void load_v(HalfRaw& x, const bf16* __restrict__ V0,
-                                       const bf16* __restrict__ V1, const bf16* __restrict__ V2,
-                                       const float* __restrict__ Gb, int j0, int S,
-                                       int len0, int len1, int len2, int tg) {
-  int sg, cc;
-  bool active;
-  v_item<D>(tg, sg, cc, active);
-#pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const int j = j0 + sg * 4 + u;
-    const int jc = FULL ? j : (j < S ? j : S - 1);
-    const bool in = FULL || j < S;
-    x.r[u] = load_raw3_b<FULL>(V0, V1, V2, (unsigned)(cc * 16), (unsigned)(jc * D + cc * 8) * 2u, in && j < len0,
-                                  in && j < len1, in && j < len2);
-    const char* gp = reinterpret_cast<const char*>(Gb) + (unsigned)(jc * 12);
-    x.g[u][0] = *reinterpret_cast<const float*>(gp);
-    x.g[u][1] = *reinterpret_cast<const float*>(gp + 4);
-    x.g[u][2] = *reinterpret_cast<const float*>(gp + 8);
-  }
-}
-
+// K work item i = (slot tg / CPR + RPP i, chunk tg % CPR); d = 64 has only two of them per thread
+// (quarters 0 and 2).  tg = thread index inside the fusion group (0..255).
 template <int D>
-__device__ __forceinline__ void fuse_store_v(const HalfRaw& x, bf16* sVT, int tg) {
-  constexpr int VSTR = FW_BC + 8;
-  int sg, cc;
-  bool active;
-  v_item<D>(tg, sg, cc, active);
-  if (!active) return;
-  float vf[4][8];
-#pragma unroll
-  for (int u = 0; u < 4; ++u) fuse8(x.r[u], x.g[u][0], x.g[u][1], x.g[u][2], vf[u]);
-  // slots 4 sg .. 4 sg + 3 go to columns col .. col + 3 (bits 2,3 of the slot index swapped)
-  const int col = 32 * (sg >> 3) + fw_swap23(4 * (sg & 7));
-  const int blk = col >> 3, half = (col >> 2) & 1;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int prow = e * (D / 8) + cc;  // LDS row of head-dim index d = 8 cc + e
-    uint2 w;
-    w.x = pack_bf16x2(vf[0][e], vf[1][e]);
-    w.y = pack_bf16x2(vf[2][e], vf[3][e]);
-    *reinterpret_cast<uint2*>(&sVT[prow * VSTR + 8 * blk + 4 * half]) = w;
+__device__ __forceinline__ bool k_quarter(int q, int& i) {
+  constexpr int N = FW_BC * (D / 8) / FW_NG;  // 4 for d = 128, 2 for d = 64
+  i = N == 4 ? q : q >> 1;
+  return N == 4 || (q & 1) == 0;
+}
+
+// raw loads of quarter q of the tile that starts at slot j0 (P0..P2: this group's K or V)
+template <int D, bool GV, bool FULL>
+__device__ __forceinline__ void stage_load(int q, PairRaw& x, const bf16* __restrict__ P0,
+                                           const bf16* __restrict__ P1, const bf16* __restrict__ P2,
+                                           const float* __restrict__ Gb, int j0, int S, int len0,
+                                           int len1, int len2, int tg) {
+  constexpr int CPR = D / 8, RPP = FW_NG / CPR;
+  int i, j, cc;
+  if (!GV) {
+    if (!k_quarter<D>(q, i)) return;
+    cc = tg % CPR;
+    j = j0 + tg / CPR + RPP * i;
+  } else {
+    int sg;
+    bool active;
+    v_item<D>(tg, sg, cc, active);
+    j = j0 + sg * 4 + q;
+  }
+  const int jc = FULL ? j : (j < S ? j : S - 1);
+  const bool in = FULL || j < S;
+  x.r[q & 1] = load_raw3_b<FULL>(P0, P1, P2, (unsigned)(cc * 16), (unsigned)(jc * D + cc * 8) * 2u,
+                                 in && j < len0, in && j < len1, in && j < len2);
+  const char* gp = reinterpret_cast<const char*>(Gb) + (unsigned)(jc * 12);
+  x.g[q & 1][0] = *reinterpret_cast<const float*>(gp);
+  x.g[q & 1][1] = *reinterpret_cast<const float*>(gp + 4);
+  x.g[q & 1][2] = *reinterpret_cast<const float*>(gp + 8);
+}
+
+// one level (0..2) of the raw data of quarter q of the tile that starts at slot j0; level 2 also
+// brings the gates of the slot
+template <int D, bool GV, bool FULL>
+__device__ __forceinline__ void stage_load_level(int q, int level, PairRaw& x,
+                                                 const bf16* __restrict__ P0,
+                                                 const bf16* __restrict__ P1,
+                                                 const bf16* __restrict__ P2,
+                                                 const float* __restrict__ Gb, int j0, int S,
+                                                 int len0, int len1, int len2, int tg) {
+  constexpr int CPR = D / 8, RPP = FW_NG / CPR;
+  int i, j, cc;
+  if (!GV) {
+    if (!k_quarter<D>(q, i)) return;
+    cc = tg % CPR;
+    j = j0 + tg / CPR + RPP * i;
+  } else {
+    int sg;
+    bool active;
+    v_item<D>(tg, sg, cc, active);
+    j = j0 + sg * 4 + q;
+  }
+  const int jc = FULL ? j : (j < S ? j : S - 1);
+  const bool in = FULL || j < S;
+  const bf16* P = level == 0 ? P0 : (level == 1 ? P1 : P2);
+  const int len = level == 0 ? len0 : (level == 1 ? len1 : len2);
+  const bool present = FULL || (in && j < len);
+  const unsigned off_b = present ? (unsigned)(jc * D + cc * 8) * 2u : (unsigned)(cc * 16);
+  uint4 v = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(P) + off_b);
+  if (!present) v = make_uint4(0, 0, 0, 0);
+  if (level == 0) x.r[q & 1].a = v;
+  else if (level == 1) x.r[q & 1].b = v;
+  else {
+    x.r[q & 1].c = v;
+    const char* gp = reinterpret_cast<const char*>(Gb) + (unsigned)(jc * 12);
+    x.g[q & 1][0] = *reinterpret_cast<const float*>(gp);
+    x.g[q & 1][1] = *reinterpret_cast<const float*>(gp + 4);
+    x.g[q & 1][2] = *reinterpret_cast<const float*>(gp + 8);
   }
 }
 
-// ---- MFMA work of one tile: two sub-steps of 32 slots ----------------------------------------
-template <int D, bool MASK>
-__device__ __forceinline__ void compute_tile(const bf16* sK, const bf16* sVT,
-                                             const bf16x8 (&qreg)[D / 16], f32x16 (&oacc)[D / 32],
-                                             float& m, float& lsum, float c, int j0, int jmax,
-                                             int li, int g) {
-  constexpr int KSTR = D + 8, VSTR = FW_BC + 8, KK = D / 16, DB = D / 32;
+// half slice (part 0..3, h = 0/1) of the fusion of quarter q: parts 0..2 add one level each (f32,
+// four elements per half), part 3 rounds to bf16 and writes to LDS (dst: Kf tile or Vf^T tile of
+// the staged tile)
+template <int D, bool GV>
+__device__ __forceinline__ void stage_slice(int q, int part, int h, const PairRaw& x, StageTmp& t,
+                                            bf16* dst, int tg) {
+  constexpr int CPR = D / 8, RPP = FW_NG / CPR, KSTR = D + 8, VSTR = FW_BC + 8;
+  int i = q, sg = 0, cc = 0;
+  if (!GV) {
+    if (!k_quarter<D>(q, i)) return;
+  } else {
+    bool active;
+    v_item<D>(tg, sg, cc, active);
+    if (!active) return;
+  }
+  float* acc = t.acc[q & 1];
+  if (part < 3) {
+    const uint4& u = part == 0 ? x.r[q & 1].a : (part == 1 ? x.r[q & 1].b : x.r[q & 1].c);
+    // gate of the level; with all gates of the slot loaded together, g[.][part]
+    const float gl = x.g[q & 1][part];
+    const unsigned w0 = h ? u.z : u.x, w1 = h ? u.w : u.y;
+    const float f[4] = {bf16lo(w0), bf16hi(w0), bf16lo(w1), bf16hi(w1)};
 #pragma unroll
-  for (int sb = 0; sb < 2; ++sb) {
-    f32x16 sacc;
+    for (int e = 0; e < 4; ++e)
+      acc[4 * h + e] = part == 0 ? gl * f[e] : fmaf(gl, f[e], acc[4 * h + e]);
+    return;
+  }
+  if (!GV) {
+    if (h == 1)
+      *reinterpret_cast<uint4*>(&dst[(tg / CPR + RPP * i) * KSTR + (tg % CPR) * 8]) = pack8(acc);
+  } else if (q == 1) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
-    const bf16* arow = &sK[(32 * sb + li) * KSTR + 8 * g];
+    for (int e = 4 * h; e < 4 * h + 4; ++e) t.w[e] = pack_bf16x2(t.acc[0][e], t.acc[1][e]);
+  } else if (q == 3) {
+    // slots 4 sg .. 4 sg + 3 go to columns col .. col + 3 (bits 2,3 of the slot index swapped)
+    const int col = 32 * (sg >> 3) + fw_swap23(4 * (sg & 7));
+    const int blk = col >> 3, half = (col >> 2) & 1;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(arow + 16 * kk);
-      sacc = mfma32(a, qreg[kk], sacc);
+    for (int e = 4 * h; e < 4 * h + 4; ++e) {
+      const int prow = e * (D / 8) + cc;  // LDS row of head-dim index d = 8 cc + e
+      uint2 w;
+      w.x = t.w[e];
+      w.y = pack_bf16x2(t.acc[0][e], t.acc[1][e]);
+      *reinterpret_cast<uint2*>(&dst[prow * VSTR + 8 * blk + 4 * half]) = w;
     }
-    // register r <-> slot j0 + 32 sb + 8 (r/4) + 4 g + r%4 of this lane's row
-    if (MASK) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int j = j0 + 32 * sb + 8 * (r >> 2) + 4 * g + (r & 3);
-        if (j > jmax) sacc[r] = -INFINITY;
+  }
+}
+
+// ---- one half step of a wave: 32 slots (one "unit") of its 32 query rows -----------------------
+// Software pipeline: the S^T MFMAs of the NEXT unit are issued between the exponentials of the
+// current one, and the staging slices between the PV MFMAs, in exactly the order written here
+// (scheduling barriers keep the compiler from regrouping them); LDS fragments are read four
+// instructions ahead of their MFMA.
+//   s_now : finished S^T of the unit to consume (register r <-> slot jb + 8 (r/4) + 4 g + r%4)
+//   s_next: S^T of unit `unit_n` of the Kf tile at sKn, left in flight for the next half step
+//   FAST  : interior half step - no masking, staging unconditional and with all levels present
+template <int D, bool GV, bool FAST>
+__device__ __forceinline__ void half_step(
+    f32x16 s_now, f32x16& s_next, const bf16* sKn, int unit_n, int jb, const bf16* sVT, int unit,
+    const bf16x8 (&qreg)[D / 16], f32x16 (&oacc)[D / 32], float& m, float& lsum, float c, int jmax,
+    PairRaw& raw, StageTmp& tmp, bf16* dst, int qf, bool do_fuse, int jl, int ql, bool do_load,
+    bool full, const bf16* __restrict__ P0, const bf16* __restrict__ P1,
+    const bf16* __restrict__ P2, const float* __restrict__ Gb, int S, int len0, int len1, int len2,
+    int li, int g, int tg) {
+  constexpr int KSTR = D + 8, VSTR = FW_BC + 8, KK = D / 16, DB = D / 32;
+  constexpr int PF = 4;          // LDS fragments in flight
+  constexpr int EPK = 16 / KK;   // exponentials per S MFMA
+  constexpr int NPV = 2 * DB;    // PV MFMAs of the unit
+  constexpr int SPM = 16 / (KK + NPV);  // staging half slices per MFMA (1 for d = 128, 2 for 64)
+  // half slice hs = 0..15 of the pair: quarter qf + hs / 8, part (hs % 8) / 2, half hs % 2; once
+  // both halves of a level are consumed, its registers are reloaded with the same level of
+  // quarter ql + hs / 8 of the tile at jl (fused one half step from now)
+  auto stage = [&](int hs) __attribute__((always_inline)) {
+    const int qo = hs >> 3, part = (hs & 7) >> 1, h = hs & 1;
+    if (FAST || do_fuse) stage_slice<D, GV>(qf + qo, part, h, raw, tmp, dst, tg);
+    if (h == 1 && part < 3) {
+      if (FAST) {
+        stage_load_level<D, GV, true>(ql + qo, part, raw, P0, P1, P2, Gb, jl, S, len0, len1, len2, tg);
+      } else if (do_load) {
+        if (full) stage_load_level<D, GV, true>(ql + qo, part, raw, P0, P1, P2, Gb, jl, S, len0, len1, len2, tg);
+        else stage_load_level<D, GV, false>(ql + qo, part, raw, P0, P1, P2, Gb, jl, S, len0, len1, len2, tg);
       }
     }
-    float mx = fmaxf(sacc[0], sacc[1]);
+  };
+  bf16x8 fr[PF];
+  const bf16* arow = &sKn[(32 * unit_n + li) * KSTR + 8 * g];
 #pragma unroll
-    for (int r = 2; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
-    mx = fmaxf(mx, xor32(mx));
-    // Lazy max-shift: the reference m only moves when the row max has grown by more than 2^8
-    // in the exponent; until then P = exp2(c (s - m)) may exceed 1 (at most 256), which bf16 and
-    // the f32 sums hold without loss, and the rescale of the accumulators is skipped.  The
-    // recursion is unchanged (O and z are always relative to the same m), only m is stale.
-    // Every row sees slot 0, so m is finite after the first sub-step that has a visible slot.
-    const bool move = (mx - m) * c > 8.f || m == -INFINITY;
-    const float m_new = move ? mx : m;
-    const float alpha = move ? ((m == -INFINITY) ? 0.f : fast_exp2((m - m_new) * c)) : 1.f;
-    const float mc = (m_new == -INFINITY) ? 0.f : m_new * c;
-    float p[16];
+  for (int kk = 0; kk < PF; ++kk) fr[kk] = *reinterpret_cast<const bf16x8*>(arow + 16 * kk);
+
+  if (!FAST) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      float e = fast_exp2(fmaf(sacc[r], c, -mc));
-      if (MASK) e = (sacc[r] == -INFINITY) ? 0.f : e;  // also covers c == 0
-      p[r] = e;
-    }
-    const uint4 pk0 = pack8(&p[0]), pk1 = pack8(&p[8]);
-    const bf16x8 p0 = __builtin_bit_cast(bf16x8, pk0);
-    const bf16x8 p1 = __builtin_bit_cast(bf16x8, pk1);
-    // row sum of the bf16-rounded P (what the PV product uses), two values per instruction
-    const bf16x2 ones = {(bf16)1.f, (bf16)1.f};
-    float psum = 0.f;
-    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.x), ones, psum, false);
-    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.y), ones, psum, false);
-    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.z), ones, psum, false);
-    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.w), ones, psum, false);
-    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.x), ones, psum, false);
-    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.y), ones, psum, false);
-    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.z), ones, psum, false);
-    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.w), ones, psum, false);
-    lsum = lsum * alpha + psum;
-    m = m_new;
-    if (__any(move)) {
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-    }
-    // O^T += Vf^T P^T: k-step ks covers columns 16 ks .. 16 ks + 15 of the Vf^T tile
-#pragma unroll
-    for (int db = 0; db < DB; ++db) {
-      const bf16* vrow = &sVT[(32 * db + li) * VSTR];  // LDS rows: see the row permutation
-      const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(vrow + 8 * (4 * sb + 0 + g));
-      const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(vrow + 8 * (4 * sb + 2 + g));
-      oacc[db] = mfma32(a0, p0, oacc[db]);
-      oacc[db] = mfma32(a1, p1, oacc[db]);
+      const int j = jb + 8 * (r >> 2) + 4 * g + (r & 3);
+      if (j > jmax) s_now[r] = -INFINITY;
     }
   }
+  float mx = fmaxf(s_now[0], s_now[1]);
+#pragma unroll
+  for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s_now[r]);
+  mx = fmaxf(mx, xor32(mx));
+  // Lazy max-shift: the reference m only moves when the row max has grown by more than 2^8
+  // in the exponent; until then P = exp2(c (s - m)) may exceed 1 (at most 256), which bf16 and
+  // the f32 sums hold without loss, and the rescale of the accumulators is skipped.  The
+  // recursion is unchanged (O and z are always relative to the same m), only m is stale.
+  // Every row sees slot 0, so m is finite after the first unit that has a visible slot.
+  const bool move = (mx - m) * c > 8.f || m == -INFINITY;
+  const float m_new = move ? mx : m;
+  const float alpha = move ? ((m == -INFINITY) ? 0.f : fast_exp2((m - m_new) * c)) : 1.f;
+  const float mc = (m_new == -INFINITY) ? 0.f : m_new * c;
+  m = m_new;
+  if (__any(move)) {
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+  }
+
+  // -- section A: S^T of the next unit, between the exponentials of this one
+  f32x16 sn;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) sn[r] = 0.f;
+  float p[16];
+  const bf16* vbase = &sVT[li * VSTR + 8 * (4 * unit + g)];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    sn = mfma32(fr[kk % PF], qreg[kk], sn);
+    if (kk + PF < KK) {
+      fr[kk % PF] = *reinterpret_cast<const bf16x8*>(arow + 16 * (kk + PF));
+    } else {  // the K fragments are all on their way: start on the Vf^T fragments
+      const int i = kk + PF - KK;  // PV MFMA i uses rows 32 (i % DB), k half i / DB
+      if (i < NPV)
+        fr[kk % PF] = *reinterpret_cast<const bf16x8*>(vbase + 32 * (i % DB) * VSTR + 16 * (i / DB));
+    }
+#pragma unroll
+    for (int r = kk * EPK; r < (kk + 1) * EPK; ++r) {
+      float e = fast_exp2(fmaf(s_now[r], c, -mc));
+      if (!FAST) e = (s_now[r] == -INFINITY) ? 0.f : e;  // also covers c == 0
+      p[r] = e;
+    }
+#pragma unroll
+    for (int hs = kk * SPM; hs < (kk + 1) * SPM; ++hs) stage(hs);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  s_next = sn;
+  const uint4 pk0 = pack8(&p[0]), pk1 = pack8(&p[8]);
+  const bf16x8 p0 = __builtin_bit_cast(bf16x8, pk0);
+  const bf16x8 p1 = __builtin_bit_cast(bf16x8, pk1);
+  // row sum of the bf16-rounded P (what the PV product uses), two values per instruction
+  const bf16x2 ones = {(bf16)1.f, (bf16)1.f};
+  float psum = 0.f;
+  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.x), ones, psum, false);
+  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.y), ones, psum, false);
+  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.z), ones, psum, false);
+  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.w), ones, psum, false);
+  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.x), ones, psum, false);
+  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.y), ones, psum, false);
+  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.z), ones, psum, false);
+  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.w), ones, psum, false);
+  lsum = lsum * alpha + psum;
+  __builtin_amdgcn_sched_barrier(0);
+
+  // -- section B: O^T += Vf^T P^T (k half 0 = columns 16 ks .. of the unit with P^T regs 0-7),
+  // one staging slice (d = 128) or two (d = 64) behind every MFMA
+#pragma unroll
+  for (int i = 0; i < NPV; ++i) {
+    constexpr int KP = KK % PF;  // ring position of PV fragment 0
+    oacc[i % DB] = mfma32(fr[(KP + i) % PF], i / DB ? p1 : p0, oacc[i % DB]);
+    if (i + PF < NPV) {
+      const int n = i + PF;
+      fr[(KP + i) % PF] = *reinterpret_cast<const bf16x8*>(vbase + 32 * (n % DB) * VSTR + 16 * (n / DB));
+    }
+#pragma unroll
+    for (int hs = (KK + i) * SPM; hs < (KK + i + 1) * SPM; ++hs) stage(hs);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// ---- the tile loop of one wave; GV = the wave stages V halves (else K halves) ------------------
+// The barrier that publishes tile jt+1 sits in the MIDDLE of tile jt's work: its second unit
+// still reads the old Vf^T buffer (hence three of them) while the first S^T of tile jt+1 is
+// already being issued.  Staging order: pair B (quarters 2,3) of tile jt+1 is fused in the first
+// half step of tile jt, pair A (quarters 0,1) of tile jt+2 in the second.
+template <int D, bool GV>
+__device__ __forceinline__ void run_tiles(bf16* smem, const bf16* __restrict__ P0,
+                                          const bf16* __restrict__ P1, const bf16* __restrict__ P2,
+                                          const float* __restrict__ Gb, const bf16x8 (&qreg)[D / 16],
+                                          f32x16 (&oacc)[D / 32], float& m, float& lsum, float c,
+                                          int ntiles, int S, int len0, int len1, int len2,
+                                          int causal, int row_lo, int jmax, int li, int g, int tg) {
+  using L = FwdSmem<D>;
+  constexpr int BC = FW_BC;
+  const int lenmin = min(len0, min(len1, len2));
+  PairRaw raw = {};  // fully defined on every path, so that it lives in registers
+  StageTmp tmp = {};
+  // this group's half of tile T lives in K buffer T & 1 or V^T buffer T % 3
+  auto dst_of = [&](int kb, int vb) { return smem + (GV ? L::VOFF + vb * L::VSZ : kb * L::KSZ); };
+  auto stage_pair_now = [&](int T, int q0, int kb, int vb) __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = q0; q < q0 + 2; ++q)
+      stage_load<D, GV, false>(q, raw, P0, P1, P2, Gb, T * BC, S, len0, len1, len2, tg);
+#pragma unroll
+    for (int hs = 0; hs < 16; ++hs)
+      stage_slice<D, GV>(q0 + (hs >> 3), (hs & 7) >> 1, hs & 1, raw, tmp, dst_of(kb, vb), tg);
+  };
+
+  // prologue: tile 0 complete, pair A of tile 1 fused, pair B of tile 1 loaded
+  stage_pair_now(0, 0, 0, 0);
+  stage_pair_now(0, 2, 0, 0);
+  if (ntiles > 1) {
+    stage_pair_now(1, 0, 1, 1);
+#pragma unroll
+    for (int q = 2; q < 4; ++q)
+      stage_load<D, GV, false>(q, raw, P0, P1, P2, Gb, BC, S, len0, len1, len2, tg);
+  }
+  __syncthreads();
+
+  f32x16 s_a, s_b;
+  {
+    constexpr int KSTR = D + 8;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s_a[r] = 0.f;
+    const bf16* arow = &smem[li * KSTR + 8 * g];
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk)
+      s_a = mfma32(*reinterpret_cast<const bf16x8*>(arow + 16 * kk), qreg[kk], s_a);
+  }
+  int vb = 0;  // V^T buffer of tile jt
+  for (int jt = 0; jt < ntiles; ++jt) {
+    const bool has1 = jt + 1 < ntiles, has2 = jt + 2 < ntiles;
+    const int j0 = jt * BC;
+    const int vb1 = vb == 2 ? 0 : vb + 1, vb2 = vb1 == 2 ? 0 : vb1 + 1;
+    const bf16* sK = smem + (jt & 1) * L::KSZ;
+    const bf16* sK1 = smem + ((jt + 1) & 1) * L::KSZ;
+    const bf16* sVT = smem + L::VOFF + vb * L::VSZ;
+    bf16* dst1 = dst_of((jt + 1) & 1, vb1);  // tile jt+1, pair B
+    bf16* dst2 = dst_of(jt & 1, vb2);        // tile jt+2, pair A
+    // row_lo = first row of the wave + (S - Tq): the wave's rows see slots <= row_lo .. row_lo + 31
+    const bool need_mask = (j0 + BC > S) || (causal && (j0 + BC - 1 > row_lo));
+    const bool full2 = j0 + 3 * BC <= lenmin;
+    const int jl = j0 + 2 * BC;  // both half steps load raw data of tile jt+2
+    if (!need_mask && has2 && full2) {
+      half_step<D, GV, true>(s_a, s_b, sK, 1, j0, sVT, 0, qreg, oacc, m, lsum, c, jmax, raw, tmp,
+                             dst1, 2, true, jl, 0, true, true, P0, P1, P2, Gb, S, len0, len1, len2,
+                             li, g, tg);
+      __syncthreads();  // tile jt+1 is complete in LDS; K buffer jt&1 may be overwritten
+      half_step<D, GV, true>(s_b, s_a, sK1, 0, j0 + 32, sVT, 1, qreg, oacc, m, lsum, c, jmax, raw,
+                             tmp, dst2, 0, true, jl, 2, true, true, P0, P1, P2, Gb, S, len0, len1,
+                             len2, li, g, tg);
+    } else {
+      half_step<D, GV, false>(s_a, s_b, sK, 1, j0, sVT, 0, qreg, oacc, m, lsum, c, jmax, raw, tmp,
+                              dst1, 2, has1, jl, 0, has2, full2, P0, P1, P2, Gb, S, len0, len1,
+                              len2, li, g, tg);
+      __syncthreads();
+      half_step<D, GV, false>(s_b, s_a, sK1, 0, j0 + 32, sVT, 1, qreg, oacc, m, lsum, c, jmax, raw,
+                              tmp, dst2, 0, has2, jl, 2, has2, full2, P0, P1, P2, Gb, S, len0, len1,
+                              len2, li, g, tg);
+    }
+    vb = vb1;
+  }
+  __syncthreads();  // every wave is done with the tile buffers (the epilogue reuses them)
 }
 
 template <int D>
@@ -298,56 +481,16 @@ __global__ __launch_bounds__(FW_NW * 64, 1) void fwd_bf16_kernel(
   int j_end = S;
   if (causal && t_last + off + 1 < S) j_end = t_last + off + 1;
   const int ntiles = (j_end + BC - 1) / BC;
-  const int lenmin = min(len0, min(len1, len2));
   const int jmax = causal ? (tq + off < S - 1 ? tq + off : S - 1) : S - 1;
 
-  HalfRaw raw = {};  // fully defined on every path, so that it lives in registers
-  // waves 0-3 own the K half of every tile, waves 4-7 the V half
-  auto load_half = [&](int jt) {
-    const int j0 = jt * BC;
-    const bool full = j0 + BC <= lenmin;
-    if (!grpV) {
-      if (full) load_k<D, true>(raw, K0b, K1b, K2b, Gb, j0, S, len0, len1, len2, tg);
-      else load_k<D, false>(raw, K0b, K1b, K2b, Gb, j0, S, len0, len1, len2, tg);
-    } else {
-      if (full) load_v<D, true>(raw, V0b, V1b, V2b, Gb, j0, S, len0, len1, len2, tg);
-      else load_v<D, false>(raw, V0b, V1b, V2b, Gb, j0, S, len0, len1, len2, tg);
-    }
-  };
-  auto store_half = [&](int buf) {
-    bf16* sK = smem + buf * L::BUF;
-    if (!grpV) fuse_store_k<D>(raw, sK, tg);
-    else fuse_store_v<D>(raw, sK + L::KSZ, tg);
-  };
-
-  // prologue: tile 0 into buffer 0, raw data of tile 1 into registers
-  load_half(0);
-  store_half(0);
-  if (ntiles > 1) load_half(1);
-  __syncthreads();
-
-  for (int jt = 0; jt < ntiles; ++jt) {
-    const bool has1 = jt + 1 < ntiles, has2 = jt + 2 < ntiles;
-    // the V group fuses tile jt+1 before its MFMA work, the K group after: on every SIMD one
-    // wave's VALU-heavy fusion then runs beside the other wave's MFMAs
-    if (grpV && has1) {
-      store_half((jt + 1) & 1);
-      if (has2) load_half(jt + 2);
-    }
-    {
-      const bf16* sK = smem + (jt & 1) * L::BUF;
-      const bf16* sVT = sK + L::KSZ;
-      const int j0 = jt * BC;
-      const bool need_mask = (j0 + BC > S) || (causal && (j0 + BC - 1 > tw0 + off));
-      if (need_mask) compute_tile<D, true>(sK, sVT, qreg, oacc, m, lsum, c, j0, jmax, li, g);
-      else compute_tile<D, false>(sK, sVT, qreg, oacc, m, lsum, c, j0, jmax, li, g);
-    }
-    if (!grpV && has1) {
-      store_half((jt + 1) & 1);
-      if (has2) load_half(jt + 2);
-    }
-    __syncthreads();  // tile jt+1 is complete in LDS; buffer jt&1 may be overwritten next
-  }
+  // waves 0-3 stage the K half of every tile, waves 4-7 the V half; the two loops have the same
+  // trip count and one barrier per trip
+  if (!grpV)
+    run_tiles<D, false>(smem, K0b, K1b, K2b, Gb, qreg, oacc, m, lsum, c, ntiles, S, len0, len1, len2,
+                        causal, tw0 + off, jmax, li, g, tg);
+  else
+    run_tiles<D, true>(smem, V0b, V1b, V2b, Gb, qreg, oacc, m, lsum, c, ntiles, S, len0, len1, len2,
+                       causal, tw0 + off, jmax, li, g, tg);
 
   // ---- epilogue: normalise, transpose O^T through LDS (tile buffers are free after the last
   // barrier), store rows with coalesced 16-byte writes

@@ -60,7 +60,15 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 }
 
 // Exchange with the lane 32 away (the other half of the wave).
-__device__ __forceinline__ float xor32(float v) { return __shfl_xor(v, 32, 64); }
+// One v_permlane32_swap (a VALU instruction of gfx950, no LDS round trip): with both operands
+// equal to v, the first result holds the lower half's values in both halves of the wave, the
+// second the upper half's; each lane then picks the one that is not its own.
+__device__ __forceinline__ float xor32(float v) {
+  typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+  const unsigned u = __float_as_uint(v);
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float((threadIdx.x & 32) ? r.x : r.y);
+}
 
 // Sum / max over aligned groups of 2^k lanes via xor butterflies.
 template <int WIDTH>
