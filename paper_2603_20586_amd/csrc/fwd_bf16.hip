@@ -72,7 +72,7 @@ __device__ __forceinline__ void v_item(int tg, int& sg, int& cc, bool& active) {
   constexpr int CPR = D / 8;
   sg = (((tg >> 3) & 1) << 1) | ((tg >> 4) & 1) | (((tg >> 5) & 3) << 2);
   cc = (tg & 7) | ((tg >> 7) << 3);
-  active = cc < CPR;
+  active = CPR == 16 || cc < CPR;  // tg < 256, so cc < 16 always
   if (!active) cc = 0;
 }
 
@@ -178,6 +178,9 @@ __device__ __forceinline__ void stage_slice(int q, int part, int h, const PairRa
 #pragma unroll
     for (int e = 0; e < 4; ++e)
       acc[4 * h + e] = part == 0 ? gl * f[e] : fmaf(gl, f[e], acc[4 * h + e]);
+    // pin the arithmetic to this slice (else it all sinks to where the tile is written)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) asm volatile("" : "+v"(acc[4 * h + e]));
     return;
   }
   if (!GV) {
@@ -185,7 +188,10 @@ __device__ __forceinline__ void stage_slice(int q, int part, int h, const PairRa
       *reinterpret_cast<uint4*>(&dst[(tg / CPR + RPP * i) * KSTR + (tg % CPR) * 8]) = pack8(acc);
   } else if (q == 1) {
 #pragma unroll
-    for (int e = 4 * h; e < 4 * h + 4; ++e) t.w[e] = pack_bf16x2(t.acc[0][e], t.acc[1][e]);
+    for (int e = 4 * h; e < 4 * h + 4; ++e) {
+      t.w[e] = pack_bf16x2(t.acc[0][e], t.acc[1][e]);
+      asm volatile("" : "+v"(t.w[e]));
+    }
   } else if (q == 3) {
     // slots 4 sg .. 4 sg + 3 go to columns col .. col + 3 (bits 2,3 of the slot index swapped)
     const int col = 32 * (sg >> 3) + fw_swap23(4 * (sg & 7));
