@@ -67,16 +67,14 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(const bf16* __restrict__ 
 template <int D>
 struct BwdSmem {
   static constexpr int BR = 32;          // query rows per tile
-  static constexpr int RSTR = D + 8;     // row-major Q / dO tiles
-  static constexpr int TSTR = BR + 8;    // transposed Q / dO tiles
-  static constexpr int SSTR = BCB + 8;   // dS tile, Kf^T
-  static constexpr int QBUF = BR * RSTR, TBUF = D * TSTR, SBUF = BR * SSTR;
+  static constexpr int RSTR = D + 8;     // row-major Q / dO tiles (rows permuted, see tile_row)
+  static constexpr int SSTR = BCB + 8;   // Kf^T
+  static constexpr int QBUF = BR * RSTR;
+  static constexpr int SBUF = BCB * BR;  // dS^T tile: [slot][row], 64-byte rows, chunks rotated
   // every per-tile array is double-buffered (index b = 0, 1)
   static constexpr int OFF_Q = 0;
   static constexpr int OFF_DO = OFF_Q + 2 * QBUF;
-  static constexpr int OFF_QT = OFF_DO + 2 * QBUF;
-  static constexpr int OFF_DOT = OFF_QT + 2 * TBUF;
-  static constexpr int OFF_DS = OFF_DOT + 2 * TBUF;
+  static constexpr int OFF_DS = OFF_DO + 2 * QBUF;
   static constexpr int LOOP_END = OFF_DS + 2 * SBUF;
   // set-up only: row-major Kf and Vf of the workgroup's 128 slots
   static constexpr int OFF_KROW = 0;
@@ -86,20 +84,38 @@ struct BwdSmem {
   static constexpr int TOTAL = OFF_KT + D * SSTR;  // bf16 elements
 };
 
-// Work item of the Q / dO tile load = (4 consecutive rows, one 16-byte chunk), 128 items per
-// tensor.  Thread bits: [2:0] chunk low bits, [3] row-group bit 0 (selects the 8-byte half of a
-// 16-byte column block of the transposed tiles), [5:4] row-group bits 2:1, [6] chunk bit 3.
-// With the transposed tiles' ROWS permuted (head-dim index d = 8 cc + e lives in LDS row
-// e * (D/8) + cc) a 16-lane write group covers every bank once and a 16-lane MFMA read group
-// touches 16 consecutive rows.
-template <int D>
-__device__ __forceinline__ void qtile_item(int t, int& rg, int& cc, bool& active) {
-  rg = ((t >> 3) & 1) | (((t >> 4) & 3) << 1);
-  cc = (t & 7) | (((t >> 6) & 1) << 3);
-  active = cc < D / 8;
-  if (!active) cc = 0;
+// LDS row of query row t (0..31) of a Q / dO tile.  The tiles are read two ways: as MFMA A
+// operands by rows (16 lanes read 16 rows x 16 bytes: the rows must differ mod 16) and, for the
+// products that contract over query rows, TRANSPOSED with ds_read_b64_tr_b16 (32 lanes read 4
+// consecutive query rows x 64 bytes: with the 272-byte row stride those rows must be 4 LDS rows
+// apart).  t = 4a + b  ->  row 4b + a (inside each group of 16) satisfies both.
+__device__ __forceinline__ int tile_row(int t) {
+  return (t & 16) | ((t & 3) << 2) | ((t >> 2) & 3);
 }
 
+// Transposed 16-bit LDS read (gfx950): inside every 16-lane group, lane i receives, for
+// k = 0..3, element (i & 3) of the 8 bytes addressed by lane 4k + (i >> 2).  With lane s
+// addressing row (s >> 2), columns 4 (s & 3) .. +3 of a row-major block, lane i gets column i of
+// rows 0..3: the block's transpose, which is the MFMA A-operand layout (row = lane, 4 k-values).
+typedef short bwd_v4s __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint2 lds_read_tr(const bf16* p) {
+  typedef __attribute__((address_space(3))) bwd_v4s* lptr;
+  const bwd_v4s v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p));
+  return __builtin_bit_cast(uint2, v);
+}
+// A operand (32 x 16) = transpose of rows k0 .. k0+15 (the MFMA k index), columns m0 .. m0+31 of
+// a row-major LDS matrix; row_ptr(k) returns the address of row k, column m0.
+template <typename RowPtr>
+__device__ __forceinline__ bf16x8 load_a_tr(RowPtr row_ptr, int lane) {
+  const int i = lane & 15, gsel = (lane >> 4) & 1, khalf = lane >> 5;
+  const int kr = 8 * khalf + (i >> 2), col = 16 * gsel + 4 * (i & 3);
+  const uint2 lo = lds_read_tr(row_ptr(kr) + col);
+  const uint2 hi = lds_read_tr(row_ptr(kr + 4) + col);
+  return __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+}
+
+// Work item of the Q / dO tile load = (row, 16-byte chunk); a tensor's 128 staging threads cover
+// 128 / CPR rows per pass.  An 8-lane LDS write group is 128 contiguous bytes of one row.
 template <int D>
 __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
     const bf16* __restrict__ dO, const bf16* __restrict__ Q, const bf16* __restrict__ K0,
@@ -110,7 +126,7 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
     bf16* __restrict__ dV2, float* __restrict__ dQacc, float* __restrict__ dgate, int Tq, int S,
     int len0, int len1, int len2, int causal, float c, float tau, int n_kvtiles, int BH) {
   using L = BwdSmem<D>;
-  constexpr int BR = L::BR, RSTR = L::RSTR, TSTR = L::TSTR, SSTR = L::SSTR;
+  constexpr int BR = L::BR, RSTR = L::RSTR, SSTR = L::SSTR;
   constexpr int CPR = D / 8, KK = D / 16, DB = D / 32, NT = 512;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16* smem = reinterpret_cast<bf16*>(smem_raw);
@@ -205,10 +221,9 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   // ---- staging of query tiles is done by the role K waves (threads 256-383 carry Q, threads
   // 384-511 carry dO, threads 256-287 the LSE / D rows): the role V waves issue the dQ atomics,
   // and a wave that waits for its prefetched loads would also wait for its own older atomics.
-  int rg, ccq;
-  bool qactive;
-  qtile_item<D>(tid & 127, rg, ccq, qactive);
-  qactive = qactive && tid >= 256;
+  constexpr int RPP = 128 / CPR, NU = BR / RPP;  // rows per pass, passes (4 for d = 128)
+  const int ccq = (tid & 127) % CPR, rq = (tid & 127) / CPR;
+  const bool qactive = tid >= 256;
   const bool stage_dO = tid >= 384;
   const bool stage_row = tid >= 256 && tid < 256 + BR;
   const int srow = tid - 256;
@@ -216,7 +231,7 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   // Two register sets: tile k+1 waits in one while tile k+2 is in flight into the other, so a
   // load has two full iterations to arrive (the memory system is busy with the dQ atomics).
   struct TileRegs {
-    uint4 x[4];
+    uint4 x[NU];
     float lse, dv;
   };
   TileRegs setA = {}, setB = {};
@@ -224,8 +239,8 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
     const int t0 = qt * BR;
     if (qactive) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int t = t0 + rg * 4 + u;
+      for (int u = 0; u < NU; ++u) {
+        const int t = t0 + rq + RPP * u;
         r.x[u] = make_uint4(0, 0, 0, 0);
         if (t < Tq) r.x[u] = *reinterpret_cast<const uint4*>(Xb + t * D + ccq * 8);
       }
@@ -237,25 +252,12 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
       r.dv = t < Tq ? Dvb[t] : 0.f;
     }
   };
-  auto stage = [&](const TileRegs& r, int buf) {  // registers -> LDS: row-major + transposed tile
+  auto stage = [&](const TileRegs& r, int buf) {  // registers -> LDS
     if (qactive) {
       bf16* sX = smem + (stage_dO ? L::OFF_DO : L::OFF_Q) + buf * L::QBUF;
-      bf16* sXT = smem + (stage_dO ? L::OFF_DOT : L::OFF_QT) + buf * L::TBUF;
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
-        *reinterpret_cast<uint4*>(&sX[(rg * 4 + u) * RSTR + ccq * 8]) = r.x[u];
-      const uint32_t* xw[4] = {&r.x[0].x, &r.x[1].x, &r.x[2].x, &r.x[3].x};
-#pragma unroll
-      for (int e2 = 0; e2 < 4; ++e2) {  // dword e2 holds columns 2*e2, 2*e2+1
-        uint2 lo, hi;
-        lo.x = (xw[0][e2] & 0xffffu) | (xw[1][e2] << 16);
-        lo.y = (xw[2][e2] & 0xffffu) | (xw[3][e2] << 16);
-        hi.x = (xw[0][e2] >> 16) | (xw[1][e2] & 0xffff0000u);
-        hi.y = (xw[2][e2] >> 16) | (xw[3][e2] & 0xffff0000u);
-        const int p0 = (2 * e2) * CPR + ccq, p1 = (2 * e2 + 1) * CPR + ccq;  // permuted rows
-        *reinterpret_cast<uint2*>(&sXT[p0 * TSTR + rg * 4]) = lo;
-        *reinterpret_cast<uint2*>(&sXT[p1 * TSTR + rg * 4]) = hi;
-      }
+      for (int u = 0; u < NU; ++u)
+        *reinterpret_cast<uint4*>(&sX[tile_row(rq + RPP * u) * RSTR + ccq * 8]) = r.x[u];
     }
     if (stage_row) {
       sL[buf * BR + srow] = r.lse;
@@ -271,11 +273,16 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
       f32x16 qacc;
 #pragma unroll
       for (int r = 0; r < 16; ++r) qacc[r] = 0.f;
-      const int arow = li * SSTR + 8 * g;
       const int brow = (32 * wave + li) * SSTR + 8 * g;
 #pragma unroll
       for (int ks = 0; ks < BCB / 16; ++ks) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(sdS + arow + 16 * ks);
+        // A = dS rows (m = query row, k = slot) = transpose of dS^T rows 16 ks .. 16 ks + 15
+        const int i = lane & 15, gsel = (lane >> 4) & 1;
+        const int ch = 2 * gsel + ((i & 3) >> 1), sub = 4 * (i & 1);  // logical 16-byte chunk
+        const int R0 = 16 * ks + 8 * g + (i >> 2), R1 = R0 + 4;
+        const uint2 lo = lds_read_tr(sdS + R0 * BR + 8 * ((ch + (R0 >> 1)) & 3) + sub);
+        const uint2 hi = lds_read_tr(sdS + R1 * BR + 8 * ((ch + (R1 >> 1)) & 3) + sub);
+        const bf16x8 a = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
         const bf16x8 b = *reinterpret_cast<const bf16x8*>(sKT + brow + 16 * ks);
         qacc = mfma32(a, b, qacc);
       }
@@ -324,7 +331,7 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
     f32x16 sacc, pacc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
-    const int arow = swap23(li) * RSTR + 8 * g;
+    const int arow = tile_row(swap23(li)) * RSTR + 8 * g;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       const bf16x8 aq = *reinterpret_cast<const bf16x8*>(sQ + arow + 16 * kk);
@@ -370,22 +377,23 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
     const bf16x8 pB0 = __builtin_bit_cast(bf16x8, pack8(&v[0]));
     const bf16x8 pB1 = __builtin_bit_cast(bf16x8, pack8(&v[8]));
     if (roleK) {
-      // dS through LDS, row = query row, column = slot (for the dQ contraction over slots)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int tl = 16 * (r >> 3) + 8 * g + (r & 7);
-        sdS[tl * SSTR + 32 * sw + li] = (bf16)v[r];
-      }
+      // dS^T through LDS: row = slot, 32 query rows per 64-byte row.  The lane's 8 values of
+      // half h are one 16-byte chunk (logical chunk 2 h + g); chunks are rotated by (row >> 1) so
+      // that the 8 lanes of a write group hit 8 different 16-byte bank groups.
+      const int R = 32 * sw + li;
+      *reinterpret_cast<uint4*>(&sdS[R * BR + 8 * ((g + (R >> 1)) & 3)]) = __builtin_bit_cast(uint4, pB0);
+      *reinterpret_cast<uint4*>(&sdS[R * BR + 8 * ((2 + g + (R >> 1)) & 3)]) = __builtin_bit_cast(uint4, pB1);
     }
-    // ---- role V: dVf^T += dO^T P ; role K: dKf^T += Q^T dS   (k-step = 16 query rows;
-    // accumulator row m of block db is LDS row 32 db + m = head-dim index 8 (p % CPR) + p / CPR)
+    // ---- role V: dVf^T += dO^T P ; role K: dKf^T += Q^T dS   (k-step = 16 query rows; A is
+    // read transposed out of the row-major tile; accumulator row m of block db = head dim 32 db + m)
     {
-      const bf16* sAT = smem + (roleK ? L::OFF_QT : L::OFF_DOT) + cur * L::TBUF;
+      const bf16* sA = roleK ? sQ : sdO;
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
-        const bf16* ar = sAT + (32 * db + li) * TSTR + 8 * g;
-        acc[db] = mfma32(*reinterpret_cast<const bf16x8*>(ar), pB0, acc[db]);
-        acc[db] = mfma32(*reinterpret_cast<const bf16x8*>(ar + 16), pB1, acc[db]);
+        const bf16x8 a0 = load_a_tr([&](int k) { return sA + tile_row(k) * RSTR + 32 * db; }, lane);
+        const bf16x8 a1 = load_a_tr([&](int k) { return sA + tile_row(16 + k) * RSTR + 32 * db; }, lane);
+        acc[db] = mfma32(a0, pB0, acc[db]);
+        acc[db] = mfma32(a1, pB1, acc[db]);
       }
     }
     if (it > 0) dq_tile(t0 - BR, cur ^ 1);  // previous tile's dS is complete since the last barrier
@@ -420,8 +428,7 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int prow = 32 * db + 8 * (r >> 2) + 4 * g + (r & 3);
-          const int d = 8 * (prow % CPR) + prow / CPR;
+          const int d = 32 * db + 8 * (r >> 2) + 4 * g + (r & 3);
           sE[(32 * sw + li) * ESTR + d] = acc[db][r] * f;
         }
     }
