@@ -70,11 +70,12 @@ struct BwdSmem {
   static constexpr int RSTR = D + 8;     // row-major Q / dO tiles (rows permuted, see tile_row)
   static constexpr int SSTR = BCB + 8;   // Kf^T
   static constexpr int QBUF = BR * RSTR;
-  static constexpr int SBUF = BCB * BR;  // dS^T tile: [slot][row], 64-byte rows, chunks rotated
-  // every per-tile array is double-buffered (index b = 0, 1)
+  static constexpr int SBUF = BCB * BR;  // P^T / dS^T tile: [slot][row], 64-byte rows, chunks rotated
+  // Q, dO (and the LSE / D rows) live for three iterations: triple-buffered; P^T, dS^T for two
   static constexpr int OFF_Q = 0;
-  static constexpr int OFF_DO = OFF_Q + 2 * QBUF;
-  static constexpr int OFF_DS = OFF_DO + 2 * QBUF;
+  static constexpr int OFF_DO = OFF_Q + 3 * QBUF;
+  static constexpr int OFF_P = OFF_DO + 3 * QBUF;
+  static constexpr int OFF_DS = OFF_P + 2 * SBUF;
   static constexpr int LOOP_END = OFF_DS + 2 * SBUF;
   // set-up only: row-major Kf and Vf of the workgroup's 128 slots
   static constexpr int OFF_KROW = 0;
@@ -131,8 +132,8 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16* smem = reinterpret_cast<bf16*>(smem_raw);
   bf16* sKT = smem + L::OFF_KT;
-  float* sL = reinterpret_cast<float*>(smem + L::TOTAL);  // [2][BR] LSE in log2 units
-  float* sDv = sL + 2 * BR;                               // [2][BR] D
+  float* sL = reinterpret_cast<float*>(smem + L::TOTAL);  // [3][BR] LSE in log2 units
+  float* sDv = sL + 3 * BR;                               // [3][BR] D
 
   // 8 waves = 2 per SIMD.  Waves 0-3 (role V) and 4-7 (role K) each own the same four blocks
   // of 32 slots: role V computes S -> P -> dVf^T, role K computes S, dP -> dS -> dKf^T and
@@ -198,13 +199,12 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
     }
   }
   __syncthreads();
-  // B operands held in registers for the whole kernel: Kf rows (both roles), Vf rows (role K)
-  bf16x8 kreg[KK], vreg[KK];
+  // B operand held in registers for the whole kernel: Kf rows (role V, for S) or Vf rows (role
+  // K, for dP) of the wave's 32 slots
+  bf16x8 breg[KK];
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) {
-    kreg[kk] = *reinterpret_cast<const bf16x8*>(smem + L::OFF_KROW + (32 * sw + li) * RSTR + 16 * kk + 8 * g);
-    vreg[kk] = *reinterpret_cast<const bf16x8*>(smem + (roleK ? L::OFF_VROW : L::OFF_KROW) + (32 * sw + li) * RSTR + 16 * kk + 8 * g);
-  }
+  for (int kk = 0; kk < KK; ++kk)
+    breg[kk] = *reinterpret_cast<const bf16x8*>(smem + (roleK ? L::OFF_VROW : L::OFF_KROW) + (32 * sw + li) * RSTR + 16 * kk + 8 * g);
   // one accumulator set per wave: dVf^T (role V) or dKf^T (role K)
   f32x16 acc[DB];
 #pragma unroll
@@ -218,50 +218,51 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   const int n_qt = (Tq + BR - 1) / BR;
   const int qt0 = t_first / BR;
 
-  // ---- staging of query tiles is done by the role K waves (threads 256-383 carry Q, threads
-  // 384-511 carry dO, threads 256-287 the LSE / D rows): the role V waves issue the dQ atomics,
-  // and a wave that waits for its prefetched loads would also wait for its own older atomics.
-  constexpr int RPP = 128 / CPR, NU = BR / RPP;  // rows per pass, passes (4 for d = 128)
-  const int ccq = (tid & 127) % CPR, rq = (tid & 127) / CPR;
-  const bool qactive = tid >= 256;
-  const bool stage_dO = tid >= 384;
-  const bool stage_row = tid >= 256 && tid < 256 + BR;
-  const int srow = tid - 256;
+  // ---- staging of query tiles is done by the role K waves: the role V waves issue the dQ
+  // atomics, and a wave that waits for its prefetched loads would also wait for its own older
+  // atomics.  Wave 4 carries Q of the EVEN tiles (tile index relative to the first one), wave 5
+  // their dO, waves 6 and 7 the odd tiles.  A wave so has ONE tile in flight at a time and only
+  // touches it every second iteration: its loads have two full iterations to arrive, which they
+  // need while the memory pipeline is backed up with the atomics.  Item = (row, 16-byte chunk);
+  // an 8-lane LDS write group is 128 contiguous bytes of one row.
+  constexpr int RPP = 64 / CPR, NU = BR / RPP;  // rows per pass, passes (8 for d = 128)
+  const int ccq = lane % CPR, rq = lane / CPR;
+  const bool stage_dO = wave & 1;
+  const int stage_par = (wave >> 1) & 1;           // parity of the tiles this wave stages
+  const bool stage_row = !stage_dO && lane < BR;   // LSE / D rows ride with the Q wave
   const bf16* Xb = (stage_dO ? dO : Q) + qbase;
-  // Two register sets: tile k+1 waits in one while tile k+2 is in flight into the other, so a
-  // load has two full iterations to arrive (the memory system is busy with the dQ atomics).
   struct TileRegs {
     uint4 x[NU];
     float lse, dv;
   };
-  TileRegs setA = {}, setB = {};
+  TileRegs treg = {};
   auto prefetch = [&](TileRegs& r, int qt) {  // global -> registers
     const int t0 = qt * BR;
-    if (qactive) {
 #pragma unroll
-      for (int u = 0; u < NU; ++u) {
-        const int t = t0 + rq + RPP * u;
-        r.x[u] = make_uint4(0, 0, 0, 0);
-        if (t < Tq) r.x[u] = *reinterpret_cast<const uint4*>(Xb + t * D + ccq * 8);
+    for (int u = 0; u < NU; ++u) {
+      const int t = t0 + rq + RPP * u;
+      r.x[u] = make_uint4(0, 0, 0, 0);
+      if (t < Tq) r.x[u] = *reinterpret_cast<const uint4*>(Xb + t * D + ccq * 8);
+    }
+    if (stage_row) {
+      // raw values only: any arithmetic here would make the wave wait for the load at once
+      const int t = t0 + lane;
+      if (t < Tq) {
+        r.lse = LSEb[t];
+        r.dv = Dvb[t];
       }
     }
-    if (stage_row) {
-      const int t = t0 + srow;
-      // rows past the end get LSE = +inf, hence P = 0
-      r.lse = t < Tq ? LSEb[t] * kLog2e : INFINITY;
-      r.dv = t < Tq ? Dvb[t] : 0.f;
-    }
   };
-  auto stage = [&](const TileRegs& r, int buf) {  // registers -> LDS
-    if (qactive) {
-      bf16* sX = smem + (stage_dO ? L::OFF_DO : L::OFF_Q) + buf * L::QBUF;
+  auto stage = [&](const TileRegs& r, int buf, int qt) {  // registers -> LDS
+    bf16* sX = smem + (stage_dO ? L::OFF_DO : L::OFF_Q) + buf * L::QBUF;
 #pragma unroll
-      for (int u = 0; u < NU; ++u)
-        *reinterpret_cast<uint4*>(&sX[tile_row(rq + RPP * u) * RSTR + ccq * 8]) = r.x[u];
-    }
+    for (int u = 0; u < NU; ++u)
+      *reinterpret_cast<uint4*>(&sX[tile_row(rq + RPP * u) * RSTR + ccq * 8]) = r.x[u];
     if (stage_row) {
-      sL[buf * BR + srow] = r.lse;
-      sDv[buf * BR + srow] = r.dv;
+      // rows past the end get LSE = +inf, hence P = 0
+      const bool valid = qt * BR + lane < Tq;
+      sL[buf * BR + lane] = valid ? r.lse * kLog2e : INFINITY;
+      sDv[buf * BR + lane] = valid ? r.dv : 0.f;
     }
   };
   // dQ[t, d] = sum_j dS[t, j] Kf[j, d] for one finished tile; work unit = 32-wide d slice, one per
@@ -301,105 +302,126 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
     }
   };
 
-  // prologue: tile 0 into buffer 0 (the set-up buffers are dead after the first barrier); tiles 1
-  // and 2 in flight.  Tile k lives in register set k & 1 (A for even k) and LDS buffer k & 1.
-  prefetch(setA, qt0);
-  if (qt0 + 1 < n_qt) prefetch(setB, qt0 + 1);
-  __syncthreads();
-  stage(setA, 0);
-  if (qt0 + 2 < n_qt) prefetch(setA, qt0 + 2);
+  // ---- main loop, ONE barrier per iteration, three tiles in flight.  In iteration `it`
+  //   role K: stages tile it+1 (prefetches it+3); for tile it-1: dP = dO Vf^T, dS = P (dP - D)
+  //           with P^T read back from LDS, publishes dS^T, dKf^T += Q^T dS
+  //   role V: for tile it: S = Q Kf^T, P = exp2(c S - LSE), publishes P^T, dVf^T += dO^T P;
+  //           for tile it-2: dQ += dS Kf (atomics)
+  // so S is computed once, and every hand-over (P^T, dS^T, staged tiles) crosses one barrier.
+  const int n_tiles = n_qt - qt0;
+  if (roleK && stage_par < n_tiles) prefetch(treg, qt0 + stage_par);  // tiles 0 and 1
+  __syncthreads();  // the set-up buffers are dead
+  if (roleK && stage_par == 0) {
+    stage(treg, 0, qt0);
+    if (n_tiles > 2) prefetch(treg, qt0 + 2);
+  }
   __syncthreads();
 
-  // ---- main loop: ONE barrier per tile.  In the same phase the workgroup stages tile i+1 into
-  // the other buffer, does the S/dP/dV/dK work of tile i and the dQ contraction of tile i-1.
-  int it = 0;
-  for (int qt = qt0; qt < n_qt; ++qt, ++it) {
-    const int t0 = qt * BR, cur = it & 1;
-    if (qt + 1 < n_qt) {
-      if (cur) {  // tile it+1 is even: set A
-        stage(setA, 0);
-        if (qt + 3 < n_qt) prefetch(setA, qt + 3);
-      } else {
-        stage(setB, 1);
-        if (qt + 3 < n_qt) prefetch(setB, qt + 3);
-      }
-    }
-    const bf16* sQ = smem + L::OFF_Q + cur * L::QBUF;
-    const bf16* sdO = smem + L::OFF_DO + cur * L::QBUF;
-    bf16* sdS = smem + L::OFF_DS + cur * L::SBUF;
-    const bool need_mask = (J0 + BCB > S) || (causal && (J0 + BCB - 1 > t0 + off));
-    f32x16 sacc, pacc;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
-    const int arow = tile_row(swap23(li)) * RSTR + 8 * g;
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      const bf16x8 aq = *reinterpret_cast<const bf16x8*>(sQ + arow + 16 * kk);
-      sacc = mfma32(aq, kreg[kk], sacc);
-    }
+  // chunk-rotated address of the lane's 16 bytes (8 query rows 16 h + 8 g ..) in a P^T / dS^T tile
+  const int Rl = 32 * sw + li;
+  auto pt_off = [&](int h) { return Rl * BR + 8 * ((2 * h + g + (Rl >> 1)) & 3); };
+  const int arow = tile_row(swap23(li)) * RSTR + 8 * g;
+
+  int b3 = 0;  // it % 3
+  for (int it = 0; it < n_tiles + 2; ++it) {
+    const int b3p = b3 == 0 ? 2 : b3 - 1;  // (it - 1) % 3
     if (roleK) {
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const bf16x8 ao = *reinterpret_cast<const bf16x8*>(sdO + arow + 16 * kk);
-        pacc = mfma32(ao, vreg[kk], pacc);
+      if (it + 1 < n_tiles && ((it + 1) & 1) == stage_par) {
+        stage(treg, b3 == 2 ? 0 : b3 + 1, qt0 + it + 1);
+        if (it + 3 < n_tiles) prefetch(treg, qt0 + it + 3);
       }
-    }
-    // register r <-> row t0 + 16 (r/8) + 8 g + r%8, column jmine
-    float v[16];
+      if (it >= 1 && it <= n_tiles) {
+        const int k = it - 1;
+        const bf16* sQ = smem + L::OFF_Q + b3p * L::QBUF;
+        const bf16* sdO = smem + L::OFF_DO + b3p * L::QBUF;
+        const bf16* sP = smem + L::OFF_P + (k & 1) * L::SBUF;
+        bf16* sdS = smem + L::OFF_DS + (k & 1) * L::SBUF;
+        f32x16 pacc;
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int tl = 16 * h + 8 * g;
-      const float4 l0 = *reinterpret_cast<const float4*>(&sL[cur * BR + tl]);
-      const float4 l1 = *reinterpret_cast<const float4*>(&sL[cur * BR + tl + 4]);
-      const float lv[8] = {l0.x, l0.y, l0.z, l0.w, l1.x, l1.y, l1.z, l1.w};
+        for (int r = 0; r < 16; ++r) pacc[r] = 0.f;
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[8 * h + u] = fast_exp2(fmaf(sacc[8 * h + u], c, -lv[u]));
-    }
-    if (need_mask) {  // diagonal and tail tiles only (uniform branch, outside the hot path)
+        for (int kk = 0; kk < KK; ++kk) {
+          const bf16x8 ao = *reinterpret_cast<const bf16x8*>(sdO + arow + 16 * kk);
+          pacc = mfma32(ao, breg[kk], pacc);
+        }
+        // register r <-> row 16 (r/8) + 8 g + r%8 of the tile, column = the lane's slot
+        float v[16];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int t = t0 + 16 * (r >> 3) + 8 * g + (r & 7);
-        const bool vis = (jmine < S) && (!causal || jmine <= t + off);
-        v[r] = vis ? v[r] : 0.f;
+        for (int h = 0; h < 2; ++h) {
+          const int tl = 16 * h + 8 * g;
+          const float4 d0 = *reinterpret_cast<const float4*>(&sDv[b3p * BR + tl]);
+          const float4 d1 = *reinterpret_cast<const float4*>(&sDv[b3p * BR + tl + 4]);
+          const float dv[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+          float pf[8];
+          unpack8(*reinterpret_cast<const uint4*>(&sP[pt_off(h)]), pf);
+#pragma unroll
+          for (int u = 0; u < 8; ++u) v[8 * h + u] = pf[u] * (pacc[8 * h + u] - dv[u]);  // dS
+        }
+        const uint4 s0 = pack8(&v[0]), s1 = pack8(&v[8]);
+        *reinterpret_cast<uint4*>(&sdS[pt_off(0)]) = s0;
+        *reinterpret_cast<uint4*>(&sdS[pt_off(1)]) = s1;
+        const bf16x8 sB0 = __builtin_bit_cast(bf16x8, s0), sB1 = __builtin_bit_cast(bf16x8, s1);
+        // dKf^T += Q^T dS (k-step = 16 query rows; A read transposed out of the row-major tile;
+        // accumulator row m of block db = head dim 32 db + m)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const bf16x8 a0 = load_a_tr([&](int r) { return sQ + tile_row(r) * RSTR + 32 * db; }, lane);
+          const bf16x8 a1 = load_a_tr([&](int r) { return sQ + tile_row(16 + r) * RSTR + 32 * db; }, lane);
+          acc[db] = mfma32(a0, sB0, acc[db]);
+          acc[db] = mfma32(a1, sB1, acc[db]);
+        }
       }
-    }
-    if (roleK) {
+    } else {
+      if (it < n_tiles) {
+        const int t0 = (qt0 + it) * BR;
+        const bf16* sQ = smem + L::OFF_Q + b3 * L::QBUF;
+        const bf16* sdO = smem + L::OFF_DO + b3 * L::QBUF;
+        bf16* sP = smem + L::OFF_P + (it & 1) * L::SBUF;
+        const bool need_mask = (J0 + BCB > S) || (causal && (J0 + BCB - 1 > t0 + off));
+        f32x16 sacc;
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int tl = 16 * h + 8 * g;
-        const float4 d0 = *reinterpret_cast<const float4*>(&sDv[cur * BR + tl]);
-        const float4 d1 = *reinterpret_cast<const float4*>(&sDv[cur * BR + tl + 4]);
-        const float dv[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+        for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[8 * h + u] *= (pacc[8 * h + u] - dv[u]);  // dS
+        for (int kk = 0; kk < KK; ++kk) {
+          const bf16x8 aq = *reinterpret_cast<const bf16x8*>(sQ + arow + 16 * kk);
+          sacc = mfma32(aq, breg[kk], sacc);
+        }
+        float v[16];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int tl = 16 * h + 8 * g;
+          const float4 l0 = *reinterpret_cast<const float4*>(&sL[b3 * BR + tl]);
+          const float4 l1 = *reinterpret_cast<const float4*>(&sL[b3 * BR + tl + 4]);
+          const float lv[8] = {l0.x, l0.y, l0.z, l0.w, l1.x, l1.y, l1.z, l1.w};
+#pragma unroll
+          for (int u = 0; u < 8; ++u) v[8 * h + u] = fast_exp2(fmaf(sacc[8 * h + u], c, -lv[u]));
+        }
+        if (need_mask) {  // diagonal and tail tiles only (uniform branch, outside the hot path)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int t = t0 + 16 * (r >> 3) + 8 * g + (r & 7);
+            const bool vis = (jmine < S) && (!causal || jmine <= t + off);
+            v[r] = vis ? v[r] : 0.f;
+          }
+        }
+        const uint4 p0 = pack8(&v[0]), p1 = pack8(&v[8]);
+        *reinterpret_cast<uint4*>(&sP[pt_off(0)]) = p0;
+        *reinterpret_cast<uint4*>(&sP[pt_off(1)]) = p1;
+        const bf16x8 pB0 = __builtin_bit_cast(bf16x8, p0), pB1 = __builtin_bit_cast(bf16x8, p1);
+        // dVf^T += dO^T P
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const bf16x8 a0 = load_a_tr([&](int r) { return sdO + tile_row(r) * RSTR + 32 * db; }, lane);
+          const bf16x8 a1 = load_a_tr([&](int r) { return sdO + tile_row(16 + r) * RSTR + 32 * db; }, lane);
+          acc[db] = mfma32(a0, pB0, acc[db]);
+          acc[db] = mfma32(a1, pB1, acc[db]);
+        }
       }
+      if (it >= 2) dq_tile((qt0 + it - 2) * BR, it & 1);  // dS^T of tile it-2 was published in it-1
     }
-    const bf16x8 pB0 = __builtin_bit_cast(bf16x8, pack8(&v[0]));
-    const bf16x8 pB1 = __builtin_bit_cast(bf16x8, pack8(&v[8]));
-    if (roleK) {
-      // dS^T through LDS: row = slot, 32 query rows per 64-byte row.  The lane's 8 values of
-      // half h are one 16-byte chunk (logical chunk 2 h + g); chunks are rotated by (row >> 1) so
-      // that the 8 lanes of a write group hit 8 different 16-byte bank groups.
-      const int R = 32 * sw + li;
-      *reinterpret_cast<uint4*>(&sdS[R * BR + 8 * ((g + (R >> 1)) & 3)]) = __builtin_bit_cast(uint4, pB0);
-      *reinterpret_cast<uint4*>(&sdS[R * BR + 8 * ((2 + g + (R >> 1)) & 3)]) = __builtin_bit_cast(uint4, pB1);
-    }
-    // ---- role V: dVf^T += dO^T P ; role K: dKf^T += Q^T dS   (k-step = 16 query rows; A is
-    // read transposed out of the row-major tile; accumulator row m of block db = head dim 32 db + m)
-    {
-      const bf16* sA = roleK ? sQ : sdO;
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const bf16x8 a0 = load_a_tr([&](int k) { return sA + tile_row(k) * RSTR + 32 * db; }, lane);
-        const bf16x8 a1 = load_a_tr([&](int k) { return sA + tile_row(16 + k) * RSTR + 32 * db; }, lane);
-        acc[db] = mfma32(a0, pB0, acc[db]);
-        acc[db] = mfma32(a1, pB1, acc[db]);
-      }
-    }
-    if (it > 0) dq_tile(t0 - BR, cur ^ 1);  // previous tile's dS is complete since the last barrier
     __syncthreads();
+    b3 = b3 == 2 ? 0 : b3 + 1;
   }
-  if (it > 0) dq_tile((n_qt - 1) * BR, (it - 1) & 1);
 
   // ---- epilogue.  dKf^T (held by role K) then dVf^T (role V) go through LDS as f32 [slot][d] so
   // that the un-fusion (dK_l = G_l tau dKf, dV_l = G_l dVf) is written with coalesced 16-byte
@@ -612,7 +634,7 @@ hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
     Vp[l] = a.V[l] ? a.V[l] : anyV;
   }
   const int n_kvtiles = (a.S + BCB - 1) / BCB;
-  const size_t smem = (size_t)L::TOTAL * sizeof(bf16) + 4 * L::BR * sizeof(float);
+  const size_t smem = (size_t)L::TOTAL * sizeof(bf16) + 6 * L::BR * sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_main_kernel<D>),
