@@ -95,6 +95,8 @@ def test_fwd_f32_shapes(mka, oracle, d, Tq, S, causal, len3):
     (130, 333, True, None),      # cache prefix, bottom-right mask
     (200, 260, False, None),     # non-causal
     (257, 257, True, [257, 100, 0]),  # absent levels
+    (150, 150, True, None),      # three kv tiles: every stage of the tile pipeline's ramp-up
+    (40, 250, True, [250, 250, 130]),  # a level that ends in the middle of a tile
     (1, 1, True, None), (1, 70, True, None)])
 def test_fwd_bf16_shapes(mka, oracle, d, Tq, S, causal, len3):
     announce(f"fwd bf16 d={d} Tq={Tq} S={S} causal={causal} len={len3}")
@@ -218,10 +220,15 @@ def _check_bwd(mka, oracle, inp, S, len3, causal, Gprev=None, use_router=True):
     ref = oracle.bwd(inp["dO"].cpu(), inp["Q"].cpu(), cpu_list(inp["K"]), cpu_list(inp["V"]), Gref,
                      inp["W_r"].cpu() if use_router else None, len3=len3, causal=causal,
                      tau=inp["scale"])
-    errs = {"dQ": max_abs(g["dQ"], ref["dQ"])}
+    # The bound is 2e-2 at unit scale.  A gradient of magnitude m is stored in bf16 with a
+    # quantisation step of m * 2^-8, which alone exceeds 2e-2 once m > 5 (short rows with a
+    # scaled-up router reach 7 here), so the bound scales with max(1, max|ref|).
+    def scaled(x, r):
+        return max_abs(x, r) / max(1.0, float(np.abs(r).max()) if r.size else 1.0)
+    errs = {"dQ": scaled(g["dQ"], ref["dQ"])}
     for l in range(3):
-        errs[f"dK{l}"] = max_abs(g["dK"][l], ref["dK"][l])
-        errs[f"dV{l}"] = max_abs(g["dV"][l], ref["dV"][l])
+        errs[f"dK{l}"] = scaled(g["dK"][l], ref["dK"][l])
+        errs[f"dV{l}"] = scaled(g["dV"][l], ref["dV"][l])
     for k, v in errs.items():
         assert v <= BF16_ATOL, (k, v, errs)
     if use_router:
@@ -238,6 +245,7 @@ def _check_bwd(mka, oracle, inp, S, len3, causal, Gprev=None, use_router=True):
     (130, 333, True, None),          # cache prefix: only the last 130 slots have router grads
     (150, 190, False, None),         # non-causal
     (257, 257, True, [257, 100, 0]),  # absent levels: zero gradients there
+    (32, 32, True, None), (96, 96, True, None), (97, 161, True, None),  # 1, 3, 4 query tiles
     (1, 1, True, None), (64, 128, True, None)])
 def test_bwd_bf16_shapes(mka, oracle, d, Tq, S, causal, len3):
     announce(f"bwd bf16 d={d} Tq={Tq} S={S} causal={causal} len={len3}")
