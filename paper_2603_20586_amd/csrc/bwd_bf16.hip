@@ -14,13 +14,16 @@
 //   prep    D = rowsum(dO*O); zero the f32 dQ accumulator
 //   main    one workgroup owns 128 KV slots (four blocks of 32): fuses its Kf/Vf ONCE, keeps them
 //           as MFMA B operands in registers, then walks over the 32-row query tiles that can
-//           see it.  Two waves per slot block: one computes S -> P -> dVf^T += dO^T P, the other
-//           S, dP -> dS -> dKf^T += Q^T dS (A operands = Q / dO rows and transposed tiles from
-//           LDS, B = P / dS straight from the accumulator layout).  dS goes through LDS once so
-//           that dQ = dS Kf can contract over all 128 slots; dQ is accumulated in f32 with
-//           atomics.  Query tiles are double-buffered in LDS and the loop has one barrier per
-//           tile: staging of tile i+1, the MFMA work of tile i and the dQ contraction of tile
-//           i-1 share a phase.  Epilogue: un-fusion, dlam, dg through LDS, coalesced accesses.
+//           see it, three tiles in flight and one barrier per tile.  Two waves per slot block:
+//           the "V" wave computes S = Q Kf^T -> P -> dVf^T += dO^T P for tile i and hands P^T
+//           over through LDS; the "K" wave, one tile behind, computes dP = dO Vf^T,
+//           dS = P (dP - D), dKf^T += Q^T dS and publishes dS^T; the V waves then contract
+//           dQ = dS Kf over all 128 slots for tile i-2 and add it to the f32 accumulator with
+//           atomics.  Q / dO tiles are kept row-major only: the operands that contract over
+//           query rows (dO^T, Q^T) and over slots (dS) are read with transposing LDS loads.
+//           The kernel is bound by the rate of the f32 atomics (performed beyond the L2, about
+//           3.4e11 elements/s on this part), not by the matrix pipe.
+//           Epilogue: un-fusion, dlam, dg through LDS, coalesced accesses.
 //   finish  dQ = tau*acc + dg W_r^T -> bf16; per-workgroup partial sums of Q^T dg and dg
 //   reduce  fixed-order sum of the partials -> dW_r, db_r   (deterministic)
 #include "fuse_tile.h"
@@ -136,10 +139,10 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   float* sDv = sL + 3 * BR;                               // [3][BR] D
 
   // 8 waves = 2 per SIMD.  Waves 0-3 (role V) and 4-7 (role K) each own the same four blocks
-  // of 32 slots: role V computes S -> P -> dVf^T, role K computes S, dP -> dS -> dKf^T and
-  // publishes dS.  S is computed by both; in exchange a wave holds one accumulator set instead
-  // of two, which is what lets two waves share a SIMD and hide each other's LDS / MFMA latency.
-  // Role V waves also stage the next query tile and run the dQ contraction of the previous one.
+  // of 32 slots: role V computes S -> P -> dVf^T and the dQ contraction, role K (one tile
+  // behind, P^T through LDS) dP -> dS -> dKf^T, and stages the query tiles.  A wave so holds one
+  // accumulator set and one B operand instead of two, which is what lets two waves share a SIMD
+  // and hide each other's LDS / MFMA latency.
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
   const bool roleK = wave >= 4;
   const int sw = wave & 3;  // slot block of this wave

@@ -2,13 +2,16 @@
 // Eq. (1) with the scale of Eq. (3); online softmax by the max-shift recursion of the section
 // "Numerical Stability via Max-Shift", applied over KV blocks with one running max per row).
 //
-// One workgroup = 8 waves x 32 query rows = 256 rows.  KV tiles of 64 slots, double-buffered in
-// LDS, one barrier per tile:
+// One workgroup = 8 waves x 32 query rows = 256 rows; KV tiles of 64 slots; one barrier per tile.
 //   * fusion (Kf = sum_l G_l K_l, Vf likewise) happens in registers between the global load and
-//     the LDS write: raw 16-byte chunks of the three levels are prefetched one tile ahead, mixed
-//     in f32, rounded once to bf16; the fused stream exists only in LDS.  Waves 0-3 fuse the K
-//     half of a tile AFTER their MFMA work, waves 4-7 fuse the V half BEFORE theirs, so that on
-//     each SIMD one wave's VALU work runs beside the other wave's MFMAs.
+//     the LDS write: raw 16-byte chunks of the three levels are loaded half a tile ahead, mixed
+//     in f32, rounded once to bf16; the fused stream exists only in LDS.  Waves 0-3 stage the K
+//     half of every tile, waves 4-7 the V half, in half slices issued behind every MFMA of the
+//     wave's own work (the kernel is bound by VALU issue: fusion, exponentials and conversions
+//     cost more issue cycles than the MFMAs they feed, so none of them may wait for another).
+//   * the work of a wave is software-pipelined over units of 32 slots: the S^T MFMAs of the next
+//     unit are issued between the exponentials of the current one; the barrier that publishes
+//     tile t+1 sits between the two units of tile t (two Kf buffers, three Vf^T buffers).
 //   * S^T = Kf Q^T (slots x rows) with 32x32x16 MFMAs: A = Kf rows from LDS, B = Q^T held in
 //     registers for the whole kernel.  In the accumulator layout a lane owns ONE query row
 //     (column l%32) and 16 of the 32 slots, so row max and row sum are in-lane reductions plus a
@@ -428,7 +431,6 @@ __global__ __launch_bounds__(FW_NW * 64, 1) void fwd_bf16_kernel(
     const bf16* __restrict__ V2, const float* __restrict__ G, bf16* __restrict__ O,
     float* __restrict__ LSE, int Tq, int S, int len0, int len1, int len2, int causal, float c,
     float tau, int n_qtiles, int BH, int interleave) {
-  using L = FwdSmem<D>;
   constexpr int BR = FW_NW * 32, BC = FW_BC;
   constexpr int KK = D / 16, DB = D / 32;
   extern __shared__ __attribute__((aligned(16))) unsigned char fw_smem_raw[];
@@ -532,8 +534,9 @@ static hipError_t launch_fwd_t(const FwdArgs& a, const void* const Kp[3], const 
   constexpr int BR = FW_NW * 32;
   const int n_qtiles = (a.Tq + BR - 1) / BR;
   const long nblocks = (long)n_qtiles * ((a.BH + 7) / 8) * 8;
-  // at most 4 workgroups per compute unit (256 CUs): the causal tail dominates, interleave heads
-  const int interleave = nblocks <= 4 * 256 ? 1 : 0;
+  // at most 2 workgroups per compute unit (256 CUs): the causal tail dominates, interleave heads
+  // (beyond that the heads' K/V streams evict each other from the L2 and HBM reads triple)
+  const int interleave = nblocks <= 2 * 256 ? 1 : 0;
   const size_t smem = (size_t)FwdSmem<D>::TOTAL * sizeof(bf16);
   static bool attr_set = false;
   if (!attr_set) {
