@@ -14,6 +14,8 @@
 //   combine  merges the partials of each (b,h) and writes O (and LSE).
 // The split kernel is bound by HBM bandwidth: per slot it reads 6 rows of d elements plus
 // 12 bytes of gates and does about 6 d fused multiply-adds.
+#include <type_traits>
+
 #include "mka_dev.h"
 #include "mka_internal.h"
 
@@ -44,15 +46,12 @@ struct Chunk;  // 16 bytes of a row, widened to f32
 template <>
 struct Chunk<bf16> {
   static constexpr int N = 8;
-  static __device__ __forceinline__ void load(const bf16* p, float* f) {
-    unpack8(load16_stream(p), f);
-  }
+  static __device__ __forceinline__ void unpack(const uint4& v, float* f) { unpack8(v, f); }
 };
 template <>
 struct Chunk<float> {
   static constexpr int N = 4;
-  static __device__ __forceinline__ void load(const float* p, float* f) {
-    const uint4 v = load16_stream(p);
+  static __device__ __forceinline__ void unpack(const uint4& v, float* f) {
     f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
     f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
   }
@@ -136,13 +135,15 @@ __global__ __launch_bounds__(256) void decode_split_kernel(
 #pragma unroll
     for (int e = 0; e < EPL; ++e) qf[e] = t[e] * c;
   }
-  const T* k0 = K0 ? K0 + bh * (long)cap0 * D + cl * EPL : nullptr;
-  const T* k1 = K1 ? K1 + bh * (long)cap1 * D + cl * EPL : nullptr;
-  const T* k2 = K2 ? K2 + bh * (long)cap2 * D + cl * EPL : nullptr;
-  const T* v0 = V0 ? V0 + bh * (long)cap0 * D + cl * EPL : nullptr;
-  const T* v1 = V1 ? V1 + bh * (long)cap1 * D + cl * EPL : nullptr;
-  const T* v2 = V2 ? V2 + bh * (long)cap2 * D + cl * EPL : nullptr;
-  const float* gp = Gc + bh * (long)capG * 3;
+  // K0..V2 are never null here (a level without memory arrives as another level's buffer with
+  // length 0, see the launcher); everything below the per-(b,h) base is a 32-bit byte offset
+  const char* k0 = reinterpret_cast<const char*>(K0 + bh * (long)cap0 * D + cl * EPL);
+  const char* k1 = reinterpret_cast<const char*>(K1 + bh * (long)cap1 * D + cl * EPL);
+  const char* k2 = reinterpret_cast<const char*>(K2 + bh * (long)cap2 * D + cl * EPL);
+  const char* v0 = reinterpret_cast<const char*>(V0 + bh * (long)cap0 * D + cl * EPL);
+  const char* v1 = reinterpret_cast<const char*>(V1 + bh * (long)cap1 * D + cl * EPL);
+  const char* v2 = reinterpret_cast<const char*>(V2 + bh * (long)cap2 * D + cl * EPL);
+  const char* gp = reinterpret_cast<const char*>(Gc + bh * (long)capG * 3);
 
   float m = -INFINITY, z = 0.f;
   float acc[EPL];
@@ -150,36 +151,56 @@ __global__ __launch_bounds__(256) void decode_split_kernel(
   for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
 
   constexpr int STEP = NWV * SPI;  // slots covered by the workgroup per sub-step
-  for (int jb = j_lo + wave * SPI + sub; jb < j_hi; jb += STEP * U) {
-    float s[U], g[U][3];
-    float vv[U][3][EPL];
+  const int lenmin = min(len0, min(len1, len2));
+  // One trip = U sub-steps.  All 6 U raw 16-byte loads of the trip (and the gates) are issued
+  // before the first use, unconditionally: an absent entry reads slot 0 of the same (b,h)
+  // instead and its bits are replaced by zero (never multiplied by a zero gate, so stale NaN /
+  // Inf bits in unused cache rows cannot leak).  FULL = every slot of the trip exists at every
+  // level: no predicates at all.
+  auto trip = [&](int base, auto full_c) __attribute__((always_inline)) {
+    constexpr bool FULL = decltype(full_c)::value;
+    uint4 rk[U][3], rv[U][3];
+    float g[U][3];
+    bool ok[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int j = jb + u * STEP;
-      const bool ok = j < j_hi;
-      const bool p0 = ok && j < len0, p1 = ok && j < len1, p2 = ok && j < len2;
-      g[u][0] = p0 ? gp[j * 3 + 0] : 0.f;
-      g[u][1] = p1 ? gp[j * 3 + 1] : 0.f;
-      g[u][2] = p2 ? gp[j * 3 + 2] : 0.f;
-      float kk[3][EPL];
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) {
-        kk[0][e] = kk[1][e] = kk[2][e] = 0.f;
-        vv[u][0][e] = vv[u][1][e] = vv[u][2][e] = 0.f;
+      const int j = base + u * STEP + wave * SPI + sub;
+      ok[u] = FULL || j < j_hi;
+      const bool p0 = FULL || (ok[u] && j < len0), p1 = FULL || (ok[u] && j < len1),
+                 p2 = FULL || (ok[u] && j < len2);
+      const unsigned rowb = (unsigned)j * (unsigned)(D * sizeof(T));
+      rk[u][0] = load16_stream(k0 + (p0 ? rowb : 0u));
+      rk[u][1] = load16_stream(k1 + (p1 ? rowb : 0u));
+      rk[u][2] = load16_stream(k2 + (p2 ? rowb : 0u));
+      rv[u][0] = load16_stream(v0 + (p0 ? rowb : 0u));
+      rv[u][1] = load16_stream(v1 + (p1 ? rowb : 0u));
+      rv[u][2] = load16_stream(v2 + (p2 ? rowb : 0u));
+      const char* gj = gp + (ok[u] ? (unsigned)j * 12u : 0u);
+      g[u][0] = *reinterpret_cast<const float*>(gj);
+      g[u][1] = *reinterpret_cast<const float*>(gj + 4);
+      g[u][2] = *reinterpret_cast<const float*>(gj + 8);
+      if (!FULL) {
+        const uint4 zero = make_uint4(0, 0, 0, 0);
+        if (!p0) { rk[u][0] = zero; rv[u][0] = zero; g[u][0] = 0.f; }
+        if (!p1) { rk[u][1] = zero; rv[u][1] = zero; g[u][1] = 0.f; }
+        if (!p2) { rk[u][2] = zero; rv[u][2] = zero; g[u][2] = 0.f; }
       }
-      if (p0) { Chunk<T>::load(k0 + (long)j * D, kk[0]); Chunk<T>::load(v0 + (long)j * D, vv[u][0]); }
-      if (p1) { Chunk<T>::load(k1 + (long)j * D, kk[1]); Chunk<T>::load(v1 + (long)j * D, vv[u][1]); }
-      if (p2) { Chunk<T>::load(k2 + (long)j * D, kk[2]); Chunk<T>::load(v2 + (long)j * D, vv[u][2]); }
-      float d0 = 0.f, d1 = 0.f, d2 = 0.f;
+    }
+    float s[U];
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) {
-        d0 = fmaf(qf[e], kk[0][e], d0);
-        d1 = fmaf(qf[e], kk[1][e], d1);
-        d2 = fmaf(qf[e], kk[2][e], d2);
+    for (int u = 0; u < U; ++u) {
+      float d[3];
+#pragma unroll
+      for (int l = 0; l < 3; ++l) {
+        float kk[EPL];
+        Chunk<T>::unpack(rk[u][l], kk);
+        d[l] = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) d[l] = fmaf(qf[e], kk[e], d[l]);
       }
-      const float part = fmaf(g[u][0], d0, fmaf(g[u][1], d1, g[u][2] * d2));
+      const float part = fmaf(g[u][0], d[0], fmaf(g[u][1], d[1], g[u][2] * d[2]));
       const float tot = row_sum<LPR>(part);
-      s[u] = ok ? tot : -INFINITY;
+      s[u] = ok[u] ? tot : -INFINITY;
     }
     float mx = s[0];
 #pragma unroll
@@ -194,12 +215,20 @@ __global__ __launch_bounds__(256) void decode_split_kernel(
     for (int u = 0; u < U; ++u) {
       const float p = fast_exp2(s[u] - mref);
       z += p;
-      const float w0 = p * g[u][0], w1 = p * g[u][1], w2 = p * g[u][2];
 #pragma unroll
-      for (int e = 0; e < EPL; ++e)
-        acc[e] = fmaf(w0, vv[u][0][e], fmaf(w1, vv[u][1][e], fmaf(w2, vv[u][2][e], acc[e])));
+      for (int l = 0; l < 3; ++l) {
+        const float w = p * g[u][l];
+        float vv[EPL];
+        Chunk<T>::unpack(rv[u][l], vv);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] = fmaf(w, vv[e], acc[e]);
+      }
     }
     m = m_new;
+  };
+  for (int base = j_lo; base < j_hi; base += STEP * U) {
+    if (base + STEP * U <= j_hi && base + STEP * U <= lenmin) trip(base, std::true_type{});
+    else trip(base, std::false_type{});
   }
 
   // merge the SPI lane groups of the wave (same column chunk, different slots)
@@ -276,16 +305,29 @@ hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t st) {
                      a.j_new);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  // a level without memory borrows another level's buffer (and capacity) and has length 0: the
+  // kernel then never uses what it reads from it
+  const void* Kp[3];
+  const void* Vp[3];
+  int capp[3];
+  int any = a.Kc[0] ? 0 : (a.Kc[1] ? 1 : 2);
+  if (!a.Kc[any] || !a.Vc[any]) return hipErrorInvalidValue;
+  for (int l = 0; l < 3; ++l) {
+    const bool has = a.Kc[l] && a.Vc[l];
+    Kp[l] = has ? a.Kc[l] : a.Kc[any];
+    Vp[l] = has ? a.Vc[l] : a.Vc[any];
+    capp[l] = has ? a.cap[l] : a.cap[any];
+  }
   constexpr int EPL = Chunk<T>::N, LPR = D / EPL, SPI = 64 / LPR, U = 4;
   constexpr int GRAN = 4 * SPI * U;  // slots the workgroup covers per loop trip
   int chunk = (a.S + a.n_splits - 1) / a.n_splits;
   chunk = (chunk + GRAN - 1) / GRAN * GRAN;
   const float c = a.scale * kLog2e;
   hipLaunchKernelGGL((decode_split_kernel<T, D, U>), dim3(a.n_splits, a.BH), dim3(256), 0, st,
-                     (const T*)a.q, (const T*)a.Kc[0], (const T*)a.Kc[1], (const T*)a.Kc[2],
-                     (const T*)a.Vc[0], (const T*)a.Vc[1], (const T*)a.Vc[2], a.Gc, a.partial,
-                     a.S, a.len[0], a.len[1], a.len[2], a.cap[0], a.cap[1], a.cap[2], a.capG,
-                     chunk, c);
+                     (const T*)a.q, (const T*)Kp[0], (const T*)Kp[1], (const T*)Kp[2],
+                     (const T*)Vp[0], (const T*)Vp[1], (const T*)Vp[2], a.Gc, a.partial,
+                     a.S, a.Kc[0] && a.Vc[0] ? a.len[0] : 0, a.Kc[1] && a.Vc[1] ? a.len[1] : 0,
+                     a.Kc[2] && a.Vc[2] ? a.len[2] : 0, capp[0], capp[1], capp[2], a.capG, chunk, c);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(a.BH), dim3(D), 0, st, a.partial,

@@ -2,7 +2,10 @@
 
     python -m paper_2603_20586_amd.prof_summary stats  <kernel_stats.csv>  <out.txt>  "<command>"
     python -m paper_2603_20586_amd.prof_summary pmc    <counter_collection.csv> <out.txt> "<command>"
+    python -m paper_2603_20586_amd.prof_summary traffic <fetch_summary.txt> <write_summary.txt> <traffic.json>
 
+`traffic`: scaled FETCH_SIZE + WRITE_SIZE of the dominant kernel of each roofline line of
+`bench.py` (picked by kernel name and workgroup count) -> HBM bytes per launch, as JSON.
 `stats`: per-kernel calls / average / total time.  `pmc`: per-kernel average of every counter in
 the file; for FETCH_SIZE / WRITE_SIZE (KiB per dispatch) it also prints the value scaled by what
 the same counter reads for the 1 GiB calibration copy that `bench.py --calibrate-copy` runs
@@ -72,7 +75,37 @@ def pmc(src, dst, cmd):
     open(dst, "w").write("\n".join(out) + "\n")
 
 
+# roofline key of bench.py -> (kernel, workgroups of its launch at that workload)
+TRAFFIC_KEYS = {
+    "C2_fwd": ("mka::fwd_bf16_kernel<128>", 512),       # 64 heads x 8 query tiles
+    "C3_fwd": ("mka::fwd_bf16_kernel<128>", 1024),      # 32 heads x 32 query tiles
+    "C2_bwd": ("mka::bwd_main_kernel<128>", 1024),      # 64 heads x 16 KV tiles
+    "C5_bwd": ("mka::bwd_main_kernel<128>", 4096),      # 128 heads x 32 KV tiles
+    "C4_decode": ("mka::decode_split_kernel<bf32,16,128>", 2048),  # 4 splits x 512 heads
+}
+
+
+def traffic(fetch_txt, write_txt, dst):
+    import json
+
+    def scaled(path):
+        out = {}
+        for line in open(path):
+            f = [x.strip() for x in line.split("|")]
+            if len(f) == 6 and f[5] and not line.startswith("#"):
+                out[(f[0], int(f[1]))] = float(f[5]) * 1e6  # scaled_MB -> bytes
+        return out
+
+    rd, wr = scaled(fetch_txt), scaled(write_txt)
+    res = {k: int(rd[v] + wr[v]) for k, v in TRAFFIC_KEYS.items() if v in rd and v in wr}
+    json.dump(res, open(dst, "w"), indent=1, sort_keys=True)
+    print(json.dumps(res, indent=1, sort_keys=True))
+
+
 if __name__ == "__main__":
-    mode, src, dst, cmd = sys.argv[1], sys.argv[2], sys.argv[3], sys.argv[4]
-    (stats if mode == "stats" else pmc)(src, dst, cmd)
-    print(open(dst).read())
+    if sys.argv[1] == "traffic":
+        traffic(sys.argv[2], sys.argv[3], sys.argv[4])
+    else:
+        mode, src, dst, cmd = sys.argv[1], sys.argv[2], sys.argv[3], sys.argv[4]
+        (stats if mode == "stats" else pmc)(src, dst, cmd)
+        print(open(dst).read())
