@@ -458,6 +458,22 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
         }
     }
     __syncthreads();
+    // all raw K_l / V_l chunks and gates of the thread's items first (unconditional loads: an
+    // absent entry reads row 0 of the (b,h) block and is not used), then the arithmetic
+    uint4 raw[NITEM][3];
+    float gl[NITEM][3];
+#pragma unroll
+    for (int i = 0; i < NITEM; ++i) {
+      const int j = J0 + erow0 + ERS * i;
+      const int jc = j < S ? j : S - 1;
+#pragma unroll
+      for (int l = 0; l < 3; ++l) {
+        const bool present = j < S && j < len[l];
+        const bf16* src = pass == 0 ? Kp[l] : Vp[l];
+        raw[i][l] = *reinterpret_cast<const uint4*>(src + kvbase + (present ? (long)j * D : 0) + ecc * 8);
+        gl[i][l] = Gb[jc * 3 + l];
+      }
+    }
 #pragma unroll
     for (int i = 0; i < NITEM; ++i) {
       const int sl = erow0 + ERS * i;
@@ -470,17 +486,17 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
 #pragma unroll
         for (int l = 0; l < 3; ++l) {
           const bool present = j < len[l];
-          const float gl = present ? Gb[j * 3 + l] : 0.f;
+          const float g_l = present ? gl[i][l] : 0.f;
           bf16* dst = pass == 0 ? dKp[l] : dVp[l];
           if (dst) {
             float o8[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o8[e] = gl * v[e];
+            for (int e = 0; e < 8; ++e) o8[e] = g_l * v[e];
             *reinterpret_cast<uint4*>(dst + o) = pack8(o8);
           }
           if (present) {
             float x[8];
-            unpack8(*reinterpret_cast<const uint4*>((pass == 0 ? Kp[l] : Vp[l]) + o), x);
+            unpack8(raw[i][l], x);
             float a = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) a = fmaf(v[e], x[e], a);
