@@ -90,17 +90,12 @@ __global__ __launch_bounds__(64) void decode_append_kernel(
   }
   __syncthreads();
   if (lane == 0) {
-    const double g0 = sg[0], g1 = sg[1], g2 = sg[2];
-    int best = 0;
-    double gm = g0;
-    if (g1 > gm) { gm = g1; best = 1; }
-    if (g2 > gm) { gm = g2; best = 2; }
-    const double e0 = exp(g0 - gm), e1 = exp(g1 - gm), e2 = exp(g2 - gm);
-    const double inv = 1.0 / (e0 + e1 + e2);
+    float lam[3];
+    const int best = gates_from_logits(sg[0], sg[1], sg[2], lam);
     float* out = Gc + (bh * capG + j_new) * 3;
-    out[0] = (float)(e0 * inv);
-    out[1] = (float)(e1 * inv);
-    out[2] = (float)(e2 * inv);
+    out[0] = lam[0];
+    out[1] = lam[1];
+    out[2] = lam[2];
     if (idx) idx[bh] = best;
   }
 }

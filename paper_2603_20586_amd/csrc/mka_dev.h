@@ -43,6 +43,24 @@ __device__ __forceinline__ uint4 pack8(const float* f) {
   return u;
 }
 
+// Gates and routing index from the three fp64 router logits (Alg. 2 step 5: softmax over the
+// levels; index = smallest level that attains the maximum).  The differences to the maximum are
+// formed in fp64, the exponentials and the normalisation in f32: gates are stored as f32 and
+// hold to about 2e-7 of the fp64 value.  Shared by the router and the decode append kernel so
+// that a token's gate is the same bits whichever of them produced it.
+__device__ __forceinline__ int gates_from_logits(double g0, double g1, double g2, float* lam) {
+  int best = 0;
+  double gm = g0;
+  if (g1 > gm) { gm = g1; best = 1; }
+  if (g2 > gm) { gm = g2; best = 2; }
+  const float e0 = expf((float)(g0 - gm)), e1 = expf((float)(g1 - gm)), e2 = expf((float)(g2 - gm));
+  const float inv = 1.0f / (e0 + e1 + e2);
+  lam[0] = e0 * inv;
+  lam[1] = e1 * inv;
+  lam[2] = e2 * inv;
+  return best;
+}
+
 // 16-byte streaming load (data that is read exactly once).
 __device__ __forceinline__ uint4 load16_stream(const void* p) {
   const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));

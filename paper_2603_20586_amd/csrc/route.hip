@@ -61,20 +61,16 @@ __global__ __launch_bounds__(64) void route_kernel(const T* __restrict__ Q,
       g2 = fma(q, sw[k * 3 + 2], g2);
     }
   }
-  int best = 0;
-  double gm = g0;
-  if (g1 > gm) { gm = g1; best = 1; }
-  if (g2 > gm) { gm = g2; best = 2; }
+  float lam[3];
+  const int best = gates_from_logits(g0, g1, g2, lam);
   if (idx) idx[row] = best;
   if (G) {
-    const double e0 = exp(g0 - gm), e1 = exp(g1 - gm), e2 = exp(g2 - gm);
-    const double inv = 1.0 / (e0 + e1 + e2);
     const long bh = row / Tq;
     const int t = (int)(row - bh * Tq);
     float* out = G + (bh * S + (S - Tq) + t) * 3;
-    out[0] = (float)(e0 * inv);
-    out[1] = (float)(e1 * inv);
-    out[2] = (float)(e2 * inv);
+    out[0] = lam[0];
+    out[1] = lam[1];
+    out[2] = lam[2];
   }
 }
 
