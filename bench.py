@@ -263,6 +263,30 @@ def main():
         del cc, ws4
         torch.cuda.empty_cache()
 
+    # ------------------------------------------------------------------ measured ceilings
+    # a pure MFMA loop and a streaming read, written in this library: what the part sustains,
+    # to quote beside the vendor peaks (`frac_of_ceiling` in every roofline line)
+    ceilings = None
+    if not args.quick:
+        cbuf = torch.empty(1 << 32, dtype=torch.int32, device=dev).fill_(1)  # 16 GiB
+        ms_r = time_region(lambda: mka.mka_ceiling_read(cbuf), 5, 2)
+        cout = torch.empty(2048 * 512, dtype=torch.float32, device=dev)
+        fl = [0.0]
+
+        def run_mfma():
+            fl[0] = mka.mka_ceiling_mfma(cout, 2048, 2000)
+        ms_m = time_region(run_mfma, 5, 2)
+        ceilings = {"mfma_bf16_tflops": fl[0] / ms_m / 1e9,
+                    "hbm_read_gbps": cbuf.numel() * 4 / ms_r / 1e6,
+                    "how": "mka_ceiling_mfma: 2048 workgroups x 8 waves x 8000 independent "
+                           "32x32x16 bf16 MFMAs; mka_ceiling_read: 16 GiB, 16-byte non-temporal loads, 8 per lane in "
+                           "flight (a plain loop: a tuned kernel can sit a few % above it)"}
+        for r in rooflines.values():
+            top = ceilings["mfma_bf16_tflops"] if r["bound"] == "mfma" else ceilings["hbm_read_gbps"]
+            r["frac_of_ceiling"] = r["achieved"] / top
+        del cout, cbuf
+        torch.cuda.empty_cache()
+
     if args.calibrate_copy:
         # plain copy of known size: reads 1 GiB, writes 1 GiB (scales rocprofv3 FETCH/WRITE_SIZE)
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -319,7 +343,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "C2 prefill shape B=4 H=16 d=128 T=2048 causal bf16: "
                                "fwd + bwd + one decode step per step"},
-        "roofline": roofline, "cpu_baseline": cpu_baseline, "phases": phases,
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "ceilings": ceilings, "phases": phases,
         "rooflines": rooflines, "workloads": workloads,
     }
     print(json.dumps(out))

@@ -150,6 +150,21 @@ mka_status mka_fused_attn_bwd(const void* dO, const void* Q, const void* const K
                               void* const dV[3], float* dW_r, float* db_r, const mka_shape* shape,
                               void* workspace, size_t workspace_bytes, void* stream);
 
+/* Measurement helpers (not part of the method): the ceilings that the rooflines of the
+ * attention kernels are quoted against besides the vendor peaks.
+ *
+ * mka_ceiling_mfma: `workgroups` x 8 waves each issue 4 * iters independent 32x32x16 bf16 MFMAs
+ *   (no memory traffic); `out` (device, workgroups * 512 floats) receives a checksum; *flops
+ *   (host, nullable) the number of floating-point operations of the launch.
+ * mka_ceiling_read: streams `bytes` (device, 16-byte aligned, at least 32 KiB) once with
+ *   16-byte non-temporal loads; `out` (device, nullable) is only written in the practically
+ *   impossible case that the xor of all words equals a magic constant.
+ * Both enqueue on `stream` and return; the caller times them.  Errors: MKA_ERR_SHAPE for
+ * non-positive sizes or null buffers, MKA_ERR_ALIGN, MKA_ERR_LAUNCH. */
+mka_status mka_ceiling_mfma(float* out, int32_t workgroups, int32_t iters, double* flops,
+                            void* stream);
+mka_status mka_ceiling_read(const void* src, size_t bytes, uint32_t* out, void* stream);
+
 /* Static, human-readable name of a status. */
 const char* mka_status_string(mka_status status);
 

@@ -64,6 +64,10 @@ def lib() -> ctypes.CDLL:
                                             POINTER(_P3), c_void_p, POINTER(c_int32 * 3),
                                             c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                             POINTER(MkaDecodeShape), c_void_p, c_size_t, c_void_p]
+        L.mka_ceiling_mfma.restype = ctypes.c_int
+        L.mka_ceiling_mfma.argtypes = [c_void_p, c_int32, c_int32, POINTER(ctypes.c_double), c_void_p]
+        L.mka_ceiling_read.restype = ctypes.c_int
+        L.mka_ceiling_read.argtypes = [c_void_p, c_size_t, c_void_p, c_void_p]
         L.mka_fused_attn_bwd.restype = ctypes.c_int
         L.mka_fused_attn_bwd.argtypes = [c_void_p, c_void_p, POINTER(_P3), POINTER(_P3), c_void_p,
                                          c_void_p, c_void_p, c_void_p, c_void_p, POINTER(_P3),
@@ -234,3 +238,20 @@ def mka_fused_attn_bwd(dO, Q, K, V, G, O, LSE, W_r=None, len3=None, causal=True,
                                     ctypes.byref(s), _ptr(workspace), workspace.numel(),
                                     _stream()), "mka_fused_attn_bwd")
     return dict(dQ=dQ, dK=dK, dV=dV, dW_r=dW, db_r=db)
+
+
+def mka_ceiling_mfma(out, workgroups: int, iters: int) -> float:
+    """Enqueue the pure-MFMA loop (include/mka.h); returns the flops of the launch."""
+    _dev_check(out)
+    fl = ctypes.c_double(0.0)
+    _check(lib().mka_ceiling_mfma(_ptr(out), workgroups, iters, ctypes.byref(fl), _stream()),
+           "mka_ceiling_mfma")
+    return fl.value
+
+
+def mka_ceiling_read(src, out=None) -> int:
+    """Enqueue the streaming read of `src` (include/mka.h); returns the bytes it reads."""
+    _dev_check(src, out)
+    nbytes = src.numel() * src.element_size()
+    _check(lib().mka_ceiling_read(_ptr(src), nbytes, _ptr(out), _stream()), "mka_ceiling_read")
+    return nbytes

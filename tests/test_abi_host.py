@@ -132,3 +132,14 @@ def test_decode_rejects_bad_arguments(m):
     assert call(d=100)[0] == 6
     rc, ln = call(dtype=9)
     assert rc == 3 and ln == [8, 8, 8]                    # lengths untouched on error
+
+
+def test_ceiling_helpers_reject_bad_arguments_on_the_host(m):
+    import ctypes
+    L = m.lib()
+    assert L.mka_ceiling_mfma(None, 4, 10, None, None) == 2      # no output buffer
+    assert L.mka_ceiling_mfma(ctypes.c_void_p(256), 0, 10, None, None) == 2
+    assert L.mka_ceiling_mfma(ctypes.c_void_p(256), 4, 0, None, None) == 2
+    assert L.mka_ceiling_read(None, 1 << 20, None, None) == 2
+    assert L.mka_ceiling_read(ctypes.c_void_p(4096), 64, None, None) == 2   # too small
+    assert L.mka_ceiling_read(ctypes.c_void_p(4100), 1 << 20, None, None) == 4  # misaligned
