@@ -106,6 +106,24 @@ def attn_fwd(Q, Kf, Vf, causal=True, tau=1.0, return_p=False):
     return (O, LSE, P) if return_p else (O, LSE)
 
 
+def mixture_fwd(Q, K, V, lam=None, causal=True, tau=1.0):
+    """Gated mixture of exponentiated scores over up to three memories of their own lengths
+    (entries of K/V may be None).  lam [B,H,Tq,3] per QUERY row, or None for all ones.
+    Returns (O, LSE)."""
+    Q = f64(Q)
+    B, H, Tq, d = Q.shape
+    Ks = [None if k is None else f64(k) for k in K]
+    Vs = [None if v is None else f64(v) for v in V]
+    S = (ctypes.c_int * 3)(*[0 if k is None else k.shape[2] for k in Ks])
+    lam = None if lam is None else f64(lam)
+    O = np.empty((B, H, Tq, d))
+    LSE = np.empty((B, H, Tq))
+    lib().mka_oracle_mixture_fwd(_p(Q), _p(Ks[0]), _p(Ks[1]), _p(Ks[2]), _p(Vs[0]), _p(Vs[1]),
+                                 _p(Vs[2]), _p(lam), B, H, Tq, S, d, int(bool(causal)),
+                                 ctypes.c_double(tau), _p(O), _p(LSE))
+    return O, LSE
+
+
 def attn_fwd_blockwise(Q, Kf, Vf, Bc, causal=True, tau=1.0):
     """Same result through the max-shift recursion over KV blocks of Bc slots."""
     Q, Kf, Vf = f64(Q), f64(Kf), f64(Vf)

@@ -156,6 +156,68 @@ void mka_oracle_attn_fwd(const double* Q, const double* Kf, const double* Vf, in
   }
 }
 
+/* ---- gated mixture of exponentiated scores over the three memories -------
+ * (paper: section "Theoretical Formulation: Recursive MKA with Online Softmax",
+ * first equation and Theorem "Recursive MKA Computes Gated Mixture Attention"):
+ *
+ *   O[t] = sum_l lam[t,l] sum_j exp(s_l[t,j]) V_l[j]  /  sum_l lam[t,l] sum_j exp(s_l[t,j])
+ *
+ * with s_l[t,j] = tau Q[t].K_l[j], the gate indexed by the QUERY row, one
+ * normalisation after the mix.  Written out directly: a first pass finds the
+ * largest exponent of the row over the levels with a positive gate (only to
+ * keep exp() in range; the quotient does not depend on it), a second pass
+ * accumulates numerator and denominator.  Level l has S[l] slots (0 = absent)
+ * and its own bottom-right aligned causal mask.  lam == NULL means lam = 1 for
+ * every level (softmax attention over the concatenation of the memories).
+ * LSE[t] = log of the denominator.  Rows that see nothing give O = 0, LSE = -inf. */
+void mka_oracle_mixture_fwd(const double* Q, const double* K1, const double* K2, const double* K3,
+                            const double* V1, const double* V2, const double* V3,
+                            const double* lam, int B, int H, int Tq, const int* S, int d,
+                            int causal, double tau, double* O, double* LSE) {
+  const double* K[3] = {K1, K2, K3};
+  const double* V[3] = {V1, V2, V3};
+  long n = (long)B * H;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (long bh = 0; bh < n; ++bh) {
+    for (int t = 0; t < Tq; ++t) {
+      const double* q = Q + ((size_t)bh * Tq + t) * d;
+      const double* lt = lam ? lam + ((size_t)bh * Tq + t) * 3 : NULL;
+      double m = -INFINITY;
+      for (int l = 0; l < 3; ++l) {
+        if (!K[l] || S[l] <= 0 || (lt && !(lt[l] > 0.0))) continue;
+        int nv = visible_upto(t, Tq, S[l], causal);
+        for (int j = 0; j < nv; ++j) {
+          const double* kr = K[l] + ((size_t)bh * S[l] + j) * d;
+          double acc = 0.0;
+          for (int k = 0; k < d; ++k) acc += q[k] * kr[k];
+          if (tau * acc > m) m = tau * acc;
+        }
+      }
+      double* o = O + ((size_t)bh * Tq + t) * d;
+      for (int k = 0; k < d; ++k) o[k] = 0.0;
+      double z = 0.0;
+      if (m > -INFINITY) {
+        for (int l = 0; l < 3; ++l) {
+          if (!K[l] || S[l] <= 0 || (lt && !(lt[l] > 0.0))) continue;
+          double w = lt ? lt[l] : 1.0;
+          int nv = visible_upto(t, Tq, S[l], causal);
+          for (int j = 0; j < nv; ++j) {
+            const double* kr = K[l] + ((size_t)bh * S[l] + j) * d;
+            const double* vr = V[l] + ((size_t)bh * S[l] + j) * d;
+            double acc = 0.0;
+            for (int k = 0; k < d; ++k) acc += q[k] * kr[k];
+            double e = w * exp(tau * acc - m);
+            z += e;
+            for (int k = 0; k < d; ++k) o[k] += e * vr[k];
+          }
+        }
+        for (int k = 0; k < d; ++k) o[k] /= z;
+      }
+      if (LSE) LSE[(size_t)bh * Tq + t] = (z > 0.0) ? m + log(z) : -INFINITY;
+    }
+  }
+}
+
 /* ---- attention by the max-shift recursion over KV blocks of Bc slots ------
  * ("Numerical Stability via Max-Shift": running max mu, normaliser z and
  * numerator alpha, both rescaled by exp(mu_old - mu_new) before a block is
