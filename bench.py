@@ -196,6 +196,16 @@ def main():
         workloads["C3_prefill_fwd"] = {"ms": ms3, "tflops": fl3 / ms3 / 1e9,
                                        "tokens_per_s": B3 * T3 / (ms3 * 1e-3)}
         rooflines["C3_fwd"] = roof_mfma(fl3, ms3, "fwd_bf16_kernel")
+        # the same shape through the per-query gated mixture over the three memories (3x the
+        # pairs) and through plain attention over one memory (what a pre-fused stream would cost)
+        msm = time_region(lambda: mka.mka_mixture_attn_fwd(
+            inp3["Q"], inp3["K"], inp3["V"], G3, causal=True, scale=inp3["scale"], O=O3, LSE=L3), 5, 2)
+        msp = time_region(lambda: mka.mka_mixture_attn_fwd(
+            inp3["Q"], [inp3["K"][0], None, None], [inp3["V"][0], None, None], None, causal=True,
+            scale=inp3["scale"], O=O3, LSE=L3), 5, 2)
+        workloads["C3_gated_mixture_fwd"] = {"ms": msm, "tflops": 3 * fl3 / msm / 1e9}
+        workloads["C3_plain_attention_fwd"] = {"ms": msp, "tflops": fl3 / msp / 1e9}
+        rooflines["C3_mixture"] = roof_mfma(3 * fl3, msm, "mix_bf16_kernel")
         del inp3, G3, O3, L3
 
         # C5: training forward + backward

@@ -150,6 +150,27 @@ mka_status mka_fused_attn_bwd(const void* dO, const void* Q, const void* const K
                               void* const dV[3], float* dW_r, float* db_r, const mka_shape* shape,
                               void* workspace, size_t workspace_bytes, void* stream);
 
+/* Gated mixture of exponentiated scores over up to three memories (paper: section "Theoretical
+ * Formulation: Recursive MKA with Online Softmax", first equation, evaluated with the max-shift
+ * recursion of that section) - the per-QUERY-gate formulation, a different function from the
+ * route-fused path above:
+ *
+ *   O[t] = sum_l G[t,l] sum_j exp(scale Q[t].K_l[j]) V_l[j] / sum_l G[t,l] sum_j exp(scale Q[t].K_l[j])
+ *
+ * Q, O [B,H,Tq,d]; K[l], V[l] [B,H,len[l],d] (device, bf16, 16-byte aligned; a NULL entry or
+ * len[l] == 0 means the memory is absent; the memories need not have equal lengths; shape->S is
+ * not read); G [B,H,Tq,3] f32 gates of the query rows (e.g. from mka_route with S = Tq), or NULL
+ * for all ones = softmax attention over the concatenation of the memories (with one memory:
+ * plain attention, the kernel for a pre-fused K/V stream).  LSE [B,H,Tq] f32 (nullable) = log of
+ * the denominator.  causal: every memory has its own bottom-right aligned mask (row t sees
+ * slots j <= t + len[l] - Tq), which requires len[l] >= Tq (else MKA_ERR_SHAPE).  Rows that see
+ * nothing (all visible memories gated off) give O = 0, LSE = -inf.  bf16 only
+ * (MKA_ERR_UNSUPPORTED otherwise), d in {64, 128}.  Enqueues on `stream` and returns; allocates
+ * nothing; O and LSE are fully overwritten.  Errors as for mka_fused_attn_fwd. */
+mka_status mka_mixture_attn_fwd(const void* Q, const void* const K[3], const void* const V[3],
+                                const float* G, void* O, float* LSE, const mka_shape* shape,
+                                void* stream);
+
 /* Measurement helpers (not part of the method): the ceilings that the rooflines of the
  * attention kernels are quoted against besides the vendor peaks.
  *

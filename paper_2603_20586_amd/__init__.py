@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     mka_fused_attn_bwd,
     mka_fused_attn_decode,
     mka_fused_attn_fwd,
+    mka_mixture_attn_fwd,
     mka_route,
     mka_workspace_bytes,
     status_string,

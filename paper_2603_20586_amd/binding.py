@@ -64,6 +64,9 @@ def lib() -> ctypes.CDLL:
                                             POINTER(_P3), c_void_p, POINTER(c_int32 * 3),
                                             c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                             POINTER(MkaDecodeShape), c_void_p, c_size_t, c_void_p]
+        L.mka_mixture_attn_fwd.restype = ctypes.c_int
+        L.mka_mixture_attn_fwd.argtypes = [c_void_p, POINTER(_P3), POINTER(_P3), c_void_p, c_void_p,
+                                           c_void_p, POINTER(MkaShape), c_void_p]
         L.mka_ceiling_mfma.restype = ctypes.c_int
         L.mka_ceiling_mfma.argtypes = [c_void_p, c_int32, c_int32, POINTER(ctypes.c_double), c_void_p]
         L.mka_ceiling_read.restype = ctypes.c_int
@@ -238,6 +241,24 @@ def mka_fused_attn_bwd(dO, Q, K, V, G, O, LSE, W_r=None, len3=None, causal=True,
                                     ctypes.byref(s), _ptr(workspace), workspace.numel(),
                                     _stream()), "mka_fused_attn_bwd")
     return dict(dQ=dQ, dK=dK, dV=dV, dW_r=dW, db_r=db)
+
+
+def mka_mixture_attn_fwd(Q, K, V, G=None, causal=True, scale=1.0, want_lse=True, O=None, LSE=None):
+    """Gated mixture of exponentiated scores over up to three memories of their own lengths
+    (section "Recursive MKA with Online Softmax"); G [B,H,Tq,3] gates of the query rows or None.
+    Returns (O, LSE)."""
+    _dev_check(Q, G, *K, *V)
+    B, H, Tq, d = Q.shape
+    len3 = [0 if k is None else k.shape[2] for k in K]
+    if O is None:
+        O = torch.empty_like(Q)
+    if LSE is None and want_lse:
+        LSE = torch.empty((B, H, Tq), dtype=torch.float32, device=Q.device)
+    s = _shape(Q, max(len3 + [Tq]), len3, causal, scale)
+    Kp, Vp = _p3(K), _p3(V)
+    _check(lib().mka_mixture_attn_fwd(_ptr(Q), ctypes.byref(Kp), ctypes.byref(Vp), _ptr(G), _ptr(O),
+                                      _ptr(LSE), ctypes.byref(s), _stream()), "mka_mixture_attn_fwd")
+    return O, LSE
 
 
 def mka_ceiling_mfma(out, workgroups: int, iters: int) -> float:

@@ -97,16 +97,6 @@ __device__ __forceinline__ int tile_row(int t) {
   return (t & 16) | ((t & 3) << 2) | ((t >> 2) & 3);
 }
 
-// Transposed 16-bit LDS read (gfx950): inside every 16-lane group, lane i receives, for
-// k = 0..3, element (i & 3) of the 8 bytes addressed by lane 4k + (i >> 2).  With lane s
-// addressing row (s >> 2), columns 4 (s & 3) .. +3 of a row-major block, lane i gets column i of
-// rows 0..3: the block's transpose, which is the MFMA A-operand layout (row = lane, 4 k-values).
-typedef short bwd_v4s __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ uint2 lds_read_tr(const bf16* p) {
-  typedef __attribute__((address_space(3))) bwd_v4s* lptr;
-  const bwd_v4s v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p));
-  return __builtin_bit_cast(uint2, v);
-}
 // A operand (32 x 16) = transpose of rows k0 .. k0+15 (the MFMA k index), columns m0 .. m0+31 of
 // a row-major LDS matrix; row_ptr(k) returns the address of row k, column m0.
 template <typename RowPtr>

@@ -128,6 +128,43 @@ mka_status mka_fused_attn_fwd(const void* Q, const void* const K[3], const void*
   return e == hipSuccess ? MKA_OK : MKA_ERR_LAUNCH;
 }
 
+mka_status mka_mixture_attn_fwd(const void* Q, const void* const K[3], const void* const V[3],
+                                const float* G, void* O, float* LSE, const mka_shape* shape,
+                                void* stream) {
+  if (!shape) return MKA_ERR_NULL;
+  if (shape->dtype != MKA_F32 && shape->dtype != MKA_BF16) return MKA_ERR_DTYPE;
+  if (shape->B < 0 || shape->H < 0 || shape->Tq < 0 || shape->d <= 0) return MKA_ERR_SHAPE;
+  if (shape->d != 64 && shape->d != 128) return MKA_ERR_UNSUPPORTED;
+  if (shape->dtype != MKA_BF16) return MKA_ERR_UNSUPPORTED;  // bf16 MFMA path only
+  if (!(shape->scale >= 0.f) || isinf(shape->scale)) return MKA_ERR_UNSUPPORTED;
+  if (!Q || !K || !V || !O) return MKA_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(O) || (reinterpret_cast<uintptr_t>(G) & 3u) ||
+      (reinterpret_cast<uintptr_t>(LSE) & 3u))
+    return MKA_ERR_ALIGN;
+  mka::MixArgs a;
+  bool any = false;
+  for (int l = 0; l < 3; ++l) {
+    if (!aligned16(K[l]) || !aligned16(V[l])) return MKA_ERR_ALIGN;
+    if (shape->len[l] < 0) return MKA_ERR_SHAPE;
+    const bool present = K[l] && V[l] && shape->len[l] > 0;
+    // bottom-right aligned causal mask: a memory shorter than the query block would leave its
+    // first rows without a diagonal
+    if (present && shape->causal && shape->len[l] < shape->Tq) return MKA_ERR_SHAPE;
+    if (present && (long long)shape->len[l] * shape->d >= (1ll << 31)) return MKA_ERR_UNSUPPORTED;
+    a.K[l] = present ? K[l] : nullptr;
+    a.V[l] = present ? V[l] : nullptr;
+    a.S[l] = present ? shape->len[l] : 0;
+    any = any || present;
+  }
+  if (!any) return MKA_ERR_NULL;  // at least one memory
+  if (shape->B == 0 || shape->H == 0 || shape->Tq == 0) return MKA_OK;
+  a.Q = Q; a.G = G; a.O = O; a.LSE = LSE;
+  a.BH = shape->B * shape->H; a.Tq = shape->Tq; a.d = shape->d;
+  a.causal = shape->causal ? 1 : 0;
+  a.scale = shape->scale;
+  return mka::launch_mix_bf16(a, (hipStream_t)stream) == hipSuccess ? MKA_OK : MKA_ERR_LAUNCH;
+}
+
 mka_status mka_fused_attn_decode(const void* q, const void* const k_new[3],
                                  const void* const v_new[3], void* const Kc[3], void* const Vc[3],
                                  float* Gc, int32_t len[3], const float* W_r, const float* b_r,

@@ -77,6 +77,16 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// Transposed 16-bit LDS read (gfx950): inside every 16-lane group, lane i receives, for
+// k = 0..3, element (i & 3) of the 8 bytes addressed by lane 4k + (i >> 2).  With lane s
+// addressing row (s >> 2), columns 4 (s & 3) .. +3 of a row-major block, lane i gets column i of
+// rows 0..3: the block's transpose, which is the MFMA A-operand layout (row = lane, 4 k-values).
+typedef short lds_v4s __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint2 lds_read_tr(const bf16* p) {
+  typedef __attribute__((address_space(3))) lds_v4s* lptr;
+  const lds_v4s v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p));
+  return __builtin_bit_cast(uint2, v);
+}
 // Exchange with the lane 32 away (the other half of the wave).
 // One v_permlane32_swap (a VALU instruction of gfx950, no LDS round trip): with both operands
 // equal to v, the first result holds the lower half's values in both halves of the wave, the

@@ -32,6 +32,20 @@ struct FwdArgs {
 hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t st);
 hipError_t launch_fwd_f32(const FwdArgs& a, hipStream_t st);
 
+struct MixArgs {
+  const void* Q;
+  const void* K[3];
+  const void* V[3];
+  const float* G;  // gates per QUERY row [BH,Tq,3], or null (all ones)
+  void* O;
+  float* LSE;      // or null
+  int BH, Tq, d;
+  int S[3];        // slots per level (0: absent)
+  int causal;
+  float scale;
+};
+hipError_t launch_mix_bf16(const MixArgs& a, hipStream_t st);
+
 struct DecodeArgs {
   const void* q;
   const void* k_new[3];

@@ -1,0 +1,108 @@
+"""GPU parity of the gated-mixture attention (section "Recursive MKA with Online Softmax") against
+the fp64 oracle, through the C ABI: ragged shapes over several tiles and all three levels, levels
+of unequal length, absent levels, zero gates, no gates (plain attention), and the full-size
+prefill shape on sampled heads."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from util import BF16_ATOL, announce, cpu_list, max_abs, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mka():
+    import paper_2603_20586_amd as m
+
+    assert torch.cuda.is_available()
+    m.lib()
+    return m
+
+
+def _inputs(B, H, Tq, S3, d, seed):
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+    def rnd(*shape):
+        return torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    Q = rnd(B, H, Tq, d)
+    K = [None if s is None else rnd(B, H, s, d) for s in S3]
+    V = [None if s is None else rnd(B, H, s, d) for s in S3]
+    G = torch.softmax(torch.randn((B, H, Tq, 3), generator=gen, device="cuda") * 2.0, -1)
+    return Q, K, V, G
+
+
+def _check(mka, oracle, Q, K, V, G, causal, scale):
+    O, LSE = mka.mka_mixture_attn_fwd(Q, K, V, G, causal=causal, scale=scale)
+    torch.cuda.synchronize()
+    Oref, Lref = oracle.mixture_fwd(Q.cpu(), cpu_list(K), cpu_list(V),
+                                    None if G is None else G.cpu(), causal=causal, tau=scale)
+    eo = max_abs(O, Oref)
+    fin = np.isfinite(Lref)
+    el = float(np.max(np.abs(to_np(LSE)[fin] - Lref[fin]))) if fin.any() else 0.0
+    assert eo <= BF16_ATOL and el <= BF16_ATOL, (eo, el)
+    assert np.array_equal(np.isfinite(to_np(LSE)), fin)
+    return eo, el
+
+
+@pytest.mark.parametrize("d", [128, 64])
+@pytest.mark.parametrize("Tq,S3,causal", [
+    (300, (300, 300, 300), True),     # several query tiles, 15 stream tiles, ragged tails
+    (130, (333, 130, 200), True),     # unequal lengths, each with its own diagonal
+    (200, (260, 70, 1), False),       # non-causal, a one-slot memory
+    (257, (257, None, 300), True),    # a memory absent
+    (64, (64, None, None), True),     # one memory, one tile
+    (1, (1, 1, 1), True), (1, (70, 3, 129), False)])
+def test_mixture_shapes(mka, oracle, d, Tq, S3, causal):
+    announce(f"mixture d={d} Tq={Tq} S={S3} causal={causal}")
+    Q, K, V, G = _inputs(2, 2, Tq, S3, d, seed=31)
+    _check(mka, oracle, Q, K, V, G, causal, 1.0 / np.sqrt(d))
+
+
+def test_mixture_without_gates_is_attention_over_the_concatenation(mka, oracle):
+    announce("mixture no gates")
+    Q, K, V, _ = _inputs(1, 3, 190, (190, 200, 250), 128, seed=32)
+    _check(mka, oracle, Q, K, V, None, True, 0.09)
+
+
+def test_mixture_zero_gates_switch_levels_off_per_row(mka, oracle):
+    announce("mixture zero gates")
+    Q, K, V, G = _inputs(1, 2, 150, (150, 150, 150), 128, seed=33)
+    G[:, :, ::2, 0] = 0.0          # even rows never look at memory 1
+    G[:, :, 5, :] = 0.0            # a row that sees nothing: O = 0, LSE = -inf
+    O, LSE = mka.mka_mixture_attn_fwd(Q, K, V, G, causal=True, scale=0.1)
+    torch.cuda.synchronize()
+    assert float(O[:, :, 5].float().abs().max()) == 0.0
+    assert bool(torch.isinf(LSE[:, :, 5]).all())
+    _check(mka, oracle, Q, K, V, G, True, 0.1)
+
+
+def test_mixture_one_memory_matches_the_route_fused_forward_with_one_hot_gates(mka):
+    """Two different kernels of the library on a case where the two formulations coincide."""
+    announce("mixture vs route-fused, one memory")
+    inp = si.prefill_inputs(1, 2, 260, 260, 128, dtype="bf16", seed=34, device="cuda")
+    G = torch.zeros((1, 2, 260, 3), device="cuda")
+    G[..., 0] = 1.0
+    O1, L1, _, _ = mka.mka_fused_attn_fwd(inp["Q"], inp["K"], inp["V"], None, None, G=G,
+                                          causal=True, scale=inp["scale"])
+    O2, L2 = mka.mka_mixture_attn_fwd(inp["Q"], [inp["K"][0], None, None], [inp["V"][0], None, None],
+                                      None, causal=True, scale=inp["scale"])
+    torch.cuda.synchronize()
+    assert float((O1.float() - O2.float()).abs().max()) <= 1e-2
+    assert float((L1 - L2).abs().max()) <= 1e-2
+
+
+def test_mixture_full_prefill_shape_sampled_heads(mka, oracle):
+    """C2 shape (B4 H16 T2048 d128), all three memories: every head runs, 3 are compared."""
+    announce("mixture C2 shape")
+    inp, cfg = si.config_inputs("C2", device="cuda")
+    G, _ = mka.mka_route(inp["Q"], inp["W_r"] * 30.0, inp["b_r"], want_idx=False)
+    O, LSE = mka.mka_mixture_attn_fwd(inp["Q"], inp["K"], inp["V"], G, causal=True, scale=inp["scale"])
+    torch.cuda.synchronize()
+    for (b, h) in [(0, 0), (2, 7), (3, 15)]:
+        sl = (slice(b, b + 1), slice(h, h + 1))
+        Oref, Lref = oracle.mixture_fwd(inp["Q"][sl].cpu(), [k[sl].cpu() for k in inp["K"]],
+                                        [v[sl].cpu() for v in inp["V"]], G[sl].cpu(),
+                                        causal=True, tau=inp["scale"])
+        assert max_abs(O[sl], Oref) <= BF16_ATOL
+        assert max_abs(LSE[sl], Lref) <= BF16_ATOL
