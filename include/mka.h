@@ -150,6 +150,17 @@ mka_status mka_fused_attn_bwd(const void* dO, const void* Q, const void* const K
                               void* const dV[3], float* dW_r, float* db_r, const mka_shape* shape,
                               void* workspace, size_t workspace_bytes, void* stream);
 
+/* Route-fusion materialised (paper: Alg. 2 steps 6-7; the "single fused KV tensor" that the
+ * paper caches): Kf[j] = sum_l [j < len[l]] G[j,l] K_l[j], Vf likewise, mixed in f32 and rounded
+ * once to bf16.  K[l], V[l], Kf, Vf [B,H,S,d] (device, bf16, 16-byte aligned; Kf/Vf are fully
+ * overwritten; a NULL K[l]/V[l] or slots j >= len[l] contribute the zero vector and the gates
+ * are not renormalised); G [B,H,S,3] f32 gates of the slots.  Reads shape->B,H,S,d,len,dtype.
+ * Attention over the result is plain softmax attention: mka_mixture_attn_fwd with one memory
+ * and G = NULL; it equals mka_fused_attn_fwd on the raw memories up to rounding order.
+ * Enqueues on `stream` and returns; allocates nothing.  bf16 only, d in {64,128}. */
+mka_status mka_fuse_kv(const void* const K[3], const void* const V[3], const float* G, void* Kf,
+                       void* Vf, const mka_shape* shape, void* stream);
+
 /* Gated mixture of exponentiated scores over up to three memories (paper: section "Theoretical
  * Formulation: Recursive MKA with Online Softmax", first equation, evaluated with the max-shift
  * recursion of that section) - the per-QUERY-gate formulation, a different function from the

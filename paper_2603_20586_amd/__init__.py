@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     mka_ceiling_read,
     mka_fused_attn_bwd,
     mka_fused_attn_decode,
+    mka_fuse_kv,
     mka_fused_attn_fwd,
     mka_mixture_attn_fwd,
     mka_route,

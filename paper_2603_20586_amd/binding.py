@@ -64,6 +64,9 @@ def lib() -> ctypes.CDLL:
                                             POINTER(_P3), c_void_p, POINTER(c_int32 * 3),
                                             c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                             POINTER(MkaDecodeShape), c_void_p, c_size_t, c_void_p]
+        L.mka_fuse_kv.restype = ctypes.c_int
+        L.mka_fuse_kv.argtypes = [POINTER(_P3), POINTER(_P3), c_void_p, c_void_p, c_void_p,
+                                  POINTER(MkaShape), c_void_p]
         L.mka_mixture_attn_fwd.restype = ctypes.c_int
         L.mka_mixture_attn_fwd.argtypes = [c_void_p, POINTER(_P3), POINTER(_P3), c_void_p, c_void_p,
                                            c_void_p, POINTER(MkaShape), c_void_p]
@@ -241,6 +244,28 @@ def mka_fused_attn_bwd(dO, Q, K, V, G, O, LSE, W_r=None, len3=None, causal=True,
                                     ctypes.byref(s), _ptr(workspace), workspace.numel(),
                                     _stream()), "mka_fused_attn_bwd")
     return dict(dQ=dQ, dK=dK, dV=dV, dW_r=dW, db_r=db)
+
+
+def mka_fuse_kv(K, V, G, len3=None, Kf=None, Vf=None):
+    """Route-fusion materialised (Alg. 2 steps 6-7): returns (Kf, Vf), bf16 [B,H,S,d]."""
+    _dev_check(G, Kf, Vf, *K, *V)
+    ref = next(k for k in K if k is not None)
+    B, H, S, d = ref.shape
+    if Kf is None:
+        Kf = torch.empty_like(ref)
+    if Vf is None:
+        Vf = torch.empty_like(ref)
+    s = MkaShape()
+    s.B, s.H, s.Tq, s.S, s.d = B, H, S, S, d
+    ln = len3 if len3 is not None else (S, S, S)
+    for l in range(3):
+        s.len[l] = int(ln[l])
+    s.dtype = _dtype_code(ref)
+    s.causal, s.scale = 0, 1.0
+    Kp, Vp = _p3(K), _p3(V)
+    _check(lib().mka_fuse_kv(ctypes.byref(Kp), ctypes.byref(Vp), _ptr(G), _ptr(Kf), _ptr(Vf),
+                             ctypes.byref(s), _stream()), "mka_fuse_kv")
+    return Kf, Vf
 
 
 def mka_mixture_attn_fwd(Q, K, V, G=None, causal=True, scale=1.0, want_lse=True, O=None, LSE=None):

@@ -128,6 +128,32 @@ mka_status mka_fused_attn_fwd(const void* Q, const void* const K[3], const void*
   return e == hipSuccess ? MKA_OK : MKA_ERR_LAUNCH;
 }
 
+mka_status mka_fuse_kv(const void* const K[3], const void* const V[3], const float* G, void* Kf,
+                       void* Vf, const mka_shape* shape, void* stream) {
+  if (!shape) return MKA_ERR_NULL;
+  if (shape->dtype != MKA_F32 && shape->dtype != MKA_BF16) return MKA_ERR_DTYPE;
+  if (shape->B < 0 || shape->H < 0 || shape->S < 0 || shape->d <= 0) return MKA_ERR_SHAPE;
+  if (shape->d != 64 && shape->d != 128) return MKA_ERR_UNSUPPORTED;
+  if (shape->dtype != MKA_BF16) return MKA_ERR_UNSUPPORTED;
+  if (!K || !V || !G || !Kf || !Vf) return MKA_ERR_NULL;
+  if (!aligned16(Kf) || !aligned16(Vf) || (reinterpret_cast<uintptr_t>(G) & 3u)) return MKA_ERR_ALIGN;
+  mka::PrefuseArgs a;
+  bool any = false;
+  for (int l = 0; l < 3; ++l) {
+    if (!aligned16(K[l]) || !aligned16(V[l])) return MKA_ERR_ALIGN;
+    if (shape->len[l] < 0 || shape->len[l] > shape->S) return MKA_ERR_SHAPE;
+    const bool present = K[l] && V[l];
+    a.K[l] = present ? K[l] : nullptr;
+    a.V[l] = present ? V[l] : nullptr;
+    a.len[l] = present ? shape->len[l] : 0;
+    any = any || present;
+  }
+  if (!any) return MKA_ERR_NULL;
+  a.G = G; a.Kf = Kf; a.Vf = Vf;
+  a.BH = shape->B * shape->H; a.S = shape->S; a.d = shape->d;
+  return mka::launch_prefuse(a, (hipStream_t)stream) == hipSuccess ? MKA_OK : MKA_ERR_LAUNCH;
+}
+
 mka_status mka_mixture_attn_fwd(const void* Q, const void* const K[3], const void* const V[3],
                                 const float* G, void* O, float* LSE, const mka_shape* shape,
                                 void* stream) {

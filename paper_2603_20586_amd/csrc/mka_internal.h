@@ -46,6 +46,17 @@ struct MixArgs {
 };
 hipError_t launch_mix_bf16(const MixArgs& a, hipStream_t st);
 
+struct PrefuseArgs {
+  const void* K[3];
+  const void* V[3];
+  const float* G;  // [BH,S,3]
+  void* Kf;
+  void* Vf;
+  int BH, S, d;
+  int len[3];
+};
+hipError_t launch_prefuse(const PrefuseArgs& a, hipStream_t st);
+
 struct DecodeArgs {
   const void* q;
   const void* k_new[3];

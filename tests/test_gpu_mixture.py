@@ -106,3 +106,36 @@ def test_mixture_full_prefill_shape_sampled_heads(mka, oracle):
                                         causal=True, tau=inp["scale"])
         assert max_abs(O[sl], Oref) <= BF16_ATOL
         assert max_abs(LSE[sl], Lref) <= BF16_ATOL
+
+
+# ------------------------------------------------------------------ materialised route-fusion
+@pytest.mark.parametrize("d", [128, 64])
+@pytest.mark.parametrize("S,len3", [(300, None), (257, [257, 100, 0]), (1, None)])
+def test_fuse_kv_against_the_oracle(mka, oracle, d, S, len3):
+    announce(f"fuse_kv d={d} S={S} len={len3}")
+    inp = si.prefill_inputs(2, 2, S, S, d, dtype="bf16", seed=41, device="cuda")
+    G = torch.softmax(torch.randn((2, 2, S, 3), device="cuda") * 2, -1)
+    Kf, Vf = mka.mka_fuse_kv(inp["K"], inp["V"], G, len3=len3)
+    torch.cuda.synchronize()
+    Kr = oracle.fuse(cpu_list(inp["K"]), G.cpu(), len3=len3)
+    Vr = oracle.fuse(cpu_list(inp["V"]), G.cpu(), len3=len3)
+    # one bf16 rounding of a value of magnitude <= ~5
+    assert max_abs(Kf, Kr) <= BF16_ATOL and max_abs(Vf, Vr) <= BF16_ATOL
+
+
+def test_prefuse_then_plain_attention_equals_the_folded_forward(mka, oracle):
+    """The materialised alternative to in-kernel fusion: same fused bf16 stream, so the two GPU
+    paths agree far inside the bound, and both match the oracle's route-fused forward."""
+    announce("prefuse + plain attention vs folded forward")
+    inp = si.prefill_inputs(1, 3, 400, 400, 128, dtype="bf16", seed=42, device="cuda")
+    O1, L1, G, _ = mka.mka_fused_attn_fwd(inp["Q"], inp["K"], inp["V"], inp["W_r"] * 20.0, inp["b_r"],
+                                          causal=True, scale=inp["scale"])
+    Kf, Vf = mka.mka_fuse_kv(inp["K"], inp["V"], G)
+    O2, L2 = mka.mka_mixture_attn_fwd(inp["Q"], [Kf, None, None], [Vf, None, None], None,
+                                      causal=True, scale=inp["scale"])
+    torch.cuda.synchronize()
+    assert float((O1.float() - O2.float()).abs().max()) <= 5e-3
+    assert float((L1 - L2).abs().max()) <= 5e-3
+    Oref, Lref = oracle.fwd(inp["Q"].cpu(), cpu_list(inp["K"]), cpu_list(inp["V"]), G.cpu(),
+                            causal=True, tau=inp["scale"])[:2]
+    assert max_abs(O2, Oref) <= BF16_ATOL and max_abs(L2, Lref) <= BF16_ATOL
