@@ -186,6 +186,7 @@ __device__ __forceinline__ void mx_half_step(f32x16 s_now, f32x16& s_next, const
     constexpr int KP = KK % PF;  // ring position of PV fragment 0
     oacc[i % DB] = mfma32(fr[(KP + i) % PF], i / DB ? p1 : p0, oacc[i % DB]);
     if (i + PF < NPV) fr[(KP + i) % PF] = v_frag(i + PF);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
@@ -264,29 +265,40 @@ __global__ __launch_bounds__(MX_NT, 1) void mix_bf16_kernel(
 
   // ---- staging: pair p = (tile p / 2, half p % 2) of the tile stream; a thread owns one 16-byte
   // chunk of K and one of V of the pair (d = 64: the first pair of a tile is the whole tile)
+  // Everything per thread is precomputed: byte offset of its chunk inside a row block, LDS
+  // offsets of the two halves; per pair only the (uniform) level base and first slot change.
   const int crow = tid / CPR, ccol = (tid % CPR) * 8;
+  const unsigned lds_o[2] = {(unsigned)(mx_row(crow) * RSTR + ccol),
+                             (unsigned)(mx_row((RP + crow) & (BC - 1)) * RSTR + ccol)};
+  const unsigned g_o = (unsigned)(crow * D + ccol) * 2u;  // bytes from the pair's first row
   uint4 rk = make_uint4(0, 0, 0, 0), rv = make_uint4(0, 0, 0, 0);
   auto pair_active = [&](int p) { return (p >> 1) < NT && (RP * (p & 1) < BC); };
   auto load_pair = [&](int p) __attribute__((always_inline)) {
     if (!pair_active(p)) return;
     int l, j0;
     mx_tile_of(L, p >> 1, l, j0);
-    const int j = j0 + RP * (p & 1) + crow;
-    const bool valid = j < sel3(l, L.S);
-    const long off = (long)(valid ? j : 0) * D + ccol;
-    const bf16* kp = sel3(l, L.K);
-    const bf16* vp = sel3(l, L.V);
-    rk = *reinterpret_cast<const uint4*>(kp + off);
-    rv = *reinterpret_cast<const uint4*>(vp + off);
-    if (!valid) {  // rows past the end of the level: zeros (P is 0 there, 0 * garbage is not)
-      rk = make_uint4(0, 0, 0, 0);
-      rv = make_uint4(0, 0, 0, 0);
+    const int jp = j0 + RP * (p & 1);  // first slot of the pair (uniform)
+    const int Sl = sel3(l, L.S);
+    const char* kp = reinterpret_cast<const char*>(sel3(l, L.K)) + (unsigned)jp * (unsigned)(D * 2);
+    const char* vp = reinterpret_cast<const char*>(sel3(l, L.V)) + (unsigned)jp * (unsigned)(D * 2);
+    if (jp + RP <= Sl) {  // all rows of the pair exist (uniform)
+      rk = *reinterpret_cast<const uint4*>(kp + g_o);
+      rv = *reinterpret_cast<const uint4*>(vp + g_o);
+    } else {  // tail of the level: rows past its end are zeros (P is 0 there, 0 * garbage is not)
+      const bool valid = jp + crow < Sl;
+      const unsigned o = valid ? g_o : (unsigned)(ccol * 2) - (unsigned)jp * (unsigned)(D * 2);
+      rk = *reinterpret_cast<const uint4*>(kp + (int)o);
+      rv = *reinterpret_cast<const uint4*>(vp + (int)o);
+      if (!valid) {
+        rk = make_uint4(0, 0, 0, 0);
+        rv = make_uint4(0, 0, 0, 0);
+      }
     }
   };
   int kbuf_w = 0, vbuf_w = 0;  // buffers of the tile that the next write_pair targets
   auto write_pair = [&](int p) __attribute__((always_inline)) {
     if (pair_active(p)) {
-      const int o = mx_row(RP * (p & 1) + crow) * RSTR + ccol;
+      const unsigned o = lds_o[p & 1];
       *reinterpret_cast<uint4*>(&smem[kbuf_w * SM::TSZ + o]) = rk;
       *reinterpret_cast<uint4*>(&smem[SM::VOFF + vbuf_w * SM::TSZ + o]) = rv;
     }
