@@ -12,13 +12,17 @@
 //
 // Skeleton as in the route-fused forward: workgroup = 8 waves x 32 query rows, S^T = K Q^T and
 // O^T += V^T P^T with 32x32x16 MFMAs (a lane owns one query row), units of 32 slots software-
-// pipelined (the S^T MFMAs of the next unit between the exponentials of the current one), the
-// barrier that publishes a tile in the middle of the previous one (two K buffers, three V).
-// Differences: both tiles are staged as plain row copies (a thread moves one 16-byte chunk of K
-// and one of V per half step); V stays row-major and its transpose for the second product is
-// read with ds_read_b64_tr_b16; the slots of a tile are permuted over the LDS rows (j = 4a+b ->
-// row 4b+a inside every 16) so that both the row reads and the transposed reads are free of
-// bank conflicts.
+// pipelined (the S^T MFMAs of the next unit between the exponentials of the current one), one
+// barrier per tile, in its middle.  Differences: the tiles are plain row copies, so they go from
+// global memory straight into LDS (global_load_lds_dwordx4: no registers hold data in flight, and
+// the prefetch distance is the depth of the buffer rings - three K and four V tiles, a tile is
+// requested two tiles before its first use); V stays row-major and its transpose for the second
+// product is read with ds_read_b64_tr_b16.  An LDS-direct load writes the 64 lanes' 16 bytes to
+// consecutive addresses, so tile rows carry no padding; instead the 16-byte chunks of a row are
+// XOR-swizzled by the row number and the slots of a tile are permuted over the rows (j = 4a+b ->
+// row 4b+a inside every 16): row reads and transposed reads are then free of bank conflicts
+// (d = 128; the transposed reads of d = 64 are two-way conflicted).  The swizzle is applied on
+// the global side: every lane picks the chunk that belongs at its LDS position.
 #include "mka_dev.h"
 #include "mka_internal.h"
 
@@ -26,31 +30,59 @@ namespace mka {
 
 namespace {
 
-constexpr int MX_BC = 64;  // slots per KV tile
-constexpr int MX_NW = 8;   // waves per workgroup
-constexpr int MX_NT = MX_NW * 64;
+constexpr int MX_BC = 64;   // slots per KV tile
+constexpr int MX_BR = 256;  // query rows per workgroup
+#ifndef MX_R
+#define MX_R 1
+#endif
+// R: blocks of 32 query rows per wave.  A K or V^T fragment read from LDS feeds R MFMAs, so R = 2
+// halves the LDS traffic per flop; the workgroup then has 4 waves (one per SIMD, 512 registers
+// each) instead of 8.
+template <int R>
+struct MixShape {
+  static constexpr int NW = MX_BR / (32 * R);  // waves per workgroup
+  static constexpr int NT = NW * 64;           // threads
+};
 
 template <int D>
 struct MixSmem {
-  static constexpr int RSTR = D + 8;         // bf16 per tile row (16-byte pad)
-  static constexpr int TSZ = MX_BC * RSTR;   // one tile
-  static constexpr int VOFF = 2 * TSZ;       // two K tiles, then three V tiles
-  static constexpr int TOTAL = 5 * TSZ;      // bf16 elements
+  static constexpr int ROWB = D * 2;          // bytes per tile row (no padding)
+  static constexpr int TSZ = MX_BC * ROWB;    // bytes per tile
+  static constexpr int NKB = 3, NVB = 4;      // ring depths
+  static constexpr int VOFF = NKB * TSZ;
+  static constexpr int TOTAL = (NKB + NVB) * TSZ;  // bytes (also covers the epilogue's O tiles)
 };
 
-// LDS row of slot j (0..63) of a tile
+// LDS row of slot j (0..63) of a tile (an involution)
 __device__ __forceinline__ int mx_row(int j) {
   return (j & ~15) | ((j & 3) << 2) | ((j >> 2) & 3);
+}
+// chunk c of row r sits at chunk position c ^ mx_swz(r) of the row
+template <int D>
+__device__ __forceinline__ int mx_swz(int r) {
+  return D == 128 ? (r & 15) : ((r >> 1) & 7);
+}
+
+// 16 bytes per lane from global memory (uniform base + per-lane byte offset) to LDS address
+// lds + 16 * lane.  Counted by vmcnt like any other load; the LDS write is done when the count
+// drops.  m0 carries the LDS address (one wait state between its write and the load).
+__device__ __forceinline__ void mx_dma16(const void* base, unsigned off, unsigned lds) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(off), "s"(base), "s"(lds)
+               : "memory");
+}
+template <int N>
+__device__ __forceinline__ void mx_wait_loads() {
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
 struct MixLevels {
   const bf16* K[3];
   const bf16* V[3];
-  int S[3];      // slots of the level (0: absent)
-  int n[3];      // tiles of the level that this workgroup visits
-  int jmax[3];   // last slot the lane's row sees (may be negative)
-  int row_lo[3]; // last slot the wave's FIRST row sees
-  float bl[3];   // log2 of the lane's gate
+  int S[3];         // slots of the level (0: absent)
+  int n[3];         // tiles of the level that this workgroup visits
+  int row_lo[3];    // last slot the wave's FIRST row sees
 };
 
 // element l of a 3-array without dynamic indexing (which would put the array in scratch memory)
@@ -59,152 +91,187 @@ __device__ __forceinline__ T sel3(int l, const T (&a)[3]) {
   return l == 0 ? a[0] : (l == 1 ? a[1] : a[2]);
 }
 
-// stream tile T -> level and first slot
-__device__ __forceinline__ void mx_tile_of(const MixLevels& L, int T, int& l, int& j0) {
-  l = (T >= L.n[0]) + (T >= L.n[0] + L.n[1]);
-  const int start = l == 0 ? 0 : (l == 1 ? L.n[0] : L.n[0] + L.n[1]);
-  j0 = (T - start) * MX_BC;
+// first level after l that has tiles (3: none)
+__device__ __forceinline__ int mx_next_level(const MixLevels& L, int l) {
+  int nl = 3;
+  if (l < 2 && L.n[2] > 0) nl = 2;
+  if (l < 1 && L.n[1] > 0) nl = 1;
+  if (l < 0 && L.n[0] > 0) nl = 0;
+  return nl;
+}
+
+// Byte offset, inside a tile, of the lane's first K fragment of unit 0 (slot li of the unit, head
+// dims 8 g ..): fragment kk of unit u is at (a0 ^ (kk << 5)) + 32 u ROWB, because the chunk index
+// 2 kk + g only meets the swizzle in an XOR and unit and tile offsets are multiples of 2 KiB.
+template <int D>
+__device__ __forceinline__ unsigned mx_kfrag0(int li, int g) {
+  const int r = mx_row(li);
+  return (unsigned)(r * (D * 2) + 16 * (g ^ mx_swz<D>(r)));
 }
 
 template <int D>
-__device__ __forceinline__ f32x16 mx_s_unit(const bf16* sK, int unit, const bf16x8 (&qreg)[D / 16],
-                                            int li, int g) {
-  constexpr int RSTR = D + 8, KK = D / 16;
+__device__ __forceinline__ f32x16 mx_s_unit(const char* sK, unsigned a0, const bf16x8 (&qreg)[D / 16]) {
+  constexpr int KK = D / 16;
   f32x16 sacc;
 #pragma unroll
   for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
-  const bf16* arow = &sK[mx_row(32 * unit + li) * RSTR + 8 * g];
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk)
-    sacc = mfma32(*reinterpret_cast<const bf16x8*>(arow + 16 * kk), qreg[kk], sacc);
+    sacc = mfma32(*reinterpret_cast<const bf16x8*>(sK + (a0 ^ (unsigned)(kk << 5))), qreg[kk], sacc);
   return sacc;
 }
 
-// One half step of a wave: finish the unit whose S^T is s_now (32 slots from jb of a level with
-// log2-gate bl and visibility limit jmax), issue the S^T of unit `unit_n` of the K tile at sKn.
-// m is the running reference exponent in log2 units (gate included); register r of s_now <->
-// slot jb + 8 (r/4) + 4 g + r%4 of the lane's row.
-template <int D, bool MASK>
-__device__ __forceinline__ void mx_half_step(f32x16 s_now, f32x16& s_next, const bf16* sKn,
-                                             int unit_n, int jb, int jmax, float bl,
-                                             const bf16* sV, int unit,
-                                             const bf16x8 (&qreg)[D / 16], f32x16 (&oacc)[D / 32],
-                                             float& m, float& lsum, float c, int lane) {
-  constexpr int RSTR = D + 8, KK = D / 16, DB = D / 32;
-  constexpr int PF = 4;          // LDS fragments in flight
-  constexpr int EPK = 16 / KK;   // exponentials per S MFMA
-  constexpr int NPV = 2 * DB;    // PV MFMAs of the unit
-  const int g = lane >> 5, li = lane & 31;
-  bf16x8 fr[PF];
-  const bf16* arow = &sKn[mx_row(32 * unit_n + li) * RSTR + 8 * g];
-#pragma unroll
-  for (int kk = 0; kk < PF; ++kk) fr[kk] = *reinterpret_cast<const bf16x8*>(arow + 16 * kk);
+// Per row block state of the online softmax and what a half step needs to know about the rows.
+struct MixRow {
+  float m, lsum;  // running reference exponent (log2 units, gate included) and denominator
+  float bl;       // log2 gate of the level being consumed
+  int jmax;       // last visible slot of that level
+};
 
-  if (MASK) {
+// One half step of a wave: finish the unit whose S^T is s_now (32 slots from jb of a level:
+// softmax, then O^T += V^T P^T with the V rows of unit U of the tile at sV) and compute the S^T
+// of the following unit into s_next - for each of the wave's R row blocks, which share every
+// LDS fragment.
+//
+// fr is a ring of D/16 LDS fragments that lives across half steps.  On entry it holds the K
+// fragments of the unit whose S^T is computed here; every S MFMA group frees a slot, which is
+// refilled with the V^T fragment of the PV MFMAs that will use the same slot; these free it again
+// and it is refilled with a K fragment of the unit after the next (at sKnn, unit offset
+// included).  Every LDS read is thus issued a whole section before its use.
+// a0: mx_kfrag0 of the lane; x_lo / x_hi: byte offsets of the lane's transposed V reads.
+// mid_a / mid_b are called in the middle of the two sections (the kernel issues its tile requests
+// there, one load instruction at a time, so that the waves' loads do not queue up behind each
+// other at the address unit).
+// Register r of s_now[.] <-> slot jb + 8 (r/4) + 4 g + r%4 of the lane's row.
+template <int D, int R, bool MASK, int U, typename FA, typename FB>
+__device__ __forceinline__ void mx_half_step(FA&& mid_a, FB&& mid_b, f32x16 (&s_now)[R], f32x16 (&s_next)[R],
+                                             bf16x8 (&fr)[D / 16], const char* sKnn, unsigned a0,
+                                             int jb, const char* sV, unsigned x_lo, unsigned x_hi,
+                                             const bf16x8 (&qreg)[R][D / 16],
+                                             f32x16 (&oacc)[R][D / 32], MixRow (&row)[R], float c,
+                                             int lane) {
+  constexpr int ROWB = D * 2, KK = D / 16, DB = D / 32;
+  constexpr int EPK = 16 / KK;   // exponentials per S MFMA
+  constexpr int NPV = 2 * DB;    // PV MFMAs of the unit and row block (== KK)
+  const int g = lane >> 5;
+
+  float kb[R], alpha[R];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int j = jb + 8 * (r >> 2) + 4 * g + (r & 3);
-      if (j > jmax) s_now[r] = -INFINITY;
+  for (int rb = 0; rb < R; ++rb) {
+    if (MASK) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int j = jb + 8 * (r >> 2) + 4 * g + (r & 3);
+        if (j > row[rb].jmax) s_now[rb][r] = -INFINITY;
+      }
     }
-  }
-  float mx = fmaxf(s_now[0], s_now[1]);
+    float mx = fmaxf(s_now[rb][0], s_now[rb][1]);
 #pragma unroll
-  for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s_now[r]);
-  mx = fmaxf(mx, xor32(mx));
-  // Lazy max-shift (as in the route-fused forward): the reference exponent only moves when the
-  // row's largest exponent has grown by more than 8, so P may reach 2^8 and the rescale of the
-  // accumulators is skipped on almost every unit.
-  const float cand = (mx == -INFINITY) ? -INFINITY : fmaf(mx, c, bl);
-  const bool move = cand - m > 8.f || (m == -INFINITY && cand > -INFINITY);
-  const float m_new = move ? cand : m;
-  const float alpha = move ? ((m == -INFINITY) ? 0.f : fast_exp2(m - m_new)) : 1.f;
-  const float kb = bl - ((m_new == -INFINITY) ? 0.f : m_new);
-  m = m_new;
-  if (__any(move)) {
+    for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s_now[rb][r]);
+    mx = fmaxf(mx, xor32(mx));
+    // Lazy max-shift (as in the route-fused forward): the reference exponent only moves when the
+    // row's largest exponent has grown by more than 8, so P may reach 2^8 and the rescale of the
+    // accumulators is skipped on almost every unit.
+    const float m = row[rb].m, bl = row[rb].bl;
+    const float cand = (mx == -INFINITY) ? -INFINITY : fmaf(mx, c, bl);
+    const bool move = cand - m > 8.f || (m == -INFINITY && cand > -INFINITY);
+    const float m_new = move ? cand : m;
+    alpha[rb] = move ? ((m == -INFINITY) ? 0.f : fast_exp2(m - m_new)) : 1.f;
+    kb[rb] = bl - ((m_new == -INFINITY) ? 0.f : m_new);
+    row[rb].m = m_new;
+    if (__any(move)) {
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+      for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+        for (int r = 0; r < 16; ++r) oacc[rb][db][r] *= alpha[rb];
+    }
   }
 
   // V^T fragment of PV MFMA i (rows 32 (i % DB) of V^T, k-step i / DB): the transpose of 8 slots
   // x 32 head dims of the row-major V tile.  k positions 0..3 <-> slots 16 ks + 4 g + 0..3,
   // positions 4..7 <-> 8 further: the slots whose P values the lane holds in registers 8 ks ..
-  const int ti = lane & 15, gsel = (lane >> 4) & 1;
-  const bf16* vcol = sV + 16 * gsel + 4 * (ti & 3);
+  // The head-dim block db only meets the swizzle in an XOR of address bits 6..7.
   auto v_frag = [&](int i) __attribute__((always_inline)) {
     const int db = i % DB, ks = i / DB;
-    const int j0 = 32 * unit + 16 * ks + 4 * g + (ti >> 2);
-    const uint2 lo = lds_read_tr(vcol + mx_row(j0) * RSTR + 32 * db);
-    const uint2 hi = lds_read_tr(vcol + mx_row(j0 + 8) * RSTR + 32 * db);
+    const char* vrow = sV + (32 * U + 16 * ks) * ROWB;
+    const uint2 lo = lds_read_tr(reinterpret_cast<const bf16*>(vrow + (x_lo ^ (unsigned)(db << 6))));
+    const uint2 hi = lds_read_tr(reinterpret_cast<const bf16*>(vrow + (x_hi ^ (unsigned)(db << 6))));
     return __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
   };
 
   // -- section A: S^T of the next unit, between the exponentials of this one
-  f32x16 sn;
+  f32x16 sn[R];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) sn[r] = 0.f;
-  float p[16];
+  for (int rb = 0; rb < R; ++rb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sn[rb][r] = 0.f;
+  float p[R][16];
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) {
-    sn = mfma32(fr[kk % PF], qreg[kk], sn);
-    if (kk + PF < KK) {
-      fr[kk % PF] = *reinterpret_cast<const bf16x8*>(arow + 16 * (kk + PF));
-    } else {  // the K fragments are all on their way: start on the V^T fragments
-      const int i = kk + PF - KK;
-      if (i < NPV) fr[kk % PF] = v_frag(i);
-    }
 #pragma unroll
-    for (int r = kk * EPK; r < (kk + 1) * EPK; ++r) {
-      float e = fast_exp2(fmaf(s_now[r], c, kb));
-      if (MASK) e = (s_now[r] == -INFINITY) ? 0.f : e;  // also covers c == 0
-      p[r] = e;
-    }
+    for (int rb = 0; rb < R; ++rb) sn[rb] = mfma32(fr[kk], qreg[rb][kk], sn[rb]);
+    fr[kk] = v_frag(kk);
+#pragma unroll
+    for (int rb = 0; rb < R; ++rb)
+#pragma unroll
+      for (int r = kk * EPK; r < (kk + 1) * EPK; ++r) {
+        float e = fast_exp2(fmaf(s_now[rb][r], c, kb[rb]));
+        if (MASK) e = (s_now[rb][r] == -INFINITY) ? 0.f : e;  // also covers c == 0
+        p[rb][r] = e;
+      }
+    if (kk == KK / 2 - 1) mid_a();
     __builtin_amdgcn_sched_barrier(0);
   }
-  s_next = sn;
-  const uint4 pk0 = pack8(&p[0]), pk1 = pack8(&p[8]);
-  const bf16x8 p0 = __builtin_bit_cast(bf16x8, pk0);
-  const bf16x8 p1 = __builtin_bit_cast(bf16x8, pk1);
-  // row sum of the bf16-rounded P (what the PV product uses), two values per instruction
-  const bf16x2 ones = {(bf16)1.f, (bf16)1.f};
-  float psum = 0.f;
-  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.x), ones, psum, false);
-  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.y), ones, psum, false);
-  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.z), ones, psum, false);
-  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.w), ones, psum, false);
-  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.x), ones, psum, false);
-  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.y), ones, psum, false);
-  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.z), ones, psum, false);
-  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.w), ones, psum, false);
-  lsum = lsum * alpha + psum;
+  bf16x8 pk[R][2];
+#pragma unroll
+  for (int rb = 0; rb < R; ++rb) {
+    s_next[rb] = sn[rb];
+    const uint4 pk0 = pack8(&p[rb][0]), pk1 = pack8(&p[rb][8]);
+    pk[rb][0] = __builtin_bit_cast(bf16x8, pk0);
+    pk[rb][1] = __builtin_bit_cast(bf16x8, pk1);
+    // row sum of the bf16-rounded P (what the PV product uses), two values per instruction
+    const bf16x2 ones = {(bf16)1.f, (bf16)1.f};
+    float psum = 0.f;
+    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.x), ones, psum, false);
+    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.y), ones, psum, false);
+    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.z), ones, psum, false);
+    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.w), ones, psum, false);
+    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.x), ones, psum, false);
+    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.y), ones, psum, false);
+    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.z), ones, psum, false);
+    psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.w), ones, psum, false);
+    row[rb].lsum = row[rb].lsum * alpha[rb] + psum;
+  }
   __builtin_amdgcn_sched_barrier(0);
 
   // -- section B: O^T += V^T P^T
 #pragma unroll
   for (int i = 0; i < NPV; ++i) {
-    constexpr int KP = KK % PF;  // ring position of PV fragment 0
-    oacc[i % DB] = mfma32(fr[(KP + i) % PF], i / DB ? p1 : p0, oacc[i % DB]);
-    if (i + PF < NPV) fr[(KP + i) % PF] = v_frag(i + PF);
+#pragma unroll
+    for (int rb = 0; rb < R; ++rb)
+      oacc[rb][i % DB] = mfma32(fr[i], pk[rb][i / DB], oacc[rb][i % DB]);
+    fr[i] = *reinterpret_cast<const bf16x8*>(sKnn + (a0 ^ (unsigned)(i << 5)));
+    if (i == NPV / 2 - 1) mid_b();
     __builtin_amdgcn_sched_barrier(0);
   }
 }
 
-template <int D>
-__global__ __launch_bounds__(MX_NT, 1) void mix_bf16_kernel(
+template <int D, int R>
+__global__ __launch_bounds__(MixShape<R>::NT, 1) void mix_bf16_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ K0, const bf16* __restrict__ K1,
     const bf16* __restrict__ K2, const bf16* __restrict__ V0, const bf16* __restrict__ V1,
     const bf16* __restrict__ V2, const float* __restrict__ G, bf16* __restrict__ O,
     float* __restrict__ LSE, int Tq, int S0, int S1, int S2, int causal, float c, int n_qtiles,
     int BH, int interleave) {
   using SM = MixSmem<D>;
-  constexpr int BR = MX_NW * 32, BC = MX_BC, RSTR = SM::RSTR;
+  constexpr int NW = MixShape<R>::NW;
+  constexpr int BR = MX_BR, BC = MX_BC, ROWB = SM::ROWB;
   constexpr int KK = D / 16, DB = D / 32, CPR = D / 8;
-  constexpr int RP = MX_NT / CPR;  // tile rows the workgroup copies per half step (32 or 64)
-  extern __shared__ __attribute__((aligned(16))) unsigned char mx_smem_raw[];
-  bf16* smem = reinterpret_cast<bf16*>(mx_smem_raw);
+  extern __shared__ __attribute__((aligned(1024))) unsigned char mx_smem_raw[];
+  char* smem = reinterpret_cast<char*>(mx_smem_raw);
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, li = lane & 31;
+  const int wave = tid >> 6;  // left divergent on purpose: uniform mask branches cost registers
   // all query tiles of one (batch, head) on ONE XCD (block index = 8 * slot + xcd), heaviest
   // tiles first; heads interleaved on small grids (shorter causal tail)
   const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3);
@@ -219,18 +286,24 @@ __global__ __launch_bounds__(MX_NT, 1) void mix_bf16_kernel(
   }
   const long bh = (long)hl * 8 + xcd;
   if (bh >= BH) return;
-  const int tw0 = qt * BR + wave * 32;  // first row of this wave
-  const int tq = tw0 + li;              // this lane's row
+  const int tw0 = qt * BR + wave * (32 * R);  // first row of this wave
+  // row block rb of the wave: rows tw0 + 32 rb ..; this lane's row there is tw0 + 32 rb + li
 
-  bf16x8 qreg[KK];
+  bf16x8 qreg[R][KK];
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) {
-    uint4 u = make_uint4(0, 0, 0, 0);
-    if (tq < Tq) u = *reinterpret_cast<const uint4*>(Q + (bh * (long)Tq + tq) * D + 16 * kk + 8 * g);
-    qreg[kk] = __builtin_bit_cast(bf16x8, u);
-  }
+  for (int rb = 0; rb < R; ++rb)
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const int tq = tw0 + 32 * rb + li;
+      uint4 u = make_uint4(0, 0, 0, 0);
+      if (tq < Tq) u = *reinterpret_cast<const uint4*>(Q + (bh * (long)Tq + tq) * D + 16 * kk + 8 * g);
+      qreg[rb][kk] = __builtin_bit_cast(bf16x8, u);
+    }
 
   MixLevels L;
+  // per row block and level: last slot the lane's row sees (may be negative), log2 of its gate
+  int jmax0[R], jmax1[R], jmax2[R];
+  float bl0[R], bl1[R], bl2[R];
   {
     const bf16* Kp[3] = {K0, K1, K2};
     const bf16* Vp[3] = {V0, V1, V2};
@@ -247,144 +320,224 @@ __global__ __launch_bounds__(MX_NT, 1) void mix_bf16_kernel(
       if (causal && t_last + (S - Tq) + 1 < S) j_end = t_last + (S - Tq) + 1;
       if (j_end < 0) j_end = 0;
       L.n[l] = (j_end + BC - 1) / BC;
-      L.jmax[l] = causal ? min(tq + (S - Tq), S - 1) : S - 1;
       L.row_lo[l] = tw0 + (S - Tq);
-      float lam = 1.f;
-      if (G && tq < Tq) lam = G[(bh * (long)Tq + tq) * 3 + l];
-      L.bl[l] = __log2f(lam);  // gate 0 -> -inf: the level never contributes to this row
+#pragma unroll
+      for (int rb = 0; rb < R; ++rb) {
+        const int tq = tw0 + 32 * rb + li;
+        const int jm = causal ? min(tq + (S - Tq), S - 1) : S - 1;
+        float lam = 1.f;
+        if (G && tq < Tq) lam = G[(bh * (long)Tq + tq) * 3 + l];
+        const float b = __log2f(lam);  // gate 0 -> -inf: the level never contributes to this row
+        if (l == 0) { jmax0[rb] = jm; bl0[rb] = b; }
+        if (l == 1) { jmax1[rb] = jm; bl1[rb] = b; }
+        if (l == 2) { jmax2[rb] = jm; bl2[rb] = b; }
+      }
     }
   }
   const int NT = L.n[0] + L.n[1] + L.n[2];
 
-  f32x16 oacc[DB];
+  f32x16 oacc[R][DB];
+  MixRow row[R];
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
-  float m = -INFINITY, lsum = 0.f;
-
-  // ---- staging: pair p = (tile p / 2, half p % 2) of the tile stream; a thread owns one 16-byte
-  // chunk of K and one of V of the pair (d = 64: the first pair of a tile is the whole tile)
-  // Everything per thread is precomputed: byte offset of its chunk inside a row block, LDS
-  // offsets of the two halves; per pair only the (uniform) level base and first slot change.
-  const int crow = tid / CPR, ccol = (tid % CPR) * 8;
-  const unsigned lds_o[2] = {(unsigned)(mx_row(crow) * RSTR + ccol),
-                             (unsigned)(mx_row((RP + crow) & (BC - 1)) * RSTR + ccol)};
-  const unsigned g_o = (unsigned)(crow * D + ccol) * 2u;  // bytes from the pair's first row
-  uint4 rk = make_uint4(0, 0, 0, 0), rv = make_uint4(0, 0, 0, 0);
-  auto pair_active = [&](int p) { return (p >> 1) < NT && (RP * (p & 1) < BC); };
-  auto load_pair = [&](int p) __attribute__((always_inline)) {
-    if (!pair_active(p)) return;
-    int l, j0;
-    mx_tile_of(L, p >> 1, l, j0);
-    const int jp = j0 + RP * (p & 1);  // first slot of the pair (uniform)
-    const int Sl = sel3(l, L.S);
-    const char* kp = reinterpret_cast<const char*>(sel3(l, L.K)) + (unsigned)jp * (unsigned)(D * 2);
-    const char* vp = reinterpret_cast<const char*>(sel3(l, L.V)) + (unsigned)jp * (unsigned)(D * 2);
-    if (jp + RP <= Sl) {  // all rows of the pair exist (uniform)
-      rk = *reinterpret_cast<const uint4*>(kp + g_o);
-      rv = *reinterpret_cast<const uint4*>(vp + g_o);
-    } else {  // tail of the level: rows past its end are zeros (P is 0 there, 0 * garbage is not)
-      const bool valid = jp + crow < Sl;
-      const unsigned o = valid ? g_o : (unsigned)(ccol * 2) - (unsigned)jp * (unsigned)(D * 2);
-      rk = *reinterpret_cast<const uint4*>(kp + (int)o);
-      rv = *reinterpret_cast<const uint4*>(vp + (int)o);
-      if (!valid) {
-        rk = make_uint4(0, 0, 0, 0);
-        rv = make_uint4(0, 0, 0, 0);
-      }
-    }
-  };
-  int kbuf_w = 0, vbuf_w = 0;  // buffers of the tile that the next write_pair targets
-  auto write_pair = [&](int p) __attribute__((always_inline)) {
-    if (pair_active(p)) {
-      const unsigned o = lds_o[p & 1];
-      *reinterpret_cast<uint4*>(&smem[kbuf_w * SM::TSZ + o]) = rk;
-      *reinterpret_cast<uint4*>(&smem[SM::VOFF + vbuf_w * SM::TSZ + o]) = rv;
-    }
-    if (p & 1) {  // tile finished: move on to the next one's buffers
-      kbuf_w ^= 1;
-      vbuf_w = vbuf_w == 2 ? 0 : vbuf_w + 1;
-    }
-  };
-
-  if (NT > 0) {
-    // prologue: tile 0 and the first half of tile 1 in LDS, the second half in flight
-#pragma unroll
-    for (int p = 0; p < 3; ++p) {
-      load_pair(p);
-      write_pair(p);
-    }
-    load_pair(3);
-    __syncthreads();
-
-    f32x16 s_a = mx_s_unit<D>(smem, 0, qreg, li, g), s_b;
-    int vb = 0;  // V buffer of the tile being consumed
-    int l_cur, j0_cur;
-    mx_tile_of(L, 0, l_cur, j0_cur);
-    for (int T = 0; T < NT; ++T) {
-      const bf16* sK = smem + (T & 1) * SM::TSZ;
-      const bf16* sK1 = smem + ((T + 1) & 1) * SM::TSZ;
-      const bf16* sV = smem + SM::VOFF + vb * SM::TSZ;
-      const int l = l_cur, j0 = j0_cur;
-      const int Sl = sel3(l, L.S), jmax = sel3(l, L.jmax), row_lo = sel3(l, L.row_lo);
-      const float bl = sel3(l, L.bl);
-      const bool mask0 = (j0 + 32 > Sl) || (causal && j0 + 31 > row_lo);
-      const bool mask1 = (j0 + 64 > Sl) || (causal && j0 + 63 > row_lo);
-      // first half step: unit 0 of tile T; staging pair 2T+3 written, 2T+4 loaded
-      if (mask0) mx_half_step<D, true>(s_a, s_b, sK, 1, j0, jmax, bl, sV, 0, qreg, oacc, m, lsum, c, lane);
-      else mx_half_step<D, false>(s_a, s_b, sK, 1, j0, jmax, bl, sV, 0, qreg, oacc, m, lsum, c, lane);
-      write_pair(2 * T + 3);
-      load_pair(2 * T + 4);
-      __syncthreads();  // tile T+1 is complete in LDS; K buffer T&1 may be overwritten
-      // second half step: unit 1 of tile T (S^T of unit 0 of tile T+1 goes in flight)
-      if (mask1) mx_half_step<D, true>(s_b, s_a, sK1, 0, j0 + 32, jmax, bl, sV, 1, qreg, oacc, m, lsum, c, lane);
-      else mx_half_step<D, false>(s_b, s_a, sK1, 0, j0 + 32, jmax, bl, sV, 1, qreg, oacc, m, lsum, c, lane);
-      write_pair(2 * T + 4);
-      load_pair(2 * T + 5);
-      vb = vb == 2 ? 0 : vb + 1;
-      if (T + 1 < NT) mx_tile_of(L, T + 1, l_cur, j0_cur);
-    }
-    __syncthreads();  // every wave is done with the tile buffers (the epilogue reuses them)
-  }
-
-  // ---- epilogue: normalise, transpose O^T through LDS, store rows with coalesced 16-byte writes
-  lsum += xor32(lsum);
-  {
-    constexpr int OSTR = D + 8;
-    bf16* sO = smem + wave * (32 * OSTR);
-    const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
+  for (int rb = 0; rb < R; ++rb) {
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int d = 32 * db + 8 * (r >> 2) + 4 * g + (r & 3);
-        sO[li * OSTR + d] = (bf16)(oacc[db][r] * inv);
+      for (int r = 0; r < 16; ++r) oacc[rb][db][r] = 0.f;
+    row[rb].m = -INFINITY;
+    row[rb].lsum = 0.f;
+    row[rb].bl = 0.f;
+    row[rb].jmax = 0;
+  }
+
+  // ---- staging.  One load instruction fills 1 KiB of a tile (RPI rows); a wave issues IPW of
+  // them for K and IPW for V per tile.  Lane i of instruction q serves LDS row RPI q + i / CPR,
+  // chunk position i % CPR: the slot and the chunk that belong there are fixed per lane.
+  constexpr int RPI = 64 / CPR;                     // tile rows per instruction (4 or 8)
+  constexpr int IPW = (BC / RPI) / NW;              // instructions per wave, tile and tensor
+  static_assert(IPW >= 1, "every wave issues at least one load per tile and tensor");
+  unsigned dslot[IPW], dchunk[IPW];
+#pragma unroll
+  for (int e = 0; e < IPW; ++e) {
+    const int r = RPI * (IPW * wave + e) + lane / CPR;
+    dslot[e] = (unsigned)mx_row(r);
+    dchunk[e] = 16u * (unsigned)((lane % CPR) ^ mx_swz<D>(r));
+  }
+  const unsigned lds0 =
+      __builtin_amdgcn_readfirstlane((unsigned)(size_t)smem + 1024u * (unsigned)(IPW * wave));
+  int kb_w = 0, vb_w = 0;  // ring positions of the next tile to request
+  // Two cursors walk the tile stream, one for the requests and one for the tile being consumed:
+  // level, first slot, tiles left in the level, and the level's data, which is only touched when
+  // the level changes (at most twice per workgroup).
+  int rq_l = mx_next_level(L, -1), rq_j0 = 0, rq_left = 0;
+  unsigned rq_last = 0;
+  const bf16* rq_k = nullptr;
+  const bf16* rq_v = nullptr;
+  auto rq_level = [&](int l) {
+    rq_l = l; rq_j0 = 0;
+    rq_left = sel3(l, L.n); rq_last = (unsigned)(sel3(l, L.S) - 1);
+    rq_k = sel3(l, L.K); rq_v = sel3(l, L.V);
+  };
+  // Request the next tile of the stream (past its end: the last tile again, so that every wave
+  // always has the same number of loads in flight and the counted waits below stay exact).
+  // Rows past the end of a level repeat its last row: their scores are masked, and P = 0 times
+  // a finite V is 0.  request_begin fixes the addresses, request_part(q) issues load q of the
+  // 2 IPW of the tile (K first), request_end moves the cursor on.
+  unsigned rq_off[IPW];
+  const bf16* rq_kc = nullptr;
+  const bf16* rq_vc = nullptr;
+  auto request_begin = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int e = 0; e < IPW; ++e)
+      rq_off[e] = min((unsigned)rq_j0 + dslot[e], rq_last) * (unsigned)ROWB + dchunk[e];
+    rq_kc = rq_k;
+    rq_vc = rq_v;
+    if (rq_left > 1) {
+      rq_j0 += BC;
+      --rq_left;
+    } else {
+      const int nl = mx_next_level(L, rq_l);
+      if (nl < 3) rq_level(nl);
+    }
+  };
+  auto request_part = [&](int q) __attribute__((always_inline)) {
+    if (q < IPW) mx_dma16(rq_kc, rq_off[q], lds0 + (unsigned)(kb_w * SM::TSZ + 1024 * q));
+    else mx_dma16(rq_vc, rq_off[q - IPW], lds0 + (unsigned)(SM::VOFF + vb_w * SM::TSZ + 1024 * (q - IPW)));
+  };
+  auto request_end = [&]() __attribute__((always_inline)) {
+    kb_w = kb_w == SM::NKB - 1 ? 0 : kb_w + 1;
+    vb_w = vb_w == SM::NVB - 1 ? 0 : vb_w + 1;
+  };
+  auto request_tile = [&]() __attribute__((always_inline)) {
+    request_begin();
+#pragma unroll
+    for (int q = 0; q < 2 * IPW; ++q) request_part(q);
+    request_end();
+  };
+  constexpr int LPT = 2 * IPW;  // loads of a wave per tile
+
+  if (NT > 0) {
+    // lane constants of the LDS reads
+    const unsigned a0 = mx_kfrag0<D>(li, g);
+    unsigned x_lo, x_hi;
+    {
+      const int ti = lane & 15, gsel = (lane >> 4) & 1;
+      const int cl = 2 * gsel + ((ti >> 1) & 1), sub = 8 * (ti & 1);
+      const int r_lo = 4 * (ti >> 2) + g, r_hi = r_lo + 2;  // rows of slots 4 g + ti / 4 (+ 8)
+      x_lo = (unsigned)(r_lo * ROWB + 16 * (cl ^ (mx_swz<D>(r_lo) & 3)) + sub) ^
+             (unsigned)(16 * (mx_swz<D>(r_lo) & ~3));
+      x_hi = (unsigned)(r_hi * ROWB + 16 * (cl ^ (mx_swz<D>(r_hi) & 3)) + sub) ^
+             (unsigned)(16 * (mx_swz<D>(r_hi) & ~3));
+    }
+
+    // prologue: tiles 0..2 requested, tile 0 landed
+    rq_level(rq_l);
+    request_tile();
+    request_tile();
+    request_tile();
+    mx_wait_loads<2 * LPT>();
+    __syncthreads();
+
+    int kb = 0, vb = 0;  // ring positions of the tile being consumed
+    f32x16 s_a[R], s_b[R];
+#pragma unroll
+    for (int rb = 0; rb < R; ++rb) s_a[rb] = mx_s_unit<D>(smem, a0, qreg[rb]);
+    bf16x8 fr[KK];       // K fragments of unit 1 of tile 0
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk)
+      fr[kk] = *reinterpret_cast<const bf16x8*>(smem + 32 * ROWB + (a0 ^ (unsigned)(kk << 5)));
+    int l = -1, j0 = 0, left = 1, Sl = 0, row_lo = 0;
+    for (int T = 0; T < NT; ++T) {
+      mx_wait_loads<LPT>();  // this wave's part of tile T+1 has landed (T+2 may be in flight)
+      __syncthreads();       // tile T+1 complete; K buffer of T and V buffer of T-1 are free
+      request_begin();       // tile T+3, issued in four places of the two half steps
+      if (left > 1) {
+        j0 += BC;
+        --left;
+      } else {  // first tile of a level (T < NT: there is one)
+        l = mx_next_level(L, l);
+        j0 = 0;
+        left = sel3(l, L.n); Sl = sel3(l, L.S); row_lo = sel3(l, L.row_lo);
+#pragma unroll
+        for (int rb = 0; rb < R; ++rb) {
+          row[rb].jmax = l == 0 ? jmax0[rb] : (l == 1 ? jmax1[rb] : jmax2[rb]);
+          row[rb].bl = l == 0 ? bl0[rb] : (l == 1 ? bl1[rb] : bl2[rb]);
+        }
       }
+      const int kb1 = kb == SM::NKB - 1 ? 0 : kb + 1;
+      const char* sK1 = smem + kb1 * SM::TSZ;
+      const char* sV = smem + SM::VOFF + vb * SM::TSZ;
+      const bool mask0 = (j0 + 32 > Sl) || (causal && j0 + 31 > row_lo);
+      const bool mask1 = (j0 + 64 > Sl) || (causal && j0 + 63 > row_lo);
+      // parts of the request per section: 2 IPW loads over 4 sections
+      constexpr int PPS = (2 * IPW + 3) / 4;
+      auto part = [&](int sct) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = sct * PPS; q < (sct + 1) * PPS && q < 2 * IPW; ++q) request_part(q);
+      };
+      auto p0 = [&]() __attribute__((always_inline)) { part(0); };
+      auto p1 = [&]() __attribute__((always_inline)) { part(1); };
+      auto p2 = [&]() __attribute__((always_inline)) { part(2); };
+      auto p3 = [&]() __attribute__((always_inline)) { part(3); };
+      // first half step: unit 0 of tile T; S^T of its unit 1; K fragments of unit 0 of tile T+1
+      if (mask0) mx_half_step<D, R, true, 0>(p0, p1, s_a, s_b, fr, sK1, a0, j0, sV, x_lo, x_hi, qreg, oacc, row, c, lane);
+      else mx_half_step<D, R, false, 0>(p0, p1, s_a, s_b, fr, sK1, a0, j0, sV, x_lo, x_hi, qreg, oacc, row, c, lane);
+      // second half step: unit 1 of tile T; S^T of unit 0 of tile T+1; K fragments of its unit 1
+      if (mask1) mx_half_step<D, R, true, 1>(p2, p3, s_b, s_a, fr, sK1 + 32 * ROWB, a0, j0 + 32, sV, x_lo, x_hi, qreg, oacc, row, c, lane);
+      else mx_half_step<D, R, false, 1>(p2, p3, s_b, s_a, fr, sK1 + 32 * ROWB, a0, j0 + 32, sV, x_lo, x_hi, qreg, oacc, row, c, lane);
+      request_end();
+      kb = kb1;
+      vb = vb == SM::NVB - 1 ? 0 : vb + 1;
+    }
+    mx_wait_loads<0>();  // the surplus requests of the last tiles must land before LDS is reused
+    __syncthreads();     // every wave is done with the tile buffers (the epilogue reuses them)
+  }
+
+  // ---- epilogue: normalise, transpose O^T through LDS, store rows with coalesced 16-byte writes
+  {
+    constexpr int OSTR = D + 8;
+    bf16* sO = reinterpret_cast<bf16*>(smem) + wave * (32 * R * OSTR);
+    float lsum[R];
+#pragma unroll
+    for (int rb = 0; rb < R; ++rb) {
+      lsum[rb] = row[rb].lsum + xor32(row[rb].lsum);
+      const float inv = lsum[rb] > 0.f ? 1.f / lsum[rb] : 0.f;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int d = 32 * db + 8 * (r >> 2) + 4 * g + (r & 3);
+          sO[(32 * rb + li) * OSTR + d] = (bf16)(oacc[rb][db][r] * inv);
+        }
+    }
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < 32 * CPR / 64; ++i) {
+    for (int i = 0; i < 32 * R * CPR / 64; ++i) {
       const int item = lane + 64 * i;
-      const int row = item / CPR, ch = item % CPR;
-      const uint4 v = *reinterpret_cast<const uint4*>(&sO[row * OSTR + ch * 8]);
-      if (tw0 + row < Tq)
-        *reinterpret_cast<uint4*>(O + (bh * (long)Tq + tw0 + row) * D + ch * 8) = v;
+      const int rr = item / CPR, ch = item % CPR;
+      const uint4 v = *reinterpret_cast<const uint4*>(&sO[rr * OSTR + ch * 8]);
+      if (tw0 + rr < Tq)
+        *reinterpret_cast<uint4*>(O + (bh * (long)Tq + tw0 + rr) * D + ch * 8) = v;
     }
-    if (LSE && g == 0 && tq < Tq)
-      LSE[bh * (long)Tq + tq] = lsum > 0.f ? (m + __log2f(lsum)) * kLn2 : -INFINITY;
+#pragma unroll
+    for (int rb = 0; rb < R; ++rb) {
+      const int tq = tw0 + 32 * rb + li;
+      if (LSE && g == 0 && tq < Tq)
+        LSE[bh * (long)Tq + tq] = lsum[rb] > 0.f ? (row[rb].m + __log2f(lsum[rb])) * kLn2 : -INFINITY;
+    }
   }
 }
 
-template <int D>
+template <int D, int R>
 hipError_t launch_mix_t(const MixArgs& a, hipStream_t st) {
-  constexpr int BR = MX_NW * 32;
+  constexpr int BR = MX_BR;
   const int n_qtiles = (a.Tq + BR - 1) / BR;
   const long nblocks = (long)n_qtiles * ((a.BH + 7) / 8) * 8;
   const int interleave = nblocks <= 2 * 256 ? 1 : 0;
-  const size_t smem = (size_t)MixSmem<D>::TOTAL * sizeof(bf16);
+  const size_t smem = (size_t)MixSmem<D>::TOTAL;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mix_bf16_kernel<D>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&mix_bf16_kernel<D, R>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -403,7 +556,7 @@ hipError_t launch_mix_t(const MixArgs& a, hipStream_t st) {
     Vp[l] = has ? a.V[l] : anyV;
     Sp[l] = has ? a.S[l] : 0;
   }
-  hipLaunchKernelGGL((mix_bf16_kernel<D>), dim3((unsigned)nblocks), dim3(MX_NT), smem, st,
+  hipLaunchKernelGGL((mix_bf16_kernel<D, R>), dim3((unsigned)nblocks), dim3(MixShape<R>::NT), smem, st,
                      (const bf16*)a.Q, (const bf16*)Kp[0], (const bf16*)Kp[1], (const bf16*)Kp[2],
                      (const bf16*)Vp[0], (const bf16*)Vp[1], (const bf16*)Vp[2], a.G, (bf16*)a.O,
                      a.LSE, a.Tq, Sp[0], Sp[1], Sp[2], a.causal, a.scale * kLog2e, n_qtiles, a.BH,
@@ -415,7 +568,7 @@ hipError_t launch_mix_t(const MixArgs& a, hipStream_t st) {
 
 hipError_t launch_mix_bf16(const MixArgs& a, hipStream_t st) {
   if (a.BH == 0 || a.Tq == 0) return hipSuccess;
-  return a.d == 128 ? launch_mix_t<128>(a, st) : launch_mix_t<64>(a, st);
+  return a.d == 128 ? launch_mix_t<128, MX_R>(a, st) : launch_mix_t<64, 1>(a, st);
 }
 
 }  // namespace mka
