@@ -189,34 +189,39 @@ def main():
         O3 = torch.empty_like(inp3["Q"])
         L3 = torch.empty((B3, H3, T3), device=dev)
         mka.mka_route(inp3["Q"], inp3["W_r"], inp3["b_r"], G=G3, want_idx=False)
+        from paper_2603_20586_amd.binding import MKA_OP_FWD
+        shp3 = _shape(inp3["Q"], T3, None, True, inp3["scale"])
+        # the library recommends the materialised route here (Kf, Vf once to the workspace, then
+        # attention over that stream); the folded route (fusion inside the attention kernel, no
+        # workspace) is timed beside it
+        ws3 = torch.empty(mka.mka_workspace_bytes(MKA_OP_FWD, shp3), dtype=torch.uint8, device=dev)
+        assert ws3.numel() > 0
         ms3 = time_region(lambda: mka.mka_fused_attn_fwd(
             inp3["Q"], inp3["K"], inp3["V"], None, None, G=G3, causal=True, scale=inp3["scale"],
-            O=O3, LSE=L3, want_idx=False), 5, 2)
+            O=O3, LSE=L3, want_idx=False, workspace=ws3), 5, 2)
+        ms3f = time_region(lambda: mka.mka_fused_attn_fwd(
+            inp3["Q"], inp3["K"], inp3["V"], None, None, G=G3, causal=True, scale=inp3["scale"],
+            O=O3, LSE=L3, want_idx=False, materialise=False), 5, 2)
         fl3 = 4 * d * attn_pairs(T3, T3) * B3 * H3
-        workloads["C3_prefill_fwd"] = {"ms": ms3, "tflops": fl3 / ms3 / 1e9,
-                                       "tokens_per_s": B3 * T3 / (ms3 * 1e-3)}
-        rooflines["C3_fwd"] = roof_mfma(fl3, ms3, "fwd_bf16_kernel")
+        Kf3 = torch.empty_like(inp3["K"][0])
+        Vf3 = torch.empty_like(inp3["V"][0])
+        msk = time_region(lambda: mka.mka_fuse_kv(inp3["K"], inp3["V"], G3, Kf=Kf3, Vf=Vf3), 5, 2)
+        del Kf3, Vf3, ws3
+        workloads["C3_prefill_fwd"] = {
+            "route": "materialised", "ms": ms3, "tflops": fl3 / ms3 / 1e9,
+            "tokens_per_s": B3 * T3 / (ms3 * 1e-3), "prefuse_ms": msk,
+            "prefuse_gbps": (8 * B3 * H3 * T3 * d * 2 + 12 * B3 * H3 * T3) / msk / 1e6}
+        workloads["C3_prefill_fwd_folded"] = {"route": "folded", "ms": ms3f,
+                                              "tflops": fl3 / ms3f / 1e9}
+        rooflines["C3_fwd"] = roof_mfma(fl3, ms3, "prefuse_kernel + mix_bf16_kernel (both in the events)")
+        rooflines["C3_fwd_folded"] = roof_mfma(fl3, ms3f, "fwd_bf16_kernel")
         # the same shape through the per-query gated mixture over the three memories (3x the
-        # pairs) and through plain attention over one memory (what a pre-fused stream would cost)
+        # pairs) and through plain attention over one memory
         msm = time_region(lambda: mka.mka_mixture_attn_fwd(
             inp3["Q"], inp3["K"], inp3["V"], G3, causal=True, scale=inp3["scale"], O=O3, LSE=L3), 5, 2)
         msp = time_region(lambda: mka.mka_mixture_attn_fwd(
             inp3["Q"], [inp3["K"][0], None, None], [inp3["V"][0], None, None], None, causal=True,
             scale=inp3["scale"], O=O3, LSE=L3), 5, 2)
-        # the materialised alternative to folding: fuse once into a bf16 stream, then plain attention
-        Kf3 = torch.empty_like(inp3["K"][0])
-        Vf3 = torch.empty_like(inp3["V"][0])
-
-        def prefuse_then_attend():
-            mka.mka_fuse_kv(inp3["K"], inp3["V"], G3, Kf=Kf3, Vf=Vf3)
-            mka.mka_mixture_attn_fwd(inp3["Q"], [Kf3, None, None], [Vf3, None, None], None,
-                                     causal=True, scale=inp3["scale"], O=O3, LSE=L3)
-        msf = time_region(prefuse_then_attend, 5, 2)
-        msk = time_region(lambda: mka.mka_fuse_kv(inp3["K"], inp3["V"], G3, Kf=Kf3, Vf=Vf3), 5, 2)
-        workloads["C3_prefuse_then_attention_fwd"] = {
-            "ms": msf, "tflops": fl3 / msf / 1e9, "prefuse_ms": msk,
-            "prefuse_gbps": (8 * B3 * H3 * T3 * d * 2 + 12 * B3 * H3 * T3) / msk / 1e6}
-        del Kf3, Vf3
         workloads["C3_gated_mixture_fwd"] = {"ms": msm, "tflops": 3 * fl3 / msm / 1e9}
         workloads["C3_plain_attention_fwd"] = {"ms": msp, "tflops": fl3 / msp / 1e9}
         rooflines["C3_mixture"] = roof_mfma(3 * fl3, msm, "mix_bf16_kernel")
@@ -230,10 +235,13 @@ def main():
         L5 = torch.empty((B5, H5, T5), device=dev)
         shp5 = _shape(inp5["Q"], T5, None, True, inp5["scale"])
         ws5 = torch.empty(mka.mka_workspace_bytes(MKA_OP_BWD, shp5), dtype=torch.uint8, device=dev)
+        ws5f = torch.empty(max(256, mka.mka_workspace_bytes(MKA_OP_FWD, shp5)), dtype=torch.uint8,
+                           device=dev)
 
         def f5():
             mka.mka_fused_attn_fwd(inp5["Q"], inp5["K"], inp5["V"], inp5["W_r"], inp5["b_r"], G=G5,
-                                   causal=True, scale=inp5["scale"], O=O5, LSE=L5, want_idx=False)
+                                   causal=True, scale=inp5["scale"], O=O5, LSE=L5, want_idx=False,
+                                   workspace=ws5f)
 
         grads5 = {}
 
@@ -252,7 +260,7 @@ def main():
             "tokens_per_s": B5 * T5 / ((msf5 + msb5) * 1e-3)}
         rooflines["C5_bwd"] = roof_mfma(10 * d * p5, msb5,
                                         "bwd_main_kernel (+prep/finish/reduce in the events)")
-        del inp5, G5, O5, L5, ws5, grads5
+        del inp5, G5, O5, L5, ws5, ws5f, grads5
         torch.cuda.empty_cache()
 
         # C4: bandwidth-bound decode, 64 steps with an appended L1 entry per step

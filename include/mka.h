@@ -55,7 +55,13 @@ typedef enum {
 
 typedef enum { MKA_F32 = 0, MKA_BF16 = 1 } mka_dtype;
 
-typedef enum { MKA_OP_ROUTE = 0, MKA_OP_FWD = 1, MKA_OP_DECODE = 2, MKA_OP_BWD = 3 } mka_op;
+typedef enum {
+  MKA_OP_ROUTE = 0,
+  MKA_OP_FWD = 1,              /* what mka_fused_attn_fwd should be given for this shape  */
+  MKA_OP_DECODE = 2,
+  MKA_OP_BWD = 3,
+  MKA_OP_FWD_MATERIALISED = 4  /* what makes mka_fused_attn_fwd write Kf, Vf (see there)   */
+} mka_op;
 
 /* Problem shape of route / forward / backward. */
 typedef struct {
@@ -107,8 +113,17 @@ mka_status mka_route(const void* Q, const float* W_r, const float* b_r, float* G
  *   O     out    [B,H,Tq,d] dtype
  *   LSE   out    [B,H,Tq] f32, log-sum-exp of the scaled visible scores; NULL = skip
  *   idx_out out  [B,H,Tq] int32 gate argmax (needs W_r); NULL = skip
- * The router and the fusion are folded into the attention launch sequence; Kf
- * and Vf are never written to memory. */
+ * Two routes compute the same thing (equal up to rounding order).  Folded: the
+ * fusion happens tile by tile inside the attention kernel and Kf, Vf are never
+ * written to memory; needs no workspace.  Materialised (bf16, d = 64 or 128): Kf
+ * and Vf are written once to the workspace (step 6 as the algorithm states it)
+ * and the attention kernel streams them; taken when `workspace` holds at least
+ * mka_workspace_bytes(MKA_OP_FWD_MATERIALISED, shape) bytes (256-byte aligned),
+ * else the folded route runs.  mka_workspace_bytes(MKA_OP_FWD, shape) is that
+ * size when the library expects the materialised route to be the faster one
+ * (long query blocks, where every query tile would fuse the same K/V tiles
+ * again) and 0 otherwise, so a caller that sizes the workspace with it gets the
+ * faster route.  The workspace contents are scratch: nothing is kept. */
 mka_status mka_fused_attn_fwd(const void* Q, const void* const K[3], const void* const V[3],
                               const float* W_r, const float* b_r, float* G, void* O, float* LSE,
                               int32_t* idx_out, const mka_shape* shape, void* workspace,

@@ -11,7 +11,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libmka.so")
 
 MKA_F32, MKA_BF16 = 0, 1
-MKA_OP_ROUTE, MKA_OP_FWD, MKA_OP_DECODE, MKA_OP_BWD = 0, 1, 2, 3
+MKA_OP_ROUTE, MKA_OP_FWD, MKA_OP_DECODE, MKA_OP_BWD, MKA_OP_FWD_MATERIALISED = 0, 1, 2, 3, 4
 
 
 class MkaError(RuntimeError):
@@ -159,9 +159,13 @@ def mka_route(Q, W_r, b_r=None, S=None, G=None, want_idx=True):
 
 
 def mka_fused_attn_fwd(Q, K, V, W_r=None, b_r=None, G=None, len3=None, causal=True, scale=1.0,
-                       want_lse=True, want_idx=True, O=None, LSE=None, idx=None):
+                       want_lse=True, want_idx=True, O=None, LSE=None, idx=None, workspace=None,
+                       materialise=None):
     """Route-fused attention forward.  K, V: sequences of three tensors (None = level absent).
-    With W_r the router runs on Q and fills G's last Tq rows.  Returns (O, LSE, G, idx)."""
+    With W_r the router runs on Q and fills G's last Tq rows.  Returns (O, LSE, G, idx).
+    `workspace`: uint8 device tensor handed to the library as it is.  Without one, `materialise`
+    picks its size: None = what the library recommends for the shape, True = enough for the
+    materialised route, False = none (folded route)."""
     _dev_check(Q, W_r, b_r, G, *K, *V)
     B, H, Tq, d = Q.shape
     ref = next(k for k in K if k is not None)
@@ -178,9 +182,16 @@ def mka_fused_attn_fwd(Q, K, V, W_r=None, b_r=None, G=None, len3=None, causal=Tr
         idx = torch.empty((B, H, Tq), dtype=torch.int32, device=Q.device)
     s = _shape(Q, S, len3, causal, scale)
     k3, v3 = _p3(K), _p3(V)
+    if workspace is None and materialise is not False:
+        op = MKA_OP_FWD_MATERIALISED if materialise else MKA_OP_FWD
+        nbytes = mka_workspace_bytes(op, s)
+        if nbytes:
+            workspace = _workspace(nbytes, Q.device)
     _check(lib().mka_fused_attn_fwd(_ptr(Q), ctypes.byref(k3), ctypes.byref(v3), _ptr(W_r),
                                     _ptr(b_r), _ptr(G), _ptr(O), _ptr(LSE), _ptr(idx),
-                                    ctypes.byref(s), None, 0, _stream()), "mka_fused_attn_fwd")
+                                    ctypes.byref(s), _ptr(workspace),
+                                    workspace.numel() if workspace is not None else 0, _stream()),
+           "mka_fused_attn_fwd")
     return O, LSE, G, idx
 
 

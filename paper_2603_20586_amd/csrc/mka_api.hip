@@ -51,13 +51,29 @@ const char* mka_status_string(mka_status st) {
   return "MKA_ERR_?: unknown status";
 }
 
+// Kf and Vf of the materialised forward: [B,H,S,d] bf16 each, 256-byte aligned.
+static size_t fwd_materialise_bytes(const mka_shape* s) {
+  if (s->dtype != MKA_BF16 || (s->d != 64 && s->d != 128) || s->S <= 0) return 0;
+  return 2 * align256((size_t)s->B * s->H * (size_t)s->S * (size_t)s->d * 2);
+}
+// Fusing once costs one pass over the six K/V tensors; folding it into the attention kernel
+// costs about a quarter of the attention time (every query tile fuses its K/V tiles again, in
+// registers).  The two break even near 3072 causal query rows (half that without the mask).
+static bool fwd_prefers_materialised(const mka_shape* s) {
+  if (fwd_materialise_bytes(s) == 0) return false;
+  return (long)s->Tq * (s->causal ? 1 : 2) >= 3072;
+}
+
 size_t mka_workspace_bytes(mka_op op, const mka_shape* s) {
   if (!s || s->B <= 0 || s->H <= 0 || s->d <= 0) return 0;
   const size_t bh = (size_t)s->B * s->H;
   switch (op) {
     case MKA_OP_ROUTE:
-    case MKA_OP_FWD:
       return 0;
+    case MKA_OP_FWD:
+      return fwd_prefers_materialised(s) ? fwd_materialise_bytes(s) : 0;
+    case MKA_OP_FWD_MATERIALISED:
+      return fwd_materialise_bytes(s);
     case MKA_OP_DECODE:
       return align256(bh * mka::kMaxSplits * (size_t)(s->d + 2) * sizeof(float));
     case MKA_OP_BWD:
@@ -93,14 +109,13 @@ mka_status mka_fused_attn_fwd(const void* Q, const void* const K[3], const void*
                               const float* W_r, const float* b_r, float* G, void* O, float* LSE,
                               int32_t* idx_out, const mka_shape* shape, void* workspace,
                               size_t workspace_bytes, void* stream) {
-  (void)workspace;
-  (void)workspace_bytes;
   bool empty = false;
   const mka_status st = check_shape(shape, &empty);
   if (st != MKA_OK) return st;
   if (!Q || !K || !V || !G || !O) return MKA_ERR_NULL;
   if (idx_out && !W_r) return MKA_ERR_NULL;
   if (!aligned16(Q) || !aligned16(G) || !aligned16(O) || !aligned16(LSE)) return MKA_ERR_ALIGN;
+  if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return MKA_ERR_ALIGN;
   mka::FwdArgs a;
   for (int l = 0; l < 3; ++l) {
     if (!aligned16(K[l]) || !aligned16(V[l])) return MKA_ERR_ALIGN;
@@ -119,6 +134,29 @@ mka_status mka_fused_attn_fwd(const void* Q, const void* const K[3], const void*
     r.Q = Q; r.W_r = W_r; r.b_r = b_r; r.G = G; r.idx = idx_out;
     r.BH = BH; r.Tq = shape->Tq; r.S = shape->S; r.d = shape->d; r.bf16 = is_bf16;
     if (mka::launch_route(r, hs) != hipSuccess) return MKA_ERR_LAUNCH;
+  }
+  const size_t mat_bytes = fwd_materialise_bytes(shape);
+  if (workspace && mat_bytes > 0 && workspace_bytes >= mat_bytes) {
+    // Alg. 2 step 6 as written: Kf, Vf once to the workspace, then attention over that stream
+    mka::PrefuseArgs pf;
+    for (int l = 0; l < 3; ++l) {
+      pf.K[l] = a.K[l]; pf.V[l] = a.V[l]; pf.len[l] = a.len[l];
+    }
+    pf.G = G;
+    pf.Kf = workspace;
+    pf.Vf = static_cast<char*>(workspace) + mat_bytes / 2;
+    pf.BH = BH; pf.S = shape->S; pf.d = shape->d;
+    if (mka::launch_prefuse(pf, hs) != hipSuccess) return MKA_ERR_LAUNCH;
+    mka::MixArgs mx;
+    mx.Q = Q;
+    mx.K[0] = pf.Kf; mx.V[0] = pf.Vf; mx.S[0] = shape->S;
+    mx.K[1] = mx.K[2] = mx.V[1] = mx.V[2] = nullptr;
+    mx.S[1] = mx.S[2] = 0;
+    mx.G = nullptr; mx.O = O; mx.LSE = LSE;
+    mx.BH = BH; mx.Tq = shape->Tq; mx.d = shape->d;
+    mx.causal = shape->causal ? 1 : 0;
+    mx.scale = shape->scale;
+    return mka::launch_mix_bf16(mx, hs) == hipSuccess ? MKA_OK : MKA_ERR_LAUNCH;
   }
   a.Q = Q; a.G = G; a.O = O; a.LSE = LSE;
   a.BH = BH; a.Tq = shape->Tq; a.S = shape->S; a.d = shape->d;

@@ -78,7 +78,7 @@ def pmc(src, dst, cmd):
 # roofline key of bench.py -> (kernel, workgroups of its launch at that workload)
 TRAFFIC_KEYS = {
     "C2_fwd": ("mka::fwd_bf16_kernel<128>", 512),       # 64 heads x 8 query tiles
-    "C3_fwd": ("mka::fwd_bf16_kernel<128>", 1024),      # 32 heads x 32 query tiles
+    "C3_fwd_folded": ("mka::fwd_bf16_kernel<128>", 1024),  # 32 heads x 32 query tiles
     "C2_bwd": ("mka::bwd_main_kernel<128>", 1024),      # 64 heads x 16 KV tiles
     "C5_bwd": ("mka::bwd_main_kernel<128>", 4096),      # 128 heads x 32 KV tiles
     "C4_decode": ("mka::decode_split_kernel<bf32,16,128>", 2048),  # 4 splits x 512 heads

@@ -100,7 +100,13 @@ def test_route_and_bwd_reject_bad_arguments(m):
     assert args(_shape(m), None, 0) == 5                  # workspace required
     assert args(_shape(m), FAKE, 16) == 5
     assert m.mka_workspace_bytes(3, _shape(m)) > 0
+    # forward: no workspace recommended for a short block; the materialised route's size is
+    # two [B,H,S,d] bf16 tensors; long blocks get it recommended; f32 has no such route
     assert m.mka_workspace_bytes(1, _shape(m)) == 0
+    assert m.mka_workspace_bytes(4, _shape(m)) == 2 * 1 * 2 * 16 * 64 * 2
+    long_ = _shape(m, Tq=4096, S=4096, d=128)
+    assert m.mka_workspace_bytes(1, long_) == m.mka_workspace_bytes(4, long_) == 2 * 2 * 4096 * 128 * 2
+    assert m.mka_workspace_bytes(4, _shape(m, dtype=0)) == 0
 
 
 def test_decode_rejects_bad_arguments(m):

@@ -98,15 +98,18 @@ def test_fwd_f32_shapes(mka, oracle, d, Tq, S, causal, len3):
     (150, 150, True, None),      # three kv tiles: every stage of the tile pipeline's ramp-up
     (40, 250, True, [250, 250, 130]),  # a level that ends in the middle of a tile
     (1, 1, True, None), (1, 70, True, None)])
-def test_fwd_bf16_shapes(mka, oracle, d, Tq, S, causal, len3):
-    announce(f"fwd bf16 d={d} Tq={Tq} S={S} causal={causal} len={len3}")
+@pytest.mark.parametrize("materialise", [False, True])
+def test_fwd_bf16_shapes(mka, oracle, d, Tq, S, causal, len3, materialise):
+    """Both routes of the forward: fusion folded into the attention kernel, and Kf / Vf written
+    once to the workspace and streamed by the attention kernel."""
+    announce(f"fwd bf16 d={d} Tq={Tq} S={S} causal={causal} len={len3} materialise={materialise}")
     inp = si.prefill_inputs(2, 2, Tq, S, d, dtype="bf16", seed=7, device="cuda")
     W = inp["W_r"] * 10.0  # visibly non-uniform gates
     inp["W_r"] = W
     Gprev = torch.softmax(torch.randn((2, 2, S, 3), device="cuda"), -1)
     O, LSE, G, idx = mka.mka_fused_attn_fwd(inp["Q"], inp["K"], inp["V"], W, inp["b_r"],
                                             G=Gprev.clone(), len3=len3, causal=causal,
-                                            scale=inp["scale"])
+                                            scale=inp["scale"], materialise=materialise)
     torch.cuda.synchronize()
     Oref, LSEref, Gref, idxref = _oracle_fwd(oracle, inp, S, len3, causal, G_prev=Gprev.cpu())
     assert max_abs(G, Gref) <= GATE_ATOL
