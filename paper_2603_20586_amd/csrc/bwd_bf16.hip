@@ -11,19 +11,20 @@
 //   dQ[t]   += sum_l dg[j(t),l] W_r[:,l]   dW_r = sum Q[t]^T dg   db_r = sum dg   (new slots only)
 //
 // Launch sequence:
-//   prep    D = rowsum(dO*O); zero the f32 dQ accumulator
-//   main    one workgroup owns 128 KV slots (four blocks of 32): fuses its Kf/Vf ONCE, keeps them
-//           as MFMA B operands in registers, then walks over the 32-row query tiles that can
-//           see it, three tiles in flight and one barrier per tile.  Two waves per slot block:
-//           the "V" wave computes S = Q Kf^T -> P -> dVf^T += dO^T P for tile i and hands P^T
-//           over through LDS; the "K" wave, one tile behind, computes dP = dO Vf^T,
-//           dS = P (dP - D), dKf^T += Q^T dS and publishes dS^T; the V waves then contract
-//           dQ = dS Kf over all 128 slots for tile i-2 and add it to the f32 accumulator with
-//           atomics.  Q / dO tiles are kept row-major only: the operands that contract over
-//           query rows (dO^T, Q^T) and over slots (dS) are read with transposing LDS loads.
-//           The kernel is bound by the rate of the f32 atomics (performed beyond the L2, about
-//           3.4e11 elements/s on this part), not by the matrix pipe.
+//   prep    D = rowsum(dO*O)
+//   main    one workgroup owns 128 KV slots (four blocks of 32): fuses its Kf/Vf ONCE (and
+//           writes them to the workspace for the dQ kernel), keeps them as MFMA B operands in
+//           registers, then walks over the 32-row query tiles that can see it, three tiles in
+//           flight and one barrier per tile.  Two waves per slot block: the "V" wave computes
+//           S = Q Kf^T -> P -> dVf^T += dO^T P for tile i and hands P^T over through LDS; the
+//           "K" wave, one tile behind, computes dP = dO Vf^T, dS = P (dP - D),
+//           dKf^T += Q^T dS.  Q / dO tiles are kept row-major only: the operands that contract
+//           over query rows (dO^T, Q^T) are read with transposing LDS loads.
 //           Epilogue: un-fusion, dlam, dg through LDS, coalesced accesses.
+//   dq      (its own file) query-stationary: S, dP a second time, dQacc = sum_j dS Kf in
+//           registers.  Adding dQ from the main kernel instead needs one f32 atomic per (KV
+//           tile, row, head dim); they retire at about one element per clock and compute unit
+//           and took four fifths of that kernel's time.
 //   finish  dQ = tau*acc + dg W_r^T -> bf16; per-workgroup partial sums of Q^T dg and dg
 //   reduce  fixed-order sum of the partials -> dW_r, db_r   (deterministic)
 #include "fuse_tile.h"
@@ -45,8 +46,7 @@ __device__ __forceinline__ int swap23(int i) {
 template <int D>
 __global__ __launch_bounds__(256) void bwd_prep_kernel(const bf16* __restrict__ dO,
                                                        const bf16* __restrict__ O,
-                                                       float* __restrict__ Dvec,
-                                                       float* __restrict__ dQacc, long rows) {
+                                                       float* __restrict__ Dvec, long rows) {
   constexpr int CPR = D / 8;
   const long item = (long)blockIdx.x * 256 + threadIdx.x;
   const long row = item / CPR;
@@ -58,9 +58,6 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(const bf16* __restrict__ 
     unpack8(*reinterpret_cast<const uint4*>(O + row * D + cc * 8), b);
 #pragma unroll
     for (int e = 0; e < 8; ++e) part = fmaf(a[e], b[e], part);
-    float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
-    *reinterpret_cast<float4*>(dQacc + row * D + cc * 8) = z;
-    *reinterpret_cast<float4*>(dQacc + row * D + cc * 8 + 4) = z;
   }
   part = group_sum<CPR>(part);  // CPR consecutive lanes hold one row
   if (row < rows && cc == 0) Dvec[row] = part;
@@ -71,21 +68,18 @@ template <int D>
 struct BwdSmem {
   static constexpr int BR = 32;          // query rows per tile
   static constexpr int RSTR = D + 8;     // row-major Q / dO tiles (rows permuted, see tile_row)
-  static constexpr int SSTR = BCB + 8;   // Kf^T
   static constexpr int QBUF = BR * RSTR;
-  static constexpr int SBUF = BCB * BR;  // P^T / dS^T tile: [slot][row], 64-byte rows, chunks rotated
-  // Q, dO (and the LSE / D rows) live for three iterations: triple-buffered; P^T, dS^T for two
+  static constexpr int SBUF = BCB * BR;  // P^T tile: [slot][row], 64-byte rows, chunks rotated
+  // Q, dO (and the LSE / D rows) live for three iterations: triple-buffered; P^T for two
   static constexpr int OFF_Q = 0;
   static constexpr int OFF_DO = OFF_Q + 3 * QBUF;
   static constexpr int OFF_P = OFF_DO + 3 * QBUF;
-  static constexpr int OFF_DS = OFF_P + 2 * SBUF;
-  static constexpr int LOOP_END = OFF_DS + 2 * SBUF;
+  static constexpr int LOOP_END = OFF_P + 2 * SBUF;
   // set-up only: row-major Kf and Vf of the workgroup's 128 slots
   static constexpr int OFF_KROW = 0;
   static constexpr int OFF_VROW = BCB * RSTR;
   static constexpr int SETUP_END = 2 * BCB * RSTR;
-  static constexpr int OFF_KT = LOOP_END > SETUP_END ? LOOP_END : SETUP_END;  // persistent Kf^T
-  static constexpr int TOTAL = OFF_KT + D * SSTR;  // bf16 elements
+  static constexpr int TOTAL = LOOP_END > SETUP_END ? LOOP_END : SETUP_END;  // bf16 elements
 };
 
 // LDS row of query row t (0..31) of a Q / dO tile.  The tiles are read two ways: as MFMA A
@@ -117,20 +111,20 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
     const bf16* __restrict__ V1, const bf16* __restrict__ V2, const float* __restrict__ G,
     const float* __restrict__ LSE, const float* __restrict__ Dvec, bf16* __restrict__ dK0,
     bf16* __restrict__ dK1, bf16* __restrict__ dK2, bf16* __restrict__ dV0, bf16* __restrict__ dV1,
-    bf16* __restrict__ dV2, float* __restrict__ dQacc, float* __restrict__ dgate, int Tq, int S,
+    bf16* __restrict__ dV2, bf16* __restrict__ Kf_out, bf16* __restrict__ Vf_out,
+    float* __restrict__ dgate, int Tq, int S,
     int len0, int len1, int len2, int causal, float c, float tau, int n_kvtiles, int BH) {
   using L = BwdSmem<D>;
-  constexpr int BR = L::BR, RSTR = L::RSTR, SSTR = L::SSTR;
+  constexpr int BR = L::BR, RSTR = L::RSTR;
   constexpr int CPR = D / 8, KK = D / 16, DB = D / 32, NT = 512;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16* smem = reinterpret_cast<bf16*>(smem_raw);
-  bf16* sKT = smem + L::OFF_KT;
   float* sL = reinterpret_cast<float*>(smem + L::TOTAL);  // [3][BR] LSE in log2 units
   float* sDv = sL + 3 * BR;                               // [3][BR] D
 
   // 8 waves = 2 per SIMD.  Waves 0-3 (role V) and 4-7 (role K) each own the same four blocks
-  // of 32 slots: role V computes S -> P -> dVf^T and the dQ contraction, role K (one tile
-  // behind, P^T through LDS) dP -> dS -> dKf^T, and stages the query tiles.  A wave so holds one
+  // of 32 slots: role V computes S -> P -> dVf^T, role K (one tile behind, P^T through LDS)
+  // dP -> dS -> dKf^T, and stages the query tiles.  A wave so holds one
   // accumulator set and one B operand instead of two, which is what lets two waves share a SIMD
   // and hide each other's LDS / MFMA latency.
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
@@ -153,6 +147,7 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   const int jmine = J0 + 32 * sw + li;  // the slot this lane owns in S / dP / dVf^T / dKf^T
 
   // ---- set-up: fuse the 128 slots once.  Item = (4 consecutive slots, 16-byte chunk).
+  // [B*H,S,d] of the workspace has the layout of the K / V tensors: element offsets are shared.
   {
     bf16* sKrow = smem + L::OFF_KROW;
     bf16* sVrow = smem + L::OFF_VROW;
@@ -179,15 +174,13 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
         }
         fuse8(rk, g0, g1, g2, kf[u]);
         fuse8(rv, g0, g1, g2, vf[u]);
-        *reinterpret_cast<uint4*>(&sKrow[(sg * 4 + u) * RSTR + cc * 8]) = pack8(kf[u]);
-        *reinterpret_cast<uint4*>(&sVrow[(sg * 4 + u) * RSTR + cc * 8]) = pack8(vf[u]);
-      }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        uint2 w;
-        w.x = pack_bf16x2(kf[0][e], kf[1][e]);
-        w.y = pack_bf16x2(kf[2][e], kf[3][e]);
-        *reinterpret_cast<uint2*>(&sKT[(cc * 8 + e) * SSTR + sg * 4]) = w;
+        const uint4 pk = pack8(kf[u]), pv = pack8(vf[u]);
+        *reinterpret_cast<uint4*>(&sKrow[(sg * 4 + u) * RSTR + cc * 8]) = pk;
+        *reinterpret_cast<uint4*>(&sVrow[(sg * 4 + u) * RSTR + cc * 8]) = pv;
+        if (in) {  // the fused stream, for the dQ kernel
+          *reinterpret_cast<uint4*>(Kf_out + eoff) = pk;
+          *reinterpret_cast<uint4*>(Vf_out + eoff) = pv;
+        }
       }
     }
   }
@@ -211,13 +204,11 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   const int n_qt = (Tq + BR - 1) / BR;
   const int qt0 = t_first / BR;
 
-  // ---- staging of query tiles is done by the role K waves: the role V waves issue the dQ
-  // atomics, and a wave that waits for its prefetched loads would also wait for its own older
-  // atomics.  Wave 4 carries Q of the EVEN tiles (tile index relative to the first one), wave 5
-  // their dO, waves 6 and 7 the odd tiles.  A wave so has ONE tile in flight at a time and only
-  // touches it every second iteration: its loads have two full iterations to arrive, which they
-  // need while the memory pipeline is backed up with the atomics.  Item = (row, 16-byte chunk);
-  // an 8-lane LDS write group is 128 contiguous bytes of one row.
+  // ---- staging of query tiles is done by the role K waves.  Wave 4 carries Q of the EVEN tiles
+  // (tile index relative to the first one), wave 5 their dO, waves 6 and 7 the odd tiles.  A
+  // wave so has ONE tile in flight at a time and only touches it every second iteration: its
+  // loads have two full iterations to arrive.  Item = (row, 16-byte chunk); an 8-lane LDS write
+  // group is 128 contiguous bytes of one row.
   constexpr int RPP = 64 / CPR, NU = BR / RPP;  // rows per pass, passes (8 for d = 128)
   const int ccq = lane % CPR, rq = lane / CPR;
   const bool stage_dO = wave & 1;
@@ -258,49 +249,11 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
       sDv[buf * BR + lane] = valid ? r.dv : 0.f;
     }
   };
-  // dQ[t, d] = sum_j dS[t, j] Kf[j, d] for one finished tile; work unit = 32-wide d slice, one per
-  // role V wave.  A = dS rows, B = Kf^T rows: in the accumulator a lane owns ONE column d and the
-  // 32 lanes of a half-wave cover 32 consecutive d, so each atomic adds two full 128-byte lines.
-  auto dq_tile = [&](int t0, int buf) {
-    if (wave < DB) {
-      const bf16* sdS = smem + L::OFF_DS + buf * L::SBUF;
-      f32x16 qacc;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) qacc[r] = 0.f;
-      const int brow = (32 * wave + li) * SSTR + 8 * g;
-#pragma unroll
-      for (int ks = 0; ks < BCB / 16; ++ks) {
-        // A = dS rows (m = query row, k = slot) = transpose of dS^T rows 16 ks .. 16 ks + 15
-        const int i = lane & 15, gsel = (lane >> 4) & 1;
-        const int ch = 2 * gsel + ((i & 3) >> 1), sub = 4 * (i & 1);  // logical 16-byte chunk
-        const int R0 = 16 * ks + 8 * g + (i >> 2), R1 = R0 + 4;
-        const uint2 lo = lds_read_tr(sdS + R0 * BR + 8 * ((ch + (R0 >> 1)) & 3) + sub);
-        const uint2 hi = lds_read_tr(sdS + R1 * BR + 8 * ((ch + (R1 >> 1)) & 3) + sub);
-        const bf16x8 a = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
-        const bf16x8 b = *reinterpret_cast<const bf16x8*>(sKT + brow + 16 * ks);
-        qacc = mfma32(a, b, qacc);
-      }
-      // register r <-> row t0 + 8 (r/4) + 4 g + r%4, column 32 wave + li
-      float* dst = dQacc + qbase + (long)(t0 + 4 * g) * D + 32 * wave + li;
-      if (t0 + BR <= Tq) {  // whole tile in range: constant offsets from one base, no tests
-#pragma unroll
-        for (int r = 0; r < 16; ++r) atomicAdd(dst + (8 * (r >> 2) + (r & 3)) * D, qacc[r]);
-      } else {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int t = t0 + 8 * (r >> 2) + 4 * g + (r & 3);
-          if (t < Tq) atomicAdd(dst + (8 * (r >> 2) + (r & 3)) * D, qacc[r]);
-        }
-      }
-    }
-  };
-
   // ---- main loop, ONE barrier per iteration, three tiles in flight.  In iteration `it`
   //   role K: stages tile it+1 (prefetches it+3); for tile it-1: dP = dO Vf^T, dS = P (dP - D)
-  //           with P^T read back from LDS, publishes dS^T, dKf^T += Q^T dS
-  //   role V: for tile it: S = Q Kf^T, P = exp2(c S - LSE), publishes P^T, dVf^T += dO^T P;
-  //           for tile it-2: dQ += dS Kf (atomics)
-  // so S is computed once, and every hand-over (P^T, dS^T, staged tiles) crosses one barrier.
+  //           with P^T read back from LDS, dKf^T += Q^T dS
+  //   role V: for tile it: S = Q Kf^T, P = exp2(c S - LSE), publishes P^T, dVf^T += dO^T P
+  // so S is computed once, and every hand-over (P^T, staged tiles) crosses one barrier.
   const int n_tiles = n_qt - qt0;
   if (roleK && stage_par < n_tiles) prefetch(treg, qt0 + stage_par);  // tiles 0 and 1
   __syncthreads();  // the set-up buffers are dead
@@ -310,13 +263,13 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   }
   __syncthreads();
 
-  // chunk-rotated address of the lane's 16 bytes (8 query rows 16 h + 8 g ..) in a P^T / dS^T tile
+  // chunk-rotated address of the lane's 16 bytes (8 query rows 16 h + 8 g ..) in a P^T tile
   const int Rl = 32 * sw + li;
   auto pt_off = [&](int h) { return Rl * BR + 8 * ((2 * h + g + (Rl >> 1)) & 3); };
   const int arow = tile_row(swap23(li)) * RSTR + 8 * g;
 
   int b3 = 0;  // it % 3
-  for (int it = 0; it < n_tiles + 2; ++it) {
+  for (int it = 0; it < n_tiles + 1; ++it) {
     const int b3p = b3 == 0 ? 2 : b3 - 1;  // (it - 1) % 3
     if (roleK) {
       if (it + 1 < n_tiles && ((it + 1) & 1) == stage_par) {
@@ -328,7 +281,6 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
         const bf16* sQ = smem + L::OFF_Q + b3p * L::QBUF;
         const bf16* sdO = smem + L::OFF_DO + b3p * L::QBUF;
         const bf16* sP = smem + L::OFF_P + (k & 1) * L::SBUF;
-        bf16* sdS = smem + L::OFF_DS + (k & 1) * L::SBUF;
         f32x16 pacc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) pacc[r] = 0.f;
@@ -351,8 +303,6 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
           for (int u = 0; u < 8; ++u) v[8 * h + u] = pf[u] * (pacc[8 * h + u] - dv[u]);  // dS
         }
         const uint4 s0 = pack8(&v[0]), s1 = pack8(&v[8]);
-        *reinterpret_cast<uint4*>(&sdS[pt_off(0)]) = s0;
-        *reinterpret_cast<uint4*>(&sdS[pt_off(1)]) = s1;
         const bf16x8 sB0 = __builtin_bit_cast(bf16x8, s0), sB1 = __builtin_bit_cast(bf16x8, s1);
         // dKf^T += Q^T dS (k-step = 16 query rows; A read transposed out of the row-major tile;
         // accumulator row m of block db = head dim 32 db + m)
@@ -410,7 +360,6 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
           acc[db] = mfma32(a1, pB1, acc[db]);
         }
       }
-      if (it >= 2) dq_tile((qt0 + it - 2) * BR, it & 1);  // dS^T of tile it-2 was published in it-1
     }
     __syncthreads();
     b3 = b3 == 2 ? 0 : b3 + 1;
@@ -600,10 +549,10 @@ __global__ __launch_bounds__(256) void bwd_reduce_kernel(const float* __restrict
 size_t a256(size_t n) { return (n + 255) & ~(size_t)255; }
 
 struct BwdWs {
-  size_t off_dq, off_d, off_dg, off_part, total;
+  size_t off_dq, off_d, off_dg, off_part, off_kf, off_vf, total;
   int nparts;
 };
-BwdWs carve(int BH, int Tq, int d) {
+BwdWs carve(int BH, int Tq, int S, int d) {
   BwdWs w;
   const size_t rows = (size_t)BH * Tq;
   w.nparts = (int)((rows + FIN_ROWS - 1) / FIN_ROWS);
@@ -611,24 +560,28 @@ BwdWs carve(int BH, int Tq, int d) {
   w.off_d = a256(rows * d * sizeof(float));
   w.off_dg = w.off_d + a256(rows * sizeof(float));
   w.off_part = w.off_dg + a256(rows * 3 * sizeof(float));
-  w.total = w.off_part + a256((size_t)w.nparts * (d * 3 + 3) * sizeof(float));
+  w.off_kf = w.off_part + a256((size_t)w.nparts * (d * 3 + 3) * sizeof(float));
+  w.off_vf = w.off_kf + a256((size_t)BH * S * d * sizeof(bf16));
+  w.total = w.off_vf + a256((size_t)BH * S * d * sizeof(bf16));
   return w;
 }
 
 template <int D>
 hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
   using L = BwdSmem<D>;
-  const BwdWs w = carve(a.BH, a.Tq, D);
+  const BwdWs w = carve(a.BH, a.Tq, a.S, D);
   unsigned char* ws = static_cast<unsigned char*>(a.workspace);
   float* dQacc = reinterpret_cast<float*>(ws + w.off_dq);
   float* Dvec = reinterpret_cast<float*>(ws + w.off_d);
   float* dgate = a.W_r ? reinterpret_cast<float*>(ws + w.off_dg) : nullptr;
   float* dWpart = reinterpret_cast<float*>(ws + w.off_part);
+  bf16* Kf = reinterpret_cast<bf16*>(ws + w.off_kf);
+  bf16* Vf = reinterpret_cast<bf16*>(ws + w.off_vf);
   const long rows = (long)a.BH * a.Tq;
   constexpr int CPR = D / 8;
 
   hipLaunchKernelGGL((bwd_prep_kernel<D>), dim3((unsigned)((rows * CPR + 255) / 256)), dim3(256),
-                     0, st, (const bf16*)a.dO, (const bf16*)a.O, Dvec, dQacc, rows);
+                     0, st, (const bf16*)a.dO, (const bf16*)a.O, Dvec, rows);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
 
@@ -656,9 +609,15 @@ hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
                      (const bf16*)Kp[0], (const bf16*)Kp[1], (const bf16*)Kp[2],
                      (const bf16*)Vp[0], (const bf16*)Vp[1], (const bf16*)Vp[2], a.G, a.LSE, Dvec,
                      (bf16*)a.dK[0], (bf16*)a.dK[1], (bf16*)a.dK[2], (bf16*)a.dV[0],
-                     (bf16*)a.dV[1], (bf16*)a.dV[2], dQacc, dgate, a.Tq, a.S, a.len[0], a.len[1],
+                     (bf16*)a.dV[1], (bf16*)a.dV[2], Kf, Vf, dgate, a.Tq, a.S, a.len[0], a.len[1],
                      a.len[2], a.causal, a.scale * kLog2e, a.scale, n_kvtiles, a.BH);
   e = hipGetLastError();
+  if (e != hipSuccess) return e;
+
+  BwdDqArgs q;
+  q.Q = a.Q; q.dO = a.dO; q.Kf = Kf; q.Vf = Vf; q.LSE = a.LSE; q.Dvec = Dvec; q.dQacc = dQacc;
+  q.BH = a.BH; q.Tq = a.Tq; q.S = a.S; q.d = D; q.causal = a.causal; q.scale = a.scale;
+  e = launch_bwd_dq_bf16(q, st);
   if (e != hipSuccess) return e;
 
   hipLaunchKernelGGL((bwd_finish_kernel<D>), dim3(w.nparts), dim3(256), 0, st, dQacc, dgate,
@@ -676,8 +635,7 @@ hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
 }  // namespace
 
 size_t bwd_workspace_bytes(int BH, int Tq, int S, int d) {
-  (void)S;
-  return carve(BH, Tq, d).total;
+  return carve(BH, Tq, S, d).total;
 }
 
 hipError_t launch_bwd_bf16(const BwdArgs& a, hipStream_t st) {

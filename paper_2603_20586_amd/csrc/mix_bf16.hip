@@ -17,12 +17,9 @@
 // global memory straight into LDS (global_load_lds_dwordx4: no registers hold data in flight, and
 // the prefetch distance is the depth of the buffer rings - three K and four V tiles, a tile is
 // requested two tiles before its first use); V stays row-major and its transpose for the second
-// product is read with ds_read_b64_tr_b16.  An LDS-direct load writes the 64 lanes' 16 bytes to
-// consecutive addresses, so tile rows carry no padding; instead the 16-byte chunks of a row are
-// XOR-swizzled by the row number and the slots of a tile are permuted over the rows (j = 4a+b ->
-// row 4b+a inside every 16): row reads and transposed reads are then free of bank conflicts
-// (d = 128; the transposed reads of d = 64 are two-way conflicted).  The swizzle is applied on
-// the global side: every lane picks the chunk that belongs at its LDS position.
+// product is read with ds_read_b64_tr_b16.  The tile layout that makes this work without padding
+// is described where it is defined (slot permutation + chunk swizzle, applied on the global side).
+#include "attn_tile.h"
 #include "mka_dev.h"
 #include "mka_internal.h"
 
@@ -53,30 +50,6 @@ struct MixSmem {
   static constexpr int TOTAL = (NKB + NVB) * TSZ;  // bytes (also covers the epilogue's O tiles)
 };
 
-// LDS row of slot j (0..63) of a tile (an involution)
-__device__ __forceinline__ int mx_row(int j) {
-  return (j & ~15) | ((j & 3) << 2) | ((j >> 2) & 3);
-}
-// chunk c of row r sits at chunk position c ^ mx_swz(r) of the row
-template <int D>
-__device__ __forceinline__ int mx_swz(int r) {
-  return D == 128 ? (r & 15) : ((r >> 1) & 7);
-}
-
-// 16 bytes per lane from global memory (uniform base + per-lane byte offset) to LDS address
-// lds + 16 * lane.  Counted by vmcnt like any other load; the LDS write is done when the count
-// drops.  m0 carries the LDS address (one wait state between its write and the load).
-__device__ __forceinline__ void mx_dma16(const void* base, unsigned off, unsigned lds) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               :
-               : "v"(off), "s"(base), "s"(lds)
-               : "memory");
-}
-template <int N>
-__device__ __forceinline__ void mx_wait_loads() {
-  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
-
 struct MixLevels {
   const bf16* K[3];
   const bf16* V[3];
@@ -98,15 +71,6 @@ __device__ __forceinline__ int mx_next_level(const MixLevels& L, int l) {
   if (l < 1 && L.n[1] > 0) nl = 1;
   if (l < 0 && L.n[0] > 0) nl = 0;
   return nl;
-}
-
-// Byte offset, inside a tile, of the lane's first K fragment of unit 0 (slot li of the unit, head
-// dims 8 g ..): fragment kk of unit u is at (a0 ^ (kk << 5)) + 32 u ROWB, because the chunk index
-// 2 kk + g only meets the swizzle in an XOR and unit and tile offsets are multiples of 2 KiB.
-template <int D>
-__device__ __forceinline__ unsigned mx_kfrag0(int li, int g) {
-  const int r = mx_row(li);
-  return (unsigned)(r * (D * 2) + 16 * (g ^ mx_swz<D>(r)));
 }
 
 template <int D>
@@ -420,15 +384,7 @@ __global__ __launch_bounds__(MixShape<R>::NT, 1) void mix_bf16_kernel(
     // lane constants of the LDS reads
     const unsigned a0 = mx_kfrag0<D>(li, g);
     unsigned x_lo, x_hi;
-    {
-      const int ti = lane & 15, gsel = (lane >> 4) & 1;
-      const int cl = 2 * gsel + ((ti >> 1) & 1), sub = 8 * (ti & 1);
-      const int r_lo = 4 * (ti >> 2) + g, r_hi = r_lo + 2;  // rows of slots 4 g + ti / 4 (+ 8)
-      x_lo = (unsigned)(r_lo * ROWB + 16 * (cl ^ (mx_swz<D>(r_lo) & 3)) + sub) ^
-             (unsigned)(16 * (mx_swz<D>(r_lo) & ~3));
-      x_hi = (unsigned)(r_hi * ROWB + 16 * (cl ^ (mx_swz<D>(r_hi) & 3)) + sub) ^
-             (unsigned)(16 * (mx_swz<D>(r_hi) & ~3));
-    }
+    mx_trfrag0<D>(lane, x_lo, x_hi);
 
     // prologue: tiles 0..2 requested, tile 0 landed
     rq_level(rq_l);

@@ -32,6 +32,21 @@ struct FwdArgs {
 hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t st);
 hipError_t launch_fwd_f32(const FwdArgs& a, hipStream_t st);
 
+// dQ accumulator of the backward, [B*H,Tq,d] f32 = sum_j dS[t,j] Kf[j] (no factor tau)
+struct BwdDqArgs {
+  const void* Q;
+  const void* dO;
+  const void* Kf;   // fused stream [B*H,S,d] bf16, as written by the main backward kernel
+  const void* Vf;
+  const float* LSE;
+  const float* Dvec;
+  float* dQacc;
+  int BH, Tq, S, d;
+  int causal;
+  float scale;
+};
+hipError_t launch_bwd_dq_bf16(const BwdDqArgs& a, hipStream_t st);
+
 struct MixArgs {
   const void* Q;
   const void* K[3];
