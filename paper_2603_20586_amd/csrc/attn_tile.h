@@ -34,6 +34,13 @@ __device__ __forceinline__ void mx_dma16(const void* base, unsigned off, unsigne
                : "v"(off), "s"(base), "s"(lds)
                : "memory");
 }
+// 4 bytes per lane, each lane with its own address, to LDS address lds + 4 * lane.
+__device__ __forceinline__ void mx_dma4(const void* src, unsigned lds) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+               :
+               : "v"(src), "s"(lds)
+               : "memory");
+}
 template <int N>
 __device__ __forceinline__ void mx_wait_loads() {
   asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");

@@ -27,6 +27,7 @@
 //           and took four fifths of that kernel's time.
 //   finish  dQ = tau*acc + dg W_r^T -> bf16; per-workgroup partial sums of Q^T dg and dg
 //   reduce  fixed-order sum of the partials -> dW_r, db_r   (deterministic)
+#include "attn_tile.h"
 #include "fuse_tile.h"
 #include "mka_dev.h"
 #include "mka_internal.h"
@@ -43,16 +44,26 @@ __device__ __forceinline__ int swap23(int i) {
 }
 
 // ------------------------------------------------------------------ prep
+// Per query row: D = dO.O and LSE in log2 units, in arrays padded to whole 32-row tiles per
+// (batch, head) (padding: D = 0, LSE = +inf, hence P = 0), so that the other kernels can fetch a
+// tile's rows without tests.
 template <int D>
 __global__ __launch_bounds__(256) void bwd_prep_kernel(const bf16* __restrict__ dO,
                                                        const bf16* __restrict__ O,
-                                                       float* __restrict__ Dvec, long rows) {
+                                                       const float* __restrict__ LSE,
+                                                       float* __restrict__ Dp,
+                                                       float* __restrict__ LSE2p, int Tq, int Tqp,
+                                                       long prows) {
   constexpr int CPR = D / 8;
   const long item = (long)blockIdx.x * 256 + threadIdx.x;
-  const long row = item / CPR;
+  const long prow = item / CPR;  // padded row index
   const int cc = (int)(item % CPR);
+  const long bh = prow / Tqp;
+  const int t = (int)(prow % Tqp);
+  const bool real = prow < prows && t < Tq;
+  const long row = bh * Tq + t;
   float part = 0.f;
-  if (row < rows) {
+  if (real) {
     float a[8], b[8];
     unpack8(*reinterpret_cast<const uint4*>(dO + row * D + cc * 8), a);
     unpack8(*reinterpret_cast<const uint4*>(O + row * D + cc * 8), b);
@@ -60,56 +71,48 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(const bf16* __restrict__ 
     for (int e = 0; e < 8; ++e) part = fmaf(a[e], b[e], part);
   }
   part = group_sum<CPR>(part);  // CPR consecutive lanes hold one row
-  if (row < rows && cc == 0) Dvec[row] = part;
+  if (prow < prows && cc == 0) {
+    Dp[prow] = real ? part : 0.f;
+    LSE2p[prow] = real ? LSE[row] * kLog2e : INFINITY;
+  }
 }
 
 // ------------------------------------------------------------------ main
 template <int D>
 struct BwdSmem {
   static constexpr int BR = 32;          // query rows per tile
-  static constexpr int RSTR = D + 8;     // row-major Q / dO tiles (rows permuted, see tile_row)
-  static constexpr int QBUF = BR * RSTR;
-  static constexpr int SBUF = BCB * BR;  // P^T tile: [slot][row], 64-byte rows, chunks rotated
-  // Q, dO (and the LSE / D rows) live for three iterations: triple-buffered; P^T for two
-  static constexpr int OFF_Q = 0;
-  static constexpr int OFF_DO = OFF_Q + 3 * QBUF;
-  static constexpr int OFF_P = OFF_DO + 3 * QBUF;
-  static constexpr int LOOP_END = OFF_P + 2 * SBUF;
+  static constexpr int RSTR = D + 8;     // set-up only: padded row-major Kf / Vf rows
+  // One slot of the query-tile ring: Q tile, dO tile (32 rows of D bf16 each, no padding, chunks
+  // swizzled as in the K / V tiles of the attention kernels) and the rows' LSE and D values.
+  // A tile is requested three iterations before its first use and read in two: five slots.
+  static constexpr int NSLOT = 5;
+  static constexpr int QB = BR * D * 2;          // bytes of one Q or dO tile
+  static constexpr int SLOTB = 2 * QB + 256;     // Q, dO, 32 LSE, 32 D
+  static constexpr int SBUF = BCB * BR;          // P^T tile: [slot][row], 64-byte rows, chunks rotated (bf16)
+  static constexpr int OFF_P = NSLOT * SLOTB;    // bytes; two P^T tiles
+  static constexpr int LOOP_END = OFF_P + 2 * SBUF * 2;
   // set-up only: row-major Kf and Vf of the workgroup's 128 slots
-  static constexpr int OFF_KROW = 0;
+  static constexpr int OFF_KROW = 0;             // bf16 elements
   static constexpr int OFF_VROW = BCB * RSTR;
-  static constexpr int SETUP_END = 2 * BCB * RSTR;
-  static constexpr int TOTAL = LOOP_END > SETUP_END ? LOOP_END : SETUP_END;  // bf16 elements
+  static constexpr int SETUP_END = 2 * BCB * RSTR * 2;  // bytes
+  static constexpr int TOTAL = LOOP_END > SETUP_END ? LOOP_END : SETUP_END;  // bytes
 };
 
-// LDS row of query row t (0..31) of a Q / dO tile.  The tiles are read two ways: as MFMA A
-// operands by rows (16 lanes read 16 rows x 16 bytes: the rows must differ mod 16) and, for the
-// products that contract over query rows, TRANSPOSED with ds_read_b64_tr_b16 (32 lanes read 4
-// consecutive query rows x 64 bytes: with the 272-byte row stride those rows must be 4 LDS rows
-// apart).  t = 4a + b  ->  row 4b + a (inside each group of 16) satisfies both.
+// LDS row of query row t (0..31) of a Q / dO tile (the slot permutation of the K / V tiles of the
+// attention kernels).  The tiles are read two ways: as MFMA A operands by rows (16 lanes read 16
+// rows x 16 bytes) and, for the products that contract over query rows, TRANSPOSED with
+// ds_read_b64_tr_b16 (32 lanes read 4 consecutive query rows x 64 bytes); t = 4a + b -> row
+// 4b + a (inside each group of 16) together with the chunk swizzle keeps both conflict-free.
 __device__ __forceinline__ int tile_row(int t) {
   return (t & 16) | ((t & 3) << 2) | ((t >> 2) & 3);
 }
 
-// A operand (32 x 16) = transpose of rows k0 .. k0+15 (the MFMA k index), columns m0 .. m0+31 of
-// a row-major LDS matrix; row_ptr(k) returns the address of row k, column m0.
-template <typename RowPtr>
-__device__ __forceinline__ bf16x8 load_a_tr(RowPtr row_ptr, int lane) {
-  const int i = lane & 15, gsel = (lane >> 4) & 1, khalf = lane >> 5;
-  const int kr = 8 * khalf + (i >> 2), col = 16 * gsel + 4 * (i & 3);
-  const uint2 lo = lds_read_tr(row_ptr(kr) + col);
-  const uint2 hi = lds_read_tr(row_ptr(kr + 4) + col);
-  return __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
-}
-
-// Work item of the Q / dO tile load = (row, 16-byte chunk); a tensor's 128 staging threads cover
-// 128 / CPR rows per pass.  An 8-lane LDS write group is 128 contiguous bytes of one row.
 template <int D>
 __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
     const bf16* __restrict__ dO, const bf16* __restrict__ Q, const bf16* __restrict__ K0,
     const bf16* __restrict__ K1, const bf16* __restrict__ K2, const bf16* __restrict__ V0,
     const bf16* __restrict__ V1, const bf16* __restrict__ V2, const float* __restrict__ G,
-    const float* __restrict__ LSE, const float* __restrict__ Dvec, bf16* __restrict__ dK0,
+    const float* __restrict__ LSE2p, const float* __restrict__ Dp, int Tqp, bf16* __restrict__ dK0,
     bf16* __restrict__ dK1, bf16* __restrict__ dK2, bf16* __restrict__ dV0, bf16* __restrict__ dV1,
     bf16* __restrict__ dV2, bf16* __restrict__ Kf_out, bf16* __restrict__ Vf_out,
     float* __restrict__ dgate, int Tq, int S,
@@ -117,14 +120,13 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   using L = BwdSmem<D>;
   constexpr int BR = L::BR, RSTR = L::RSTR;
   constexpr int CPR = D / 8, KK = D / 16, DB = D / 32, NT = 512;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   bf16* smem = reinterpret_cast<bf16*>(smem_raw);
-  float* sL = reinterpret_cast<float*>(smem + L::TOTAL);  // [3][BR] LSE in log2 units
-  float* sDv = sL + 3 * BR;                               // [3][BR] D
+  char* lds = reinterpret_cast<char*>(smem_raw);
 
   // 8 waves = 2 per SIMD.  Waves 0-3 (role V) and 4-7 (role K) each own the same four blocks
   // of 32 slots: role V computes S -> P -> dVf^T, role K (one tile behind, P^T through LDS)
-  // dP -> dS -> dKf^T, and stages the query tiles.  A wave so holds one
+  // dP -> dS -> dKf^T.  A wave so holds one
   // accumulator set and one B operand instead of two, which is what lets two waves share a SIMD
   // and hide each other's LDS / MFMA latency.
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
@@ -142,8 +144,6 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   const long kvbase = bh * (long)S * D;
   const long qbase = bh * (long)Tq * D;
   const float* Gb = G + bh * (long)S * 3;
-  const float* LSEb = LSE + bh * (long)Tq;
-  const float* Dvb = Dvec + bh * (long)Tq;
   const int jmine = J0 + 32 * sw + li;  // the slot this lane owns in S / dP / dVf^T / dKf^T
 
   // ---- set-up: fuse the 128 slots once.  Item = (4 consecutive slots, 16-byte chunk).
@@ -204,98 +204,109 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   const int n_qt = (Tq + BR - 1) / BR;
   const int qt0 = t_first / BR;
 
-  // ---- staging of query tiles is done by the role K waves.  Wave 4 carries Q of the EVEN tiles
-  // (tile index relative to the first one), wave 5 their dO, waves 6 and 7 the odd tiles.  A
-  // wave so has ONE tile in flight at a time and only touches it every second iteration: its
-  // loads have two full iterations to arrive.  Item = (row, 16-byte chunk); an 8-lane LDS write
-  // group is 128 contiguous bytes of one row.
-  constexpr int RPP = 64 / CPR, NU = BR / RPP;  // rows per pass, passes (8 for d = 128)
-  const int ccq = lane % CPR, rq = lane / CPR;
-  const bool stage_dO = wave & 1;
-  const int stage_par = (wave >> 1) & 1;           // parity of the tiles this wave stages
-  const bool stage_row = !stage_dO && lane < BR;   // LSE / D rows ride with the Q wave
-  const bf16* Xb = (stage_dO ? dO : Q) + qbase;
-  struct TileRegs {
-    uint4 x[NU];
-    float lse, dv;
-  };
-  TileRegs treg = {};
-  auto prefetch = [&](TileRegs& r, int qt) {  // global -> registers
-    const int t0 = qt * BR;
-#pragma unroll
-    for (int u = 0; u < NU; ++u) {
-      const int t = t0 + rq + RPP * u;
-      r.x[u] = make_uint4(0, 0, 0, 0);
-      if (t < Tq) r.x[u] = *reinterpret_cast<const uint4*>(Xb + t * D + ccq * 8);
-    }
-    if (stage_row) {
-      // raw values only: any arithmetic here would make the wave wait for the load at once
-      const int t = t0 + lane;
-      if (t < Tq) {
-        r.lse = LSEb[t];
-        r.dv = Dvb[t];
-      }
-    }
-  };
-  auto stage = [&](const TileRegs& r, int buf, int qt) {  // registers -> LDS
-    bf16* sX = smem + (stage_dO ? L::OFF_DO : L::OFF_Q) + buf * L::QBUF;
-#pragma unroll
-    for (int u = 0; u < NU; ++u)
-      *reinterpret_cast<uint4*>(&sX[tile_row(rq + RPP * u) * RSTR + ccq * 8]) = r.x[u];
-    if (stage_row) {
-      // rows past the end get LSE = +inf, hence P = 0
-      const bool valid = qt * BR + lane < Tq;
-      sL[buf * BR + lane] = valid ? r.lse * kLog2e : INFINITY;
-      sDv[buf * BR + lane] = valid ? r.dv : 0.f;
-    }
-  };
-  // ---- main loop, ONE barrier per iteration, three tiles in flight.  In iteration `it`
-  //   role K: stages tile it+1 (prefetches it+3); for tile it-1: dP = dO Vf^T, dS = P (dP - D)
-  //           with P^T read back from LDS, dKf^T += Q^T dS
-  //   role V: for tile it: S = Q Kf^T, P = exp2(c S - LSE), publishes P^T, dVf^T += dO^T P
-  // so S is computed once, and every hand-over (P^T, staged tiles) crosses one barrier.
+  // ---- staging: query tiles go from global memory straight into LDS (no registers hold data in
+  // flight), requested three iterations before their first use; every wave issues an equal
+  // share of a tile's load instructions (1 KiB each: lane i fills LDS row RPI q + i / CPR, chunk
+  // position i % CPR of instruction q, and picks the query row and chunk that belong there),
+  // wave 0 one more for the rows' LSE and D values.
+  constexpr int ROWB = D * 2, RPI = 64 / CPR;
+  constexpr int IPT = L::QB / 1024;  // load instructions per tensor and tile
+  constexpr int LPW = 2 * IPT / 8;   // per wave
   const int n_tiles = n_qt - qt0;
-  if (roleK && stage_par < n_tiles) prefetch(treg, qt0 + stage_par);  // tiles 0 and 1
-  __syncthreads();  // the set-up buffers are dead
-  if (roleK && stage_par == 0) {
-    stage(treg, 0, qt0);
-    if (n_tiles > 2) prefetch(treg, qt0 + 2);
+  const int uw = __builtin_amdgcn_readfirstlane(wave);
+  const char* Qb = reinterpret_cast<const char*>(Q + qbase);
+  const char* dOb = reinterpret_cast<const char*>(dO + qbase);
+  unsigned st_row[LPW], st_chunk[LPW];
+#pragma unroll
+  for (int e = 0; e < LPW; ++e) {
+    const int q = (8 * e + uw) % IPT;
+    const int r = RPI * q + lane / CPR;
+    st_row[e] = (unsigned)tile_row(r);
+    st_chunk[e] = 16u * (unsigned)((lane % CPR) ^ mx_swz<D>(r));
   }
-  __syncthreads();
+  const float* ld_src = (lane < 32 ? LSE2p : Dp) + bh * (long)Tqp + (lane & 31);
+  const unsigned lds_base = (unsigned)(size_t)lds;
+  // tile k of this workgroup (past the last one: the last again, so that the counted waits stay
+  // exact) into ring slot `slot`; rows past the end repeat the last row (their LSE is +inf)
+  auto request = [&](int k, int slot) __attribute__((always_inline)) {
+    const int t0 = (qt0 + (k < n_tiles ? k : n_tiles - 1)) * BR;
+    const unsigned sb = lds_base + (unsigned)(slot * L::SLOTB);
+#pragma unroll
+    for (int e = 0; e < LPW; ++e) {
+      const int idx = 8 * e + uw, tensor = idx / IPT, q = idx % IPT;
+      const unsigned o = min((unsigned)t0 + st_row[e], (unsigned)(Tq - 1)) * (unsigned)ROWB + st_chunk[e];
+      mx_dma16(tensor ? dOb : Qb, o, sb + (unsigned)(tensor * L::QB + 1024 * q));
+    }
+    if (uw == 0) mx_dma4(ld_src + t0, sb + 2 * L::QB);
+  };
+  // before a barrier that publishes a tile: all but the two youngest tiles of this wave landed
+  auto wait_tile = [&]() __attribute__((always_inline)) {
+    if (uw == 0) mx_wait_loads<2 * (LPW + 1)>();
+    else mx_wait_loads<2 * LPW>();
+  };
+
+  // lane constants of the LDS reads: A operand rows (slot li of a 32-row tile, head dims 8 g ..)
+  // and transposed reads (k-step of 16 query rows, 32 head dims)
+  const unsigned aq0 = mx_kfrag0<D>(swap23(li), g);
+  unsigned xq_lo, xq_hi;
+  {
+    const int i = lane & 15, gsel = (lane >> 4) & 1, khalf = lane >> 5;
+    const int cl = 2 * gsel + ((i & 3) >> 1), sub = 8 * (i & 1);
+    const int r_lo = tile_row(8 * khalf + (i >> 2)), r_hi = tile_row(8 * khalf + (i >> 2) + 4);
+    xq_lo = (unsigned)(r_lo * ROWB + 16 * (cl ^ mx_swz<D>(r_lo)) + sub);
+    xq_hi = (unsigned)(r_hi * ROWB + 16 * (cl ^ mx_swz<D>(r_hi)) + sub);
+  }
+  // A operand (32 head dims x 16 query rows) = transpose of query rows 16 half .. of a tile at
+  // byte offset tb, head dims 32 db ..: db only meets the swizzle in an XOR of address bits 6..7
+  auto tr_frag = [&](unsigned tb, int db, int half) __attribute__((always_inline)) {
+    const char* base = lds + tb + 16 * half * ROWB;
+    const uint2 lo = lds_read_tr(reinterpret_cast<const bf16*>(base + (xq_lo ^ (unsigned)(db << 6))));
+    const uint2 hi = lds_read_tr(reinterpret_cast<const bf16*>(base + (xq_hi ^ (unsigned)(db << 6))));
+    return __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+  };
+
+  // ---- main loop, ONE barrier per iteration.  In iteration `it`
+  //   all:    request tile it+3
+  //   role K: for tile it-1: dP = dO Vf^T, dS = P (dP - D) with P^T read back from LDS,
+  //           dKf^T += Q^T dS
+  //   role V: for tile it: S = Q Kf^T, P = exp2(c S - LSE), publishes P^T, dVf^T += dO^T P
+  // so S is computed once, and every hand-over (P^T, requested tiles) crosses one barrier.
+  __syncthreads();  // the set-up buffers are dead
+  request(0, 0);
+  request(1, 1);
+  request(2, 2);
+  wait_tile();
+  __syncthreads();  // tile 0 is complete
 
   // chunk-rotated address of the lane's 16 bytes (8 query rows 16 h + 8 g ..) in a P^T tile
   const int Rl = 32 * sw + li;
   auto pt_off = [&](int h) { return Rl * BR + 8 * ((2 * h + g + (Rl >> 1)) & 3); };
-  const int arow = tile_row(swap23(li)) * RSTR + 8 * g;
+  bf16* sPbase = reinterpret_cast<bf16*>(lds + L::OFF_P);
 
-  int b3 = 0;  // it % 3
+  int b5 = 0;  // it % NSLOT
   for (int it = 0; it < n_tiles + 1; ++it) {
-    const int b3p = b3 == 0 ? 2 : b3 - 1;  // (it - 1) % 3
+    request(it + 3, b5 + 3 >= L::NSLOT ? b5 + 3 - L::NSLOT : b5 + 3);
     if (roleK) {
-      if (it + 1 < n_tiles && ((it + 1) & 1) == stage_par) {
-        stage(treg, b3 == 2 ? 0 : b3 + 1, qt0 + it + 1);
-        if (it + 3 < n_tiles) prefetch(treg, qt0 + it + 3);
-      }
-      if (it >= 1 && it <= n_tiles) {
+      if (it >= 1) {
         const int k = it - 1;
-        const bf16* sQ = smem + L::OFF_Q + b3p * L::QBUF;
-        const bf16* sdO = smem + L::OFF_DO + b3p * L::QBUF;
-        const bf16* sP = smem + L::OFF_P + (k & 1) * L::SBUF;
+        const unsigned tb = (unsigned)((b5 == 0 ? L::NSLOT - 1 : b5 - 1) * L::SLOTB);  // slot of tile it-1
+        const bf16* sP = sPbase + (k & 1) * L::SBUF;
         f32x16 pacc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) pacc[r] = 0.f;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-          const bf16x8 ao = *reinterpret_cast<const bf16x8*>(sdO + arow + 16 * kk);
+          const bf16x8 ao = *reinterpret_cast<const bf16x8*>(lds + tb + L::QB + (aq0 ^ (unsigned)(kk << 5)));
           pacc = mfma32(ao, breg[kk], pacc);
         }
         // register r <-> row 16 (r/8) + 8 g + r%8 of the tile, column = the lane's slot
+        const float* sDv = reinterpret_cast<const float*>(lds + tb + 2 * L::QB + 128);
         float v[16];
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
           const int tl = 16 * h + 8 * g;
-          const float4 d0 = *reinterpret_cast<const float4*>(&sDv[b3p * BR + tl]);
-          const float4 d1 = *reinterpret_cast<const float4*>(&sDv[b3p * BR + tl + 4]);
+          const float4 d0 = *reinterpret_cast<const float4*>(&sDv[tl]);
+          const float4 d1 = *reinterpret_cast<const float4*>(&sDv[tl + 4]);
           const float dv[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
           float pf[8];
           unpack8(*reinterpret_cast<const uint4*>(&sP[pt_off(h)]), pf);
@@ -308,8 +319,8 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
         // accumulator row m of block db = head dim 32 db + m)
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          const bf16x8 a0 = load_a_tr([&](int r) { return sQ + tile_row(r) * RSTR + 32 * db; }, lane);
-          const bf16x8 a1 = load_a_tr([&](int r) { return sQ + tile_row(16 + r) * RSTR + 32 * db; }, lane);
+          const bf16x8 a0 = tr_frag(tb, db, 0);
+          const bf16x8 a1 = tr_frag(tb, db, 1);
           acc[db] = mfma32(a0, sB0, acc[db]);
           acc[db] = mfma32(a1, sB1, acc[db]);
         }
@@ -317,24 +328,24 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
     } else {
       if (it < n_tiles) {
         const int t0 = (qt0 + it) * BR;
-        const bf16* sQ = smem + L::OFF_Q + b3 * L::QBUF;
-        const bf16* sdO = smem + L::OFF_DO + b3 * L::QBUF;
-        bf16* sP = smem + L::OFF_P + (it & 1) * L::SBUF;
+        const unsigned tb = (unsigned)(b5 * L::SLOTB);
+        bf16* sP = sPbase + (it & 1) * L::SBUF;
         const bool need_mask = (J0 + BCB > S) || (causal && (J0 + BCB - 1 > t0 + off));
         f32x16 sacc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-          const bf16x8 aq = *reinterpret_cast<const bf16x8*>(sQ + arow + 16 * kk);
+          const bf16x8 aq = *reinterpret_cast<const bf16x8*>(lds + tb + (aq0 ^ (unsigned)(kk << 5)));
           sacc = mfma32(aq, breg[kk], sacc);
         }
+        const float* sL = reinterpret_cast<const float*>(lds + tb + 2 * L::QB);
         float v[16];
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
           const int tl = 16 * h + 8 * g;
-          const float4 l0 = *reinterpret_cast<const float4*>(&sL[b3 * BR + tl]);
-          const float4 l1 = *reinterpret_cast<const float4*>(&sL[b3 * BR + tl + 4]);
+          const float4 l0 = *reinterpret_cast<const float4*>(&sL[tl]);
+          const float4 l1 = *reinterpret_cast<const float4*>(&sL[tl + 4]);
           const float lv[8] = {l0.x, l0.y, l0.z, l0.w, l1.x, l1.y, l1.z, l1.w};
 #pragma unroll
           for (int u = 0; u < 8; ++u) v[8 * h + u] = fast_exp2(fmaf(sacc[8 * h + u], c, -lv[u]));
@@ -354,16 +365,19 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
         // dVf^T += dO^T P
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          const bf16x8 a0 = load_a_tr([&](int r) { return sdO + tile_row(r) * RSTR + 32 * db; }, lane);
-          const bf16x8 a1 = load_a_tr([&](int r) { return sdO + tile_row(16 + r) * RSTR + 32 * db; }, lane);
+          const bf16x8 a0 = tr_frag(tb + L::QB, db, 0);
+          const bf16x8 a1 = tr_frag(tb + L::QB, db, 1);
           acc[db] = mfma32(a0, pB0, acc[db]);
           acc[db] = mfma32(a1, pB1, acc[db]);
         }
       }
     }
+    wait_tile();  // this wave's part of tile it+1 has landed
     __syncthreads();
-    b3 = b3 == 2 ? 0 : b3 + 1;
+    b5 = b5 == L::NSLOT - 1 ? 0 : b5 + 1;
   }
+  mx_wait_loads<0>();  // the surplus requests must land before the epilogue reuses the buffers
+  __syncthreads();
 
   // ---- epilogue.  dKf^T (held by role K) then dVf^T (role V) go through LDS as f32 [slot][d] so
   // that the un-fusion (dK_l = G_l tau dKf, dV_l = G_l dVf) is written with coalesced 16-byte
@@ -371,7 +385,7 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   // loads.  Item = (slot, 16-byte chunk): CPR consecutive lanes hold one slot's row.
   constexpr int ESTR = D + 4;                 // f32 per staged row
   constexpr int NITEM = BCB * CPR / NT;       // items per thread
-  static_assert((size_t)BCB * ESTR * 4 <= (size_t)L::TOTAL * 2, "staging tile must fit");
+  static_assert((size_t)BCB * ESTR * 4 <= (size_t)L::TOTAL, "staging tile must fit");
   float* sE = reinterpret_cast<float*>(smem_raw);
   const int ecc = tid % CPR, erow0 = tid / CPR;
   constexpr int ERS = NT / CPR;               // slots covered per pass
@@ -549,16 +563,19 @@ __global__ __launch_bounds__(256) void bwd_reduce_kernel(const float* __restrict
 size_t a256(size_t n) { return (n + 255) & ~(size_t)255; }
 
 struct BwdWs {
-  size_t off_dq, off_d, off_dg, off_part, off_kf, off_vf, total;
-  int nparts;
+  size_t off_dq, off_d, off_lse, off_dg, off_part, off_kf, off_vf, total;
+  int nparts, Tqp;
 };
 BwdWs carve(int BH, int Tq, int S, int d) {
   BwdWs w;
   const size_t rows = (size_t)BH * Tq;
   w.nparts = (int)((rows + FIN_ROWS - 1) / FIN_ROWS);
+  w.Tqp = (Tq + 31) / 32 * 32;  // D and LSE rows are padded to whole 32-row tiles per (b,h)
+  const size_t prows = (size_t)BH * w.Tqp;
   w.off_dq = 0;
   w.off_d = a256(rows * d * sizeof(float));
-  w.off_dg = w.off_d + a256(rows * sizeof(float));
+  w.off_lse = w.off_d + a256(prows * sizeof(float));
+  w.off_dg = w.off_lse + a256(prows * sizeof(float));
   w.off_part = w.off_dg + a256(rows * 3 * sizeof(float));
   w.off_kf = w.off_part + a256((size_t)w.nparts * (d * 3 + 3) * sizeof(float));
   w.off_vf = w.off_kf + a256((size_t)BH * S * d * sizeof(bf16));
@@ -572,7 +589,8 @@ hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
   const BwdWs w = carve(a.BH, a.Tq, a.S, D);
   unsigned char* ws = static_cast<unsigned char*>(a.workspace);
   float* dQacc = reinterpret_cast<float*>(ws + w.off_dq);
-  float* Dvec = reinterpret_cast<float*>(ws + w.off_d);
+  float* Dp = reinterpret_cast<float*>(ws + w.off_d);
+  float* LSE2p = reinterpret_cast<float*>(ws + w.off_lse);
   float* dgate = a.W_r ? reinterpret_cast<float*>(ws + w.off_dg) : nullptr;
   float* dWpart = reinterpret_cast<float*>(ws + w.off_part);
   bf16* Kf = reinterpret_cast<bf16*>(ws + w.off_kf);
@@ -580,8 +598,10 @@ hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
   const long rows = (long)a.BH * a.Tq;
   constexpr int CPR = D / 8;
 
-  hipLaunchKernelGGL((bwd_prep_kernel<D>), dim3((unsigned)((rows * CPR + 255) / 256)), dim3(256),
-                     0, st, (const bf16*)a.dO, (const bf16*)a.O, Dvec, rows);
+  const long prows = (long)a.BH * w.Tqp;
+  hipLaunchKernelGGL((bwd_prep_kernel<D>), dim3((unsigned)((prows * CPR + 255) / 256)), dim3(256),
+                     0, st, (const bf16*)a.dO, (const bf16*)a.O, a.LSE, Dp, LSE2p, a.Tq, w.Tqp,
+                     prows);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
 
@@ -596,7 +616,7 @@ hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
     Vp[l] = a.V[l] ? a.V[l] : anyV;
   }
   const int n_kvtiles = (a.S + BCB - 1) / BCB;
-  const size_t smem = (size_t)L::TOTAL * sizeof(bf16) + 6 * L::BR * sizeof(float);
+  const size_t smem = (size_t)L::TOTAL;
   static bool attr_set = false;
   if (!attr_set) {
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_main_kernel<D>),
@@ -607,7 +627,7 @@ hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
   hipLaunchKernelGGL((bwd_main_kernel<D>), dim3((unsigned)((long)n_kvtiles * ((a.BH + 7) / 8) * 8)),
                      dim3(512), smem, st, (const bf16*)a.dO, (const bf16*)a.Q,
                      (const bf16*)Kp[0], (const bf16*)Kp[1], (const bf16*)Kp[2],
-                     (const bf16*)Vp[0], (const bf16*)Vp[1], (const bf16*)Vp[2], a.G, a.LSE, Dvec,
+                     (const bf16*)Vp[0], (const bf16*)Vp[1], (const bf16*)Vp[2], a.G, LSE2p, Dp, w.Tqp,
                      (bf16*)a.dK[0], (bf16*)a.dK[1], (bf16*)a.dK[2], (bf16*)a.dV[0],
                      (bf16*)a.dV[1], (bf16*)a.dV[2], Kf, Vf, dgate, a.Tq, a.S, a.len[0], a.len[1],
                      a.len[2], a.causal, a.scale * kLog2e, a.scale, n_kvtiles, a.BH);
@@ -615,7 +635,7 @@ hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
   if (e != hipSuccess) return e;
 
   BwdDqArgs q;
-  q.Q = a.Q; q.dO = a.dO; q.Kf = Kf; q.Vf = Vf; q.LSE = a.LSE; q.Dvec = Dvec; q.dQacc = dQacc;
+  q.Q = a.Q; q.dO = a.dO; q.Kf = Kf; q.Vf = Vf; q.LSE2p = LSE2p; q.Dp = Dp; q.Tqp = w.Tqp; q.dQacc = dQacc;
   q.BH = a.BH; q.Tq = a.Tq; q.S = a.S; q.d = D; q.causal = a.causal; q.scale = a.scale;
   e = launch_bwd_dq_bf16(q, st);
   if (e != hipSuccess) return e;

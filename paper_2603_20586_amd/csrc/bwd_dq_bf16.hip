@@ -129,8 +129,8 @@ __device__ __forceinline__ void dq_unit(F1&& mid1, F2&& mid2, bf16x8 (&fr)[D / 1
 template <int D>
 __global__ __launch_bounds__(DQ_NT, 1) void bwd_dq_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ dO, const bf16* __restrict__ Kf,
-    const bf16* __restrict__ Vf, const float* __restrict__ LSE, const float* __restrict__ Dvec,
-    float* __restrict__ dQacc, int Tq, int S, int causal, float c, int n_qtiles, int BH,
+    const bf16* __restrict__ Vf, const float* __restrict__ LSE2p, const float* __restrict__ Dp,
+    float* __restrict__ dQacc, int Tq, int Tqp, int S, int causal, float c, int n_qtiles, int BH,
     int interleave) {
   using SM = DqSmem<D>;
   constexpr int BR = DQ_BR, BC = DQ_BC, ROWB = SM::ROWB;
@@ -172,8 +172,8 @@ __global__ __launch_bounds__(DQ_NT, 1) void bwd_dq_kernel(
   }
   float lse2 = INFINITY, dr = 0.f;
   if (tq < Tq) {
-    lse2 = LSE[bh * (long)Tq + tq] * kLog2e;
-    dr = Dvec[bh * (long)Tq + tq];
+    lse2 = LSE2p[bh * (long)Tqp + tq];
+    dr = Dp[bh * (long)Tqp + tq];
   }
 
   // tiles this workgroup visits, the lane's last visible slot, the wave's first row's
@@ -317,7 +317,7 @@ hipError_t launch_dq_t(const BwdDqArgs& a, hipStream_t st) {
   }
   hipLaunchKernelGGL((bwd_dq_kernel<D>), dim3((unsigned)nblocks), dim3(DQ_NT), smem, st,
                      (const bf16*)a.Q, (const bf16*)a.dO, (const bf16*)a.Kf, (const bf16*)a.Vf,
-                     a.LSE, a.Dvec, a.dQacc, a.Tq, a.S, a.causal, a.scale * kLog2e, n_qtiles, a.BH,
+                     a.LSE2p, a.Dp, a.dQacc, a.Tq, a.Tqp, a.S, a.causal, a.scale * kLog2e, n_qtiles, a.BH,
                      interleave);
   return hipGetLastError();
 }

@@ -38,10 +38,10 @@ struct BwdDqArgs {
   const void* dO;
   const void* Kf;   // fused stream [B*H,S,d] bf16, as written by the main backward kernel
   const void* Vf;
-  const float* LSE;
-  const float* Dvec;
+  const float* LSE2p;  // [B*H,Tqp] LSE in log2 units, rows padded per (b,h)
+  const float* Dp;     // [B*H,Tqp] D = dO.O
   float* dQacc;
-  int BH, Tq, S, d;
+  int BH, Tq, Tqp, S, d;
   int causal;
   float scale;
 };
