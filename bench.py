@@ -175,7 +175,7 @@ def main():
 
     rooflines = {
         "C2_fwd": roof_mfma(fl_fwd, ms_fwdk, "fwd_bf16_kernel"),
-        "C2_bwd": roof_mfma(fl_bwd, ms_bwd, "bwd_main_kernel (+prep/finish/reduce in the events)"),
+        "C2_bwd": roof_mfma(fl_bwd, ms_bwd, "bwd_main_kernel + bwd_dq_kernel (+prep/finish/reduce in the events)"),
     }
     workloads = {}
 
@@ -259,7 +259,7 @@ def main():
             "fwd_bwd_tflops": 14 * d * p5 / (msf5 + msb5) / 1e9,
             "tokens_per_s": B5 * T5 / ((msf5 + msb5) * 1e-3)}
         rooflines["C5_bwd"] = roof_mfma(10 * d * p5, msb5,
-                                        "bwd_main_kernel (+prep/finish/reduce in the events)")
+                                        "bwd_main_kernel + bwd_dq_kernel (+prep/finish/reduce in the events)")
         del inp5, G5, O5, L5, ws5, ws5f, grads5
         torch.cuda.empty_cache()
 

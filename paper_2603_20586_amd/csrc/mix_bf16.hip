@@ -13,7 +13,7 @@
 // Skeleton as in the route-fused forward: workgroup = 8 waves x 32 query rows, S^T = K Q^T and
 // O^T += V^T P^T with 32x32x16 MFMAs (a lane owns one query row), units of 32 slots software-
 // pipelined (the S^T MFMAs of the next unit between the exponentials of the current one), one
-// barrier per tile, in its middle.  Differences: the tiles are plain row copies, so they go from
+// barrier per tile.  Differences: the tiles are plain row copies, so they go from
 // global memory straight into LDS (global_load_lds_dwordx4: no registers hold data in flight, and
 // the prefetch distance is the depth of the buffer rings - three K and four V tiles, a tile is
 // requested two tiles before its first use); V stays row-major and its transpose for the second

@@ -1,12 +1,15 @@
 """Turn rocprofv3 CSV output into the short text summaries kept under profiles/.
 
     python -m paper_2603_20586_amd.prof_summary stats  <kernel_stats.csv>  <out.txt>  "<command>"
+    python -m paper_2603_20586_amd.prof_summary trace  <kernel_trace.csv>  <out.txt>  "<command>"
     python -m paper_2603_20586_amd.prof_summary pmc    <counter_collection.csv> <out.txt> "<command>"
     python -m paper_2603_20586_amd.prof_summary traffic <fetch_summary.txt> <write_summary.txt> <traffic.json>
 
 `traffic`: scaled FETCH_SIZE + WRITE_SIZE of the dominant kernel of each roofline line of
 `bench.py` (picked by kernel name and workgroup count) -> HBM bytes per launch, as JSON.
-`stats`: per-kernel calls / average / total time.  `pmc`: per-kernel average of every counter in
+`stats`: per-kernel calls / average / total time.  `trace`: the same from the kernel trace, one
+line per (kernel, workgroup count), i.e. per launch shape: one kernel runs at several workloads in
+one bench.py run, and the roofline lines are per workload.  `pmc`: per-kernel average of every counter in
 the file; for FETCH_SIZE / WRITE_SIZE (KiB per dispatch) it also prints the value scaled by what
 the same counter reads for the 1 GiB calibration copy that `bench.py --calibrate-copy` runs
 (factor = 2^20 KiB / measured KiB of that copy), i.e. an estimate of true HBM bytes.
@@ -46,6 +49,24 @@ def stats(src, dst, cmd):
     open(dst, "w").write("\n".join(out) + "\n")
 
 
+def trace(src, dst, cmd):
+    acc = collections.defaultdict(list)
+    for r in csv.DictReader(open(src)):
+        wgs = 1
+        for ax in "XYZ":
+            wgs *= max(1, int(r["Grid_Size_" + ax]) // max(1, int(r["Workgroup_Size_" + ax])))
+        acc[(short(r["Kernel_Name"]), wgs)].append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
+    total = sum(sum(v) for v in acc.values())
+    out = ["# rocprofv3 kernel-trace summary, per kernel and launch shape", f"# command: {cmd}",
+           "# kernel | workgroups | calls | avg_us | total_ms | pct", ""]
+    for (k, wgs), v in sorted(acc.items(), key=lambda kv: -sum(kv[1])):
+        if "mka::" not in k:
+            continue
+        out.append(f"{k} | {wgs} | {len(v)} | {sum(v) / len(v) / 1e3:.1f} | {sum(v) / 1e6:.2f} | "
+                   f"{100.0 * sum(v) / total:.2f}")
+    open(dst, "w").write("\n".join(out) + "\n")
+
+
 def pmc(src, dst, cmd):
     rows = list(csv.DictReader(open(src)))
     acc = collections.defaultdict(lambda: collections.defaultdict(list))
@@ -75,13 +96,16 @@ def pmc(src, dst, cmd):
     open(dst, "w").write("\n".join(out) + "\n")
 
 
-# roofline key of bench.py -> (kernel, workgroups of its launch at that workload)
+# roofline key of bench.py -> [(kernel, workgroups of its launch at that workload), ...]: the
+# kernels that carry the line's algorithmic work; their traffic is summed
 TRAFFIC_KEYS = {
-    "C2_fwd": ("mka::fwd_bf16_kernel<128>", 512),       # 64 heads x 8 query tiles
-    "C3_fwd_folded": ("mka::fwd_bf16_kernel<128>", 1024),  # 32 heads x 32 query tiles
-    "C2_bwd": ("mka::bwd_main_kernel<128>", 1024),      # 64 heads x 16 KV tiles
-    "C5_bwd": ("mka::bwd_main_kernel<128>", 4096),      # 128 heads x 32 KV tiles
-    "C4_decode": ("mka::decode_split_kernel<bf32,16,128>", 2048),  # 4 splits x 512 heads
+    "C2_fwd": [("mka::fwd_bf16_kernel<128>", 512)],       # 64 heads x 8 query tiles
+    "C3_fwd_folded": [("mka::fwd_bf16_kernel<128>", 1024)],  # 32 heads x 32 query tiles
+    "C2_bwd": [("mka::bwd_main_kernel<128>", 1024),       # 64 heads x 16 KV tiles
+               ("mka::bwd_dq_kernel<128>", 512)],         # 64 heads x 8 query tiles
+    "C5_bwd": [("mka::bwd_main_kernel<128>", 4096),       # 128 heads x 32 KV tiles
+               ("mka::bwd_dq_kernel<128>", 2048)],        # 128 heads x 16 query tiles
+    "C4_decode": [("mka::decode_split_kernel<bf32,16,128>", 2048)],  # 4 splits x 512 heads
 }
 
 
@@ -97,7 +121,8 @@ def traffic(fetch_txt, write_txt, dst):
         return out
 
     rd, wr = scaled(fetch_txt), scaled(write_txt)
-    res = {k: int(rd[v] + wr[v]) for k, v in TRAFFIC_KEYS.items() if v in rd and v in wr}
+    res = {k: int(sum(rd[v] + wr[v] for v in vs)) for k, vs in TRAFFIC_KEYS.items()
+           if all(v in rd and v in wr for v in vs)}
     json.dump(res, open(dst, "w"), indent=1, sort_keys=True)
     print(json.dumps(res, indent=1, sort_keys=True))
 
@@ -107,5 +132,5 @@ if __name__ == "__main__":
         traffic(sys.argv[2], sys.argv[3], sys.argv[4])
     else:
         mode, src, dst, cmd = sys.argv[1], sys.argv[2], sys.argv[3], sys.argv[4]
-        (stats if mode == "stats" else pmc)(src, dst, cmd)
+        {"stats": stats, "trace": trace, "pmc": pmc}[mode](src, dst, cmd)
         print(open(dst).read())
