@@ -157,8 +157,10 @@ mka_status mka_fused_attn_decode(const void* q, const void* const k_new[3],
  *   dQ     out [B,H,Tq,d] dtype (includes the path through the gates of the new slots)
  *   dK,dV  out three [B,H,S,d] dtype each (entry NULL = skip; zero where the level is absent)
  *   dW_r   out [d,3] f32, db_r out [3] f32 (set, not accumulated; NULL = skip)
- * dQ accumulates across KV tiles with f32 atomics (run-to-run differences in
- * the last bits); dW_r/db_r use a fixed-order two-stage reduction. */
+ * Every output is a fixed-order sum: the same call gives the same bits (dQ is
+ * accumulated in registers by a query-stationary kernel, dW_r/db_r by a
+ * two-stage reduction).  The workspace (mka_workspace_bytes(MKA_OP_BWD, shape))
+ * holds the f32 dQ accumulator, padded D / LSE rows and the fused Kf / Vf stream. */
 mka_status mka_fused_attn_bwd(const void* dO, const void* Q, const void* const K[3],
                               const void* const V[3], const float* G, const void* O,
                               const float* LSE, const float* W_r, void* dQ, void* const dK[3],

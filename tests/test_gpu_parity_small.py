@@ -258,6 +258,26 @@ def test_bwd_bf16_shapes(mka, oracle, d, Tq, S, causal, len3):
     _check_bwd(mka, oracle, inp, S, len3, causal, Gprev=Gprev)
 
 
+def test_bwd_same_call_same_bits(mka):
+    """Every sum of the backward has a fixed order (no atomics): two calls agree bit for bit.
+    Shape with several query tiles per dQ workgroup and several KV tiles per row."""
+    announce("bwd bf16 repeatable")
+    inp = si.prefill_inputs(2, 3, 600, 700, 128, dtype="bf16", seed=21, device="cuda", with_dO=True)
+    O, LSE, G, _ = mka.mka_fused_attn_fwd(inp["Q"], inp["K"], inp["V"], inp["W_r"], inp["b_r"],
+                                          causal=True, scale=inp["scale"])
+    outs = []
+    for _ in range(2):
+        g = mka.mka_fused_attn_bwd(inp["dO"], inp["Q"], inp["K"], inp["V"], G, O, LSE, inp["W_r"],
+                                   causal=True, scale=inp["scale"])
+        torch.cuda.synchronize()
+        outs.append(g)
+    a, b = outs
+    assert torch.equal(a["dQ"], b["dQ"])
+    assert torch.equal(a["dW_r"], b["dW_r"]) and torch.equal(a["db_r"], b["db_r"])
+    for l in range(3):
+        assert torch.equal(a["dK"][l], b["dK"][l]) and torch.equal(a["dV"][l], b["dV"][l])
+
+
 def test_bwd_bf16_given_gates_no_router(mka, oracle):
     announce("bwd bf16 given gates")
     inp = si.prefill_inputs(1, 2, 140, 140, 128, dtype="bf16", seed=14, device="cuda", with_dO=True)
