@@ -21,12 +21,12 @@
 //           dKf^T += Q^T dS.  Q / dO tiles are kept row-major only: the operands that contract
 //           over query rows (dO^T, Q^T) are read with transposing LDS loads.
 //           Epilogue: un-fusion, dlam, dg through LDS, coalesced accesses.
-//   dq      (its own file) query-stationary: S, dP a second time, dQacc = sum_j dS Kf in
-//           registers.  Adding dQ from the main kernel instead needs one f32 atomic per (KV
+//   dq      (its own file) query-stationary: S, dP a second time, sum_j dS Kf in registers,
+//           dQ = tau*acc + dg W_r^T -> bf16.  Adding dQ from the main kernel instead needs one f32 atomic per (KV
 //           tile, row, head dim); they retire at about one element per clock and compute unit
 //           and took four fifths of that kernel's time.
-//   finish  dQ = tau*acc + dg W_r^T -> bf16; per-workgroup partial sums of Q^T dg and dg
-//   reduce  fixed-order sum of the partials -> dW_r, db_r   (deterministic)
+//   wpart   per-workgroup partial sums of Q^T dg and dg       (only with a router)
+//   reduce  fixed-order sum of the partials -> dW_r, db_r     (deterministic)
 #include "attn_tile.h"
 #include "fuse_tile.h"
 #include "mka_dev.h"
@@ -479,21 +479,15 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   }
 }
 
-// ------------------------------------------------------------------ finish
-// dQ = tau * acc + dg W_r^T, and per-workgroup partial sums of Q^T dg and dg in a fixed order.
+// ------------------------------------------------------------------ router-gradient partials
+// Per-workgroup partial sums of Q^T dg and dg in a fixed order.
 template <int D>
-__global__ __launch_bounds__(256) void bwd_finish_kernel(
-    const float* __restrict__ dQacc, const float* __restrict__ dgate, const bf16* __restrict__ Q,
-    const float* __restrict__ W_r, bf16* __restrict__ dQ, float* __restrict__ dWpart, long rows,
-    float tau) {
+__global__ __launch_bounds__(256) void bwd_wpart_kernel(const float* __restrict__ dgate,
+                                                        const bf16* __restrict__ Q,
+                                                        float* __restrict__ dWpart, long rows) {
   constexpr int CPR = D / 8, RL = 256 / CPR;  // row lanes per workgroup
-  __shared__ float sW[D * 3];
   __shared__ float sPart[RL][D * 3 + 3];
   const int tid = threadIdx.x, cc = tid % CPR, rl = tid / CPR;
-  const bool route = (W_r != nullptr);
-  if (route)
-    for (int i = tid; i < D * 3; i += 256) sW[i] = W_r[i];
-  __syncthreads();
   float wacc[8][3];
   float bacc[3] = {0.f, 0.f, 0.f};
 #pragma unroll
@@ -502,27 +496,17 @@ __global__ __launch_bounds__(256) void bwd_finish_kernel(
   for (int i = rl; i < FIN_ROWS; i += RL) {
     const long row = row0 + i;
     if (row >= rows) break;
-    const float4 a0 = *reinterpret_cast<const float4*>(dQacc + row * D + cc * 8);
-    const float4 a1 = *reinterpret_cast<const float4*>(dQacc + row * D + cc * 8 + 4);
-    float o[8] = {a0.x * tau, a0.y * tau, a0.z * tau, a0.w * tau,
-                  a1.x * tau, a1.y * tau, a1.z * tau, a1.w * tau};
-    if (route) {
-      const float dg0 = dgate[row * 3 + 0], dg1 = dgate[row * 3 + 1], dg2 = dgate[row * 3 + 2];
-      float q[8];
-      unpack8(*reinterpret_cast<const uint4*>(Q + row * D + cc * 8), q);
+    const float dg0 = dgate[row * 3 + 0], dg1 = dgate[row * 3 + 1], dg2 = dgate[row * 3 + 2];
+    float q[8];
+    unpack8(*reinterpret_cast<const uint4*>(Q + row * D + cc * 8), q);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int k = cc * 8 + e;
-        o[e] += dg0 * sW[k * 3 + 0] + dg1 * sW[k * 3 + 1] + dg2 * sW[k * 3 + 2];
-        wacc[e][0] = fmaf(q[e], dg0, wacc[e][0]);
-        wacc[e][1] = fmaf(q[e], dg1, wacc[e][1]);
-        wacc[e][2] = fmaf(q[e], dg2, wacc[e][2]);
-      }
-      if (cc == 0) { bacc[0] += dg0; bacc[1] += dg1; bacc[2] += dg2; }
+    for (int e = 0; e < 8; ++e) {
+      wacc[e][0] = fmaf(q[e], dg0, wacc[e][0]);
+      wacc[e][1] = fmaf(q[e], dg1, wacc[e][1]);
+      wacc[e][2] = fmaf(q[e], dg2, wacc[e][2]);
     }
-    *reinterpret_cast<uint4*>(dQ + row * D + cc * 8) = pack8(o);
+    if (cc == 0) { bacc[0] += dg0; bacc[1] += dg1; bacc[2] += dg2; }
   }
-  if (!route) return;
 #pragma unroll
   for (int e = 0; e < 8; ++e)
 #pragma unroll
@@ -563,7 +547,7 @@ __global__ __launch_bounds__(256) void bwd_reduce_kernel(const float* __restrict
 size_t a256(size_t n) { return (n + 255) & ~(size_t)255; }
 
 struct BwdWs {
-  size_t off_dq, off_d, off_lse, off_dg, off_part, off_kf, off_vf, total;
+  size_t off_d, off_lse, off_dg, off_part, off_kf, off_vf, total;
   int nparts, Tqp;
 };
 BwdWs carve(int BH, int Tq, int S, int d) {
@@ -572,8 +556,7 @@ BwdWs carve(int BH, int Tq, int S, int d) {
   w.nparts = (int)((rows + FIN_ROWS - 1) / FIN_ROWS);
   w.Tqp = (Tq + 31) / 32 * 32;  // D and LSE rows are padded to whole 32-row tiles per (b,h)
   const size_t prows = (size_t)BH * w.Tqp;
-  w.off_dq = 0;
-  w.off_d = a256(rows * d * sizeof(float));
+  w.off_d = 0;
   w.off_lse = w.off_d + a256(prows * sizeof(float));
   w.off_dg = w.off_lse + a256(prows * sizeof(float));
   w.off_part = w.off_dg + a256(rows * 3 * sizeof(float));
@@ -588,7 +571,6 @@ hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
   using L = BwdSmem<D>;
   const BwdWs w = carve(a.BH, a.Tq, a.S, D);
   unsigned char* ws = static_cast<unsigned char*>(a.workspace);
-  float* dQacc = reinterpret_cast<float*>(ws + w.off_dq);
   float* Dp = reinterpret_cast<float*>(ws + w.off_d);
   float* LSE2p = reinterpret_cast<float*>(ws + w.off_lse);
   float* dgate = a.W_r ? reinterpret_cast<float*>(ws + w.off_dg) : nullptr;
@@ -635,16 +617,16 @@ hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
   if (e != hipSuccess) return e;
 
   BwdDqArgs q;
-  q.Q = a.Q; q.dO = a.dO; q.Kf = Kf; q.Vf = Vf; q.LSE2p = LSE2p; q.Dp = Dp; q.Tqp = w.Tqp; q.dQacc = dQacc;
+  q.Q = a.Q; q.dO = a.dO; q.Kf = Kf; q.Vf = Vf; q.LSE2p = LSE2p; q.Dp = Dp; q.Tqp = w.Tqp; q.dgate = dgate; q.W_r = a.W_r; q.dQ = a.dQ;
   q.BH = a.BH; q.Tq = a.Tq; q.S = a.S; q.d = D; q.causal = a.causal; q.scale = a.scale;
   e = launch_bwd_dq_bf16(q, st);
   if (e != hipSuccess) return e;
 
-  hipLaunchKernelGGL((bwd_finish_kernel<D>), dim3(w.nparts), dim3(256), 0, st, dQacc, dgate,
-                     (const bf16*)a.Q, a.W_r, (bf16*)a.dQ, dWpart, rows, a.scale);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
   if (a.W_r && (a.dW_r || a.db_r)) {
+    hipLaunchKernelGGL((bwd_wpart_kernel<D>), dim3(w.nparts), dim3(256), 0, st, dgate,
+                       (const bf16*)a.Q, dWpart, rows);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(bwd_reduce_kernel, dim3(D * 3 + 3), dim3(256), 0, st, dWpart, w.nparts,
                        D * 3 + 3, a.dW_r, a.db_r);
     e = hipGetLastError();

@@ -2,9 +2,9 @@
 // no backward; this is the query-side part of the chain rule through Alg. 2 steps 6-9:
 //
 //   P[t,j]  = exp(tau Q[t].Kf[j] - LSE[t])        dP[t,j] = dO[t].Vf[j]
-//   dS[t,j] = P[t,j] (dP[t,j] - D[t])             dQacc[t] = sum_j dS[t,j] Kf[j]
+//   dS[t,j] = P[t,j] (dP[t,j] - D[t])             dQ[t] = tau sum_j dS[t,j] Kf[j] + sum_l dg[t,l] W_r[:,l]
 //
-// (the factor tau and the router term are added by the finish kernel).  A workgroup owns 256
+// (dg: gradient of the row's router logits, from the main kernel).  A workgroup owns 256
 // query rows and walks over the fused K / V stream, which the main backward kernel has written
 // to the workspace while it fused its own tiles: dQ of a row is then the sum over ITS OWN
 // workgroup's tiles, held in registers and stored once - the alternative, adding one partial
@@ -41,7 +41,7 @@ struct DqSmem {
   static constexpr int NB = 4;               // ring depth; slot s = K tile at 2 s TSZ, V tile after it
   static constexpr int RING = 2 * NB * TSZ;
   static constexpr int ESTR = D + 4;         // f32 per row of the epilogue's staging tile
-  static constexpr int EPI = DQ_BR * ESTR * 4;
+  static constexpr int EPI = DQ_BR * ESTR * 4 + D * 3 * 4;  // + the router weights
   static constexpr int TOTAL = RING > EPI ? RING : EPI;  // bytes
 };
 
@@ -130,7 +130,8 @@ template <int D>
 __global__ __launch_bounds__(DQ_NT, 1) void bwd_dq_kernel(
     const bf16* __restrict__ Q, const bf16* __restrict__ dO, const bf16* __restrict__ Kf,
     const bf16* __restrict__ Vf, const float* __restrict__ LSE2p, const float* __restrict__ Dp,
-    float* __restrict__ dQacc, int Tq, int Tqp, int S, int causal, float c, int n_qtiles, int BH,
+    const float* __restrict__ dgate, const float* __restrict__ W_r, bf16* __restrict__ dQ,
+    float tau, int Tq, int Tqp, int S, int causal, float c, int n_qtiles, int BH,
     int interleave) {
   using SM = DqSmem<D>;
   constexpr int BR = DQ_BR, BC = DQ_BC, ROWB = SM::ROWB;
@@ -277,10 +278,15 @@ __global__ __launch_bounds__(DQ_NT, 1) void bwd_dq_kernel(
   mx_wait_loads<0>();  // the surplus requests of the last tiles must land before LDS is reused
   __syncthreads();     // every wave is done with the tile buffers (the epilogue reuses them)
 
-  // ---- epilogue: dQ^T -> rows through LDS, coalesced 16-byte stores of f32
+  // ---- epilogue: dQ^T -> rows through LDS; dQ = tau acc + dg W_r^T, rounded once, coalesced
+  // stores (the 32 lanes of a half-wave write one row)
   {
     constexpr int ESTR = SM::ESTR;
     float* sE = reinterpret_cast<float*>(smem) + wave * (32 * ESTR);
+    float* sW = reinterpret_cast<float*>(smem) + DQ_BR * ESTR;
+    const bool route = W_r != nullptr && dgate != nullptr;
+    if (route)
+      for (int i = tid; i < D * 3; i += DQ_NT) sW[i] = W_r[i];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -290,14 +296,29 @@ __global__ __launch_bounds__(DQ_NT, 1) void bwd_dq_kernel(
             make_float4(acc[db][r], acc[db][r + 1], acc[db][r + 2], acc[db][r + 3]);
       }
     __syncthreads();
-    constexpr int FPR = D / 4;  // float4 per row
+    constexpr int FPR = D / 4;  // 4-element groups per row
 #pragma unroll
     for (int i = 0; i < 32 * FPR / 64; ++i) {
       const int item = lane + 64 * i;
       const int rr = item / FPR, ch = item % FPR;
       const float4 v4 = *reinterpret_cast<const float4*>(&sE[rr * ESTR + ch * 4]);
-      if (tw0 + rr < Tq)
-        *reinterpret_cast<float4*>(dQacc + (bh * (long)Tq + tw0 + rr) * D + ch * 4) = v4;
+      const int t = tw0 + rr;
+      if (t < Tq) {
+        float o[4] = {v4.x * tau, v4.y * tau, v4.z * tau, v4.w * tau};
+        if (route) {
+          const float* dgr = dgate + (bh * (long)Tq + t) * 3;
+          const float dg0 = dgr[0], dg1 = dgr[1], dg2 = dgr[2];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int k = ch * 4 + e;
+            o[e] += dg0 * sW[k * 3 + 0] + dg1 * sW[k * 3 + 1] + dg2 * sW[k * 3 + 2];
+          }
+        }
+        uint2 w;
+        w.x = pack_bf16x2(o[0], o[1]);
+        w.y = pack_bf16x2(o[2], o[3]);
+        *reinterpret_cast<uint2*>(dQ + (bh * (long)Tq + t) * D + ch * 4) = w;
+      }
     }
   }
 }
@@ -317,7 +338,7 @@ hipError_t launch_dq_t(const BwdDqArgs& a, hipStream_t st) {
   }
   hipLaunchKernelGGL((bwd_dq_kernel<D>), dim3((unsigned)nblocks), dim3(DQ_NT), smem, st,
                      (const bf16*)a.Q, (const bf16*)a.dO, (const bf16*)a.Kf, (const bf16*)a.Vf,
-                     a.LSE2p, a.Dp, a.dQacc, a.Tq, a.Tqp, a.S, a.causal, a.scale * kLog2e, n_qtiles, a.BH,
+                     a.LSE2p, a.Dp, a.dgate, a.W_r, (bf16*)a.dQ, a.scale, a.Tq, a.Tqp, a.S, a.causal, a.scale * kLog2e, n_qtiles, a.BH,
                      interleave);
   return hipGetLastError();
 }

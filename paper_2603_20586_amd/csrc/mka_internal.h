@@ -32,7 +32,7 @@ struct FwdArgs {
 hipError_t launch_fwd_bf16(const FwdArgs& a, hipStream_t st);
 hipError_t launch_fwd_f32(const FwdArgs& a, hipStream_t st);
 
-// dQ accumulator of the backward, [B*H,Tq,d] f32 = sum_j dS[t,j] Kf[j] (no factor tau)
+// dQ of the backward = tau sum_j dS[t,j] Kf[j] + dg W_r^T, [B*H,Tq,d] bf16
 struct BwdDqArgs {
   const void* Q;
   const void* dO;
@@ -40,7 +40,9 @@ struct BwdDqArgs {
   const void* Vf;
   const float* LSE2p;  // [B*H,Tqp] LSE in log2 units, rows padded per (b,h)
   const float* Dp;     // [B*H,Tqp] D = dO.O
-  float* dQacc;
+  const float* dgate;  // [B*H,Tq,3] gradient of the router logits, or null (gates were given)
+  const float* W_r;    // [d,3] or null
+  void* dQ;
   int BH, Tq, Tqp, S, d;
   int causal;
   float scale;
