@@ -151,33 +151,47 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   {
     bf16* sKrow = smem + L::OFF_KROW;
     bf16* sVrow = smem + L::OFF_VROW;
-    const bool full = (J0 + BCB <= len0) && (J0 + BCB <= len1) && (J0 + BCB <= len2);
+    const bf16* Ksrc[3] = {K0, K1, K2};
+    const bf16* Vsrc[3] = {V0, V1, V2};
+    const int lens[3] = {len0, len1, len2};
     for (int it = tid; it < (BCB / 4) * CPR; it += NT) {
       const int sg = it / CPR, cc = it % CPR;
-      float kf[4][8], vf[4][8];
+      // all 24 raw chunks and the gates of the item first (one round trip to memory instead of
+      // four): unconditional loads, an absent entry reads row 0 of the (b,h) block and is
+      // replaced by zeros afterwards
+      uint4 rk[4][3], rv[4][3];
+      float gg[4][3];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int j = J0 + sg * 4 + u;
         const int jc = j < S ? j : S - 1;
-        const bool in = j < S;
-        const long eoff = kvbase + (long)jc * D + cc * 8;
-        const float g0 = Gb[jc * 3 + 0], g1 = Gb[jc * 3 + 1], g2 = Gb[jc * 3 + 2];
-        Raw3 rk, rv;
-        if (full) {
-          rk = load_raw3<true, long>(K0, K1, K2, 0, eoff, true, true, true);
-          rv = load_raw3<true, long>(V0, V1, V2, 0, eoff, true, true, true);
-        } else {
-          rk = load_raw3<false, long>(K0, K1, K2, kvbase + cc * 8, eoff, in && j < len0,
-                                      in && j < len1, in && j < len2);
-          rv = load_raw3<false, long>(V0, V1, V2, kvbase + cc * 8, eoff, in && j < len0,
-                                      in && j < len1, in && j < len2);
+#pragma unroll
+        for (int l = 0; l < 3; ++l) {
+          const bool present = j < S && j < lens[l];
+          const long o = kvbase + (present ? (long)j * D : 0) + cc * 8;
+          rk[u][l] = *reinterpret_cast<const uint4*>(Ksrc[l] + o);
+          rv[u][l] = *reinterpret_cast<const uint4*>(Vsrc[l] + o);
+          gg[u][l] = Gb[jc * 3 + l];
         }
-        fuse8(rk, g0, g1, g2, kf[u]);
-        fuse8(rv, g0, g1, g2, vf[u]);
-        const uint4 pk = pack8(kf[u]), pv = pack8(vf[u]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int j = J0 + sg * 4 + u;
+        const bool in = j < S;
+        const uint4 z = make_uint4(0, 0, 0, 0);
+        Raw3 k3, v3;
+        k3.a = (in && j < len0) ? rk[u][0] : z;  v3.a = (in && j < len0) ? rv[u][0] : z;
+        k3.b = (in && j < len1) ? rk[u][1] : z;  v3.b = (in && j < len1) ? rv[u][1] : z;
+        k3.c = (in && j < len2) ? rk[u][2] : z;  v3.c = (in && j < len2) ? rv[u][2] : z;
+        float kf[8], vf[8];
+        fuse8(k3, gg[u][0], gg[u][1], gg[u][2], kf);
+        fuse8(v3, gg[u][0], gg[u][1], gg[u][2], vf);
+        const uint4 pk = pack8(kf), pv = pack8(vf);
         *reinterpret_cast<uint4*>(&sKrow[(sg * 4 + u) * RSTR + cc * 8]) = pk;
         *reinterpret_cast<uint4*>(&sVrow[(sg * 4 + u) * RSTR + cc * 8]) = pv;
         if (in) {  // the fused stream, for the dQ kernel
+          const long eoff = kvbase + (long)j * D + cc * 8;
           *reinterpret_cast<uint4*>(Kf_out + eoff) = pk;
           *reinterpret_cast<uint4*>(Vf_out + eoff) = pv;
         }
@@ -397,6 +411,25 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   bf16* dKp[3] = {dK0, dK1, dK2};
   bf16* dVp[3] = {dV0, dV1, dV2};
   const int len[3] = {len0, len1, len2};
+  // all raw K_l / V_l chunks and gates of the thread's items, for both passes, are requested now
+  // (unconditional loads: an absent entry reads row 0 of the (b,h) block and is not used): one
+  // round trip to memory for the whole epilogue, overlapped with the staging of the accumulators
+  uint4 rawK[NITEM][3], rawV[NITEM][3];
+  float gl[NITEM][3];
+#pragma unroll
+  for (int i = 0; i < NITEM; ++i) {
+    const int j = J0 + erow0 + ERS * i;
+    const int jc = j < S ? j : S - 1;
+#pragma unroll
+    for (int l = 0; l < 3; ++l) {
+      const bool present = j < S && j < len[l];
+      const long o = kvbase + (present ? (long)j * D : 0) + ecc * 8;
+      rawK[i][l] = *reinterpret_cast<const uint4*>(Kp[l] + o);
+      rawV[i][l] = *reinterpret_cast<const uint4*>(Vp[l] + o);
+      gl[i][l] = Gb[jc * 3 + l];
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int pass = 0; pass < 2; ++pass) {
     __syncthreads();  // LDS free (main loop done / previous pass consumed)
@@ -411,22 +444,6 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
         }
     }
     __syncthreads();
-    // all raw K_l / V_l chunks and gates of the thread's items first (unconditional loads: an
-    // absent entry reads row 0 of the (b,h) block and is not used), then the arithmetic
-    uint4 raw[NITEM][3];
-    float gl[NITEM][3];
-#pragma unroll
-    for (int i = 0; i < NITEM; ++i) {
-      const int j = J0 + erow0 + ERS * i;
-      const int jc = j < S ? j : S - 1;
-#pragma unroll
-      for (int l = 0; l < 3; ++l) {
-        const bool present = j < S && j < len[l];
-        const bf16* src = pass == 0 ? Kp[l] : Vp[l];
-        raw[i][l] = *reinterpret_cast<const uint4*>(src + kvbase + (present ? (long)j * D : 0) + ecc * 8);
-        gl[i][l] = Gb[jc * 3 + l];
-      }
-    }
 #pragma unroll
     for (int i = 0; i < NITEM; ++i) {
       const int sl = erow0 + ERS * i;
@@ -449,7 +466,7 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
           }
           if (present) {
             float x[8];
-            unpack8(raw[i][l], x);
+            unpack8(pass == 0 ? rawK[i][l] : rawV[i][l], x);
             float a = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) a = fmaf(v[e], x[e], a);
