@@ -80,6 +80,23 @@ def route(Q, W_r, b_r=None, S=None, G_prev=None):
     return G, idx
 
 
+ROUTE_SOFT, ROUTE_FIXED, ROUTE_TOP2, ROUTE_TOP1 = 0, 1, 2, 3
+
+
+def route_variant(Q, W_r, b_r=None, mode=ROUTE_SOFT, S=None, G_prev=None):
+    """Gates of the routing ablation (soft / fixed 1/3 / hard top-2 / hard top-1) for the Tq new
+    slots.  Returns (G [B,H,S,3], idx [B,H,Tq] int32 = argmax of the logits in every mode)."""
+    Q, W_r, b_r = f64(Q), f64(W_r), f64(b_r)
+    B, H, Tq, d = Q.shape
+    S = Tq if S is None else S
+    G = np.zeros((B, H, S, 3)) if G_prev is None else f64(G_prev).copy()
+    assert G.shape == (B, H, S, 3) and W_r.shape == (d, 3)
+    idx = np.zeros((B, H, Tq), dtype=np.int32)
+    lib().mka_oracle_route_variant(_p(Q), _p(W_r), _p(b_r), int(mode), B, H, Tq, S, d, _p(G),
+                                   idx.ctypes.data_as(_ip))
+    return G, idx
+
+
 def fuse(X, G, len3=None):
     """Xf[j] = sum_l [j < len_l] G[j,l] X_l[j] for a triple of memories X = (X1, X2, X3)."""
     X = [f64(x) for x in X]

@@ -91,6 +91,53 @@ void mka_oracle_route(const double* Q, const double* W_r, const double* b_r,
   }
 }
 
+/* ---- routing variants of the ablation (section "Routing Mechanism Ablation", table
+ * "Routing mechanism ablation"): the paper names them without formulas.  Reading: mode 0 = the
+ * learned soft gates of step 5; mode 1 = fixed lam = 1/3 for every level; mode 2 = hard top-2: the
+ * level with the smallest logit is dropped and the other two soft gates are renormalised to sum
+ * 1; mode 3 = hard top-1: the gate is the indicator of the largest logit.  Ties go to the lower
+ * level (the argmax keeps the lowest index, the dropped level is the highest index among equal
+ * minima). */
+void mka_oracle_route_variant(const double* Q, const double* W_r, const double* b_r, int mode,
+                              int B, int H, int Tq, int S, int d, double* G, int32_t* idx) {
+  long n = (long)B * H;
+#pragma omp parallel for schedule(static)
+  for (long bh = 0; bh < n; ++bh) {
+    for (int t = 0; t < Tq; ++t) {
+      const double* q = Q + ((size_t)bh * Tq + t) * d;
+      double g[3];
+      for (int l = 0; l < 3; ++l) {
+        double acc = b_r ? b_r[l] : 0.0;
+        for (int k = 0; k < d; ++k) acc = fma(q[k], W_r[(size_t)k * 3 + l], acc);
+        g[l] = acc;
+      }
+      int best = 0, drop = 0;
+      for (int l = 1; l < 3; ++l) {
+        if (g[l] > g[best]) best = l;
+        if (g[l] <= g[drop]) drop = l;
+      }
+      double lam[3];
+      if (mode == 1) {
+        lam[0] = lam[1] = lam[2] = 1.0 / 3.0;
+      } else if (mode == 3) {
+        for (int l = 0; l < 3; ++l) lam[l] = (l == best) ? 1.0 : 0.0;
+      } else {
+        double e[3], z = 0.0;
+        for (int l = 0; l < 3; ++l) {
+          e[l] = (mode == 2 && l == drop) ? 0.0 : exp(g[l] - g[best]);
+          z += e[l];
+        }
+        for (int l = 0; l < 3; ++l) lam[l] = e[l] / z;
+      }
+      if (G) {
+        double* row = G + ((size_t)bh * S + (S - Tq + t)) * 3;
+        for (int l = 0; l < 3; ++l) row[l] = lam[l];
+      }
+      if (idx) idx[(size_t)bh * Tq + t] = best;
+    }
+  }
+}
+
 /* ---- fusion: Alg. 2 step 6 (token-wise gate-weighted mix) ----------------- */
 void mka_oracle_fuse(const double* X1, const double* X2, const double* X3, const double* G,
                      const int32_t* len, int B, int H, int S, int d, double* Xf) {
