@@ -102,6 +102,28 @@ size_t mka_workspace_bytes(mka_op op, const mka_shape* shape);
 mka_status mka_route(const void* Q, const float* W_r, const float* b_r, float* G_out,
                      int32_t* idx_out, const mka_shape* shape, void* stream);
 
+/* Routing variants of the paper's ablation (section "Routing Mechanism Ablation", table
+ * "Routing mechanism ablation"); the paper names them without formulas, this is the reading:
+ *   MKA_ROUTE_SOFT   the learned soft gates of Alg. 2 step 5 (= mka_route)
+ *   MKA_ROUTE_FIXED  lam = 1/3 for every level
+ *   MKA_ROUTE_TOP2   the level with the smallest logit gets 0, the other two soft gates are
+ *                    renormalised to sum 1
+ *   MKA_ROUTE_TOP1   the gate is the indicator of the largest logit
+ * Ties go to the lower level (argmax: lowest index; dropped level: highest index among equal
+ * minima); the decisions are taken on the fp64 logits of mka_route.  Arguments, layout and
+ * errors as for mka_route (W_r is required in every mode: idx_out is the argmax of the logits);
+ * an unknown mode gives MKA_ERR_UNSUPPORTED.  The gates are data for mka_fused_attn_fwd and
+ * mka_fused_attn_bwd called without W_r (hard gates carry no router gradient). */
+typedef enum {
+  MKA_ROUTE_SOFT = 0,
+  MKA_ROUTE_FIXED = 1,
+  MKA_ROUTE_TOP2 = 2,
+  MKA_ROUTE_TOP1 = 3
+} mka_routing;
+mka_status mka_route_variant(const void* Q, const float* W_r, const float* b_r, int32_t mode,
+                             float* G_out, int32_t* idx_out, const mka_shape* shape,
+                             void* stream);
+
 /* Alg. 2 steps 5-7 and 9 for Tq query rows (prefill, or a training forward).
  *   Q     in     [B,H,Tq,d]
  *   K,V   in     three [B,H,S,d] each (entry NULL = level absent)

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     mka_fused_attn_fwd,
     mka_mixture_attn_fwd,
     mka_route,
+    mka_route_variant,
     mka_workspace_bytes,
     status_string,
 )

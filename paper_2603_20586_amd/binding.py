@@ -55,6 +55,9 @@ def lib() -> ctypes.CDLL:
         L.mka_route.restype = ctypes.c_int
         L.mka_route.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                 POINTER(MkaShape), c_void_p]
+        L.mka_route_variant.restype = ctypes.c_int
+        L.mka_route_variant.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p,
+                                        POINTER(MkaShape), c_void_p]
         L.mka_fused_attn_fwd.restype = ctypes.c_int
         L.mka_fused_attn_fwd.argtypes = [c_void_p, POINTER(_P3), POINTER(_P3), c_void_p, c_void_p,
                                          c_void_p, c_void_p, c_void_p, c_void_p,
@@ -155,6 +158,24 @@ def mka_route(Q, W_r, b_r=None, S=None, G=None, want_idx=True):
     s = _shape(Q, S, None, False, 1.0)
     _check(lib().mka_route(_ptr(Q), _ptr(W_r), _ptr(b_r), _ptr(G), _ptr(idx), ctypes.byref(s),
                            _stream()), "mka_route")
+    return G, idx
+
+
+MKA_ROUTE_SOFT, MKA_ROUTE_FIXED, MKA_ROUTE_TOP2, MKA_ROUTE_TOP1 = 0, 1, 2, 3
+
+
+def mka_route_variant(Q, W_r, b_r=None, mode=MKA_ROUTE_SOFT, S=None, G=None, want_idx=True):
+    """Gates of the routing ablation (soft / fixed 1/3 / hard top-2 / hard top-1).  Returns
+    (G [B,H,S,3] f32, idx [B,H,Tq] int32 or None); arguments as for mka_route."""
+    _dev_check(Q, W_r, b_r, G)
+    B, H, Tq, d = Q.shape
+    S = Tq if S is None else S
+    if G is None:
+        G = torch.zeros((B, H, S, 3), dtype=torch.float32, device=Q.device)
+    idx = torch.empty((B, H, Tq), dtype=torch.int32, device=Q.device) if want_idx else None
+    s = _shape(Q, S, None, False, 1.0)
+    _check(lib().mka_route_variant(_ptr(Q), _ptr(W_r), _ptr(b_r), int(mode), _ptr(G), _ptr(idx),
+                                   ctypes.byref(s), _stream()), "mka_route_variant")
     return G, idx
 
 

@@ -85,6 +85,13 @@ size_t mka_workspace_bytes(mka_op op, const mka_shape* s) {
 
 mka_status mka_route(const void* Q, const float* W_r, const float* b_r, float* G_out,
                      int32_t* idx_out, const mka_shape* shape, void* stream) {
+  return mka_route_variant(Q, W_r, b_r, MKA_ROUTE_SOFT, G_out, idx_out, shape, stream);
+}
+
+mka_status mka_route_variant(const void* Q, const float* W_r, const float* b_r, int32_t mode,
+                             float* G_out, int32_t* idx_out, const mka_shape* shape,
+                             void* stream) {
+  if (mode < MKA_ROUTE_SOFT || mode > MKA_ROUTE_TOP1) return MKA_ERR_UNSUPPORTED;
   bool empty = false;
   mka_shape tmp;
   if (!shape) return MKA_ERR_NULL;
@@ -102,6 +109,7 @@ mka_status mka_route(const void* Q, const float* W_r, const float* b_r, float* G
   a.Q = Q; a.W_r = W_r; a.b_r = b_r; a.G = G_out; a.idx = idx_out;
   a.BH = shape->B * shape->H; a.Tq = shape->Tq; a.S = shape->S; a.d = shape->d;
   a.bf16 = shape->dtype == MKA_BF16;
+  a.mode = mode;
   return mka::launch_route(a, (hipStream_t)stream) == hipSuccess ? MKA_OK : MKA_ERR_LAUNCH;
 }
 

@@ -61,6 +61,36 @@ __device__ __forceinline__ int gates_from_logits(double g0, double g1, double g2
   return best;
 }
 
+// Gates of the routing variants (paper: section "Routing Mechanism Ablation"): mode 0 soft (the
+// function above), 1 fixed 1/3, 2 hard top-2 (the smallest logit is dropped, the other two soft
+// gates renormalised), 3 hard top-1 (indicator of the largest logit).  Ties go to the lower level.
+// The decisions are taken on the fp64 logits.  Returns the argmax.
+__device__ __forceinline__ int gates_variant(double g0, double g1, double g2, int mode, float* lam) {
+  if (mode == 0) return gates_from_logits(g0, g1, g2, lam);
+  int best = 0, drop = 0;
+  double gm = g0, gn = g0;
+  if (g1 > gm) { gm = g1; best = 1; }
+  if (g2 > gm) { gm = g2; best = 2; }
+  if (g1 <= gn) { gn = g1; drop = 1; }
+  if (g2 <= gn) { gn = g2; drop = 2; }
+  if (mode == 1) {
+    lam[0] = lam[1] = lam[2] = 1.0f / 3.0f;
+  } else if (mode == 3) {
+    lam[0] = best == 0 ? 1.f : 0.f;
+    lam[1] = best == 1 ? 1.f : 0.f;
+    lam[2] = best == 2 ? 1.f : 0.f;
+  } else {
+    const float e0 = drop == 0 ? 0.f : expf((float)(g0 - gm));
+    const float e1 = drop == 1 ? 0.f : expf((float)(g1 - gm));
+    const float e2 = drop == 2 ? 0.f : expf((float)(g2 - gm));
+    const float inv = 1.0f / (e0 + e1 + e2);
+    lam[0] = e0 * inv;
+    lam[1] = e1 * inv;
+    lam[2] = e2 * inv;
+  }
+  return best;
+}
+
 // 16-byte streaming load (data that is read exactly once).
 __device__ __forceinline__ uint4 load16_stream(const void* p) {
   const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));

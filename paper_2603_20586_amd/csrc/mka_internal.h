@@ -14,6 +14,7 @@ struct RouteArgs {
   int32_t* idx;       // [B*H*Tq] or null
   int BH, Tq, S, d;
   bool bf16;
+  int mode = 0;       // mka_routing
 };
 hipError_t launch_route(const RouteArgs& a, hipStream_t st);
 

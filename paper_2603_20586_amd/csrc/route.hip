@@ -1,5 +1,6 @@
 // Router kernel: Alg. 2 step 5 of the paper — gates lam = softmax_3(Q W_r + b_r), one triple
-// per token, plus the argmax of the logits.
+// per token, plus the argmax of the logits; also the routing variants of the paper's ablation
+// (section "Routing Mechanism Ablation": fixed 1/3, hard top-2, hard top-1).
 //
 // One lane owns one query row.  The logits are an fp64 fma chain in ascending k that starts
 // from the bias; every product bf16*f32 or f32*f32 is exact in fp64 and each fma is correctly
@@ -16,7 +17,7 @@ __global__ __launch_bounds__(64) void route_kernel(const T* __restrict__ Q,
                                                    const float* __restrict__ W_r,
                                                    const float* __restrict__ b_r,
                                                    float* __restrict__ G, int32_t* __restrict__ idx,
-                                                   long rows, int Tq, int S) {
+                                                   long rows, int Tq, int S, int mode) {
   constexpr int ROWB = D * (int)sizeof(T);   // bytes per row
   constexpr int STR = ROWB + 16;             // padded LDS row stride (bytes)
   constexpr int CPR = ROWB / 16;             // 16-byte chunks per row
@@ -62,7 +63,7 @@ __global__ __launch_bounds__(64) void route_kernel(const T* __restrict__ Q,
     }
   }
   float lam[3];
-  const int best = gates_from_logits(g0, g1, g2, lam);
+  const int best = gates_variant(g0, g1, g2, mode, lam);
   if (idx) idx[row] = best;
   if (G) {
     const long bh = row / Tq;
@@ -80,7 +81,7 @@ hipError_t launch_route(const RouteArgs& a, hipStream_t st) {
   const unsigned grid = (unsigned)((rows + 63) / 64);
 #define MKA_ROUTE(T, D)                                                                        \
   hipLaunchKernelGGL((route_kernel<T, D>), dim3(grid), dim3(64), 0, st, (const T*)a.Q, a.W_r, \
-                     a.b_r, a.G, a.idx, rows, a.Tq, a.S)
+                     a.b_r, a.G, a.idx, rows, a.Tq, a.S, a.mode)
   if (a.bf16) {
     if (a.d == 128) MKA_ROUTE(bf16, 128); else MKA_ROUTE(bf16, 64);
   } else {

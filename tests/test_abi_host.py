@@ -92,6 +92,10 @@ def test_route_and_bwd_reject_bad_arguments(m):
     assert L.mka_route(FAKE, None, None, FAKE, None, ctypes.byref(s), None) == 1
     assert L.mka_route(FAKE, FAKE, None, FAKE, None, None, None) == 1
     assert L.mka_route(FAKE, FAKE, None, FAKE + 4, None, ctypes.byref(s), None) == 4
+    # routing variants: same checks, and the mode must be one of the four
+    assert L.mka_route_variant(FAKE, FAKE, None, 4, FAKE, None, ctypes.byref(s), None) == 6
+    assert L.mka_route_variant(FAKE, FAKE, None, -1, FAKE, None, ctypes.byref(s), None) == 6
+    assert L.mka_route_variant(FAKE, None, None, 1, FAKE, None, ctypes.byref(s), None) == 1
     p3 = _P3(FAKE, FAKE, FAKE)
     args = lambda shp, ws, wsb: L.mka_fused_attn_bwd(  # noqa: E731
         FAKE, FAKE, ctypes.byref(p3), ctypes.byref(p3), FAKE, FAKE, FAKE, FAKE, FAKE,

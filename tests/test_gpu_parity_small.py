@@ -53,6 +53,69 @@ def test_route_exact_ties_go_to_lowest_level(mka):
     assert torch.all(G == torch.tensor(1.0 / 3.0, dtype=torch.float32))
 
 
+# ------------------------------------------------------------------ routing variants
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 128)])
+@pytest.mark.parametrize("mode", [0, 1, 2, 3])
+def test_route_variants(mka, oracle, dtype, d, mode):
+    """Soft / fixed / hard top-2 / hard top-1 gates: values within the gate tolerance, zeros and
+    ones exactly where the oracle has them (the decisions are taken on the same fp64 logits),
+    argmax bit-exact in every mode."""
+    announce(f"route variant mode={mode} {dtype} d={d}")
+    B, H, Tq, S = 2, 3, 130, 200
+    inp = si.prefill_inputs(B, H, Tq, S, d, dtype=dtype, seed=12, device="cuda")
+    W = inp["W_r"] * 20.0
+    b = torch.tensor([0.1, -0.2, 0.05], device="cuda")
+    Gprev = torch.rand((B, H, S, 3), device="cuda")
+    G, idx = mka.mka_route_variant(inp["Q"], W, b, mode, S=S, G=Gprev.clone())
+    torch.cuda.synchronize()
+    Gref, idxref = oracle.route_variant(inp["Q"].cpu(), W.cpu(), b.cpu(), mode, S=S,
+                                        G_prev=Gprev.cpu())
+    np.testing.assert_array_equal(idx.cpu().numpy(), idxref)
+    assert max_abs(G, Gref) <= GATE_ATOL
+    Gn = G.cpu().numpy().astype(np.float64)
+    np.testing.assert_array_equal(Gn[:, :, S - Tq:] == 0.0, Gref[:, :, S - Tq:] == 0.0)
+    np.testing.assert_array_equal(Gn[:, :, S - Tq:] == 1.0, Gref[:, :, S - Tq:] == 1.0)
+    assert torch.equal(G[:, :, :S - Tq], Gprev[:, :, :S - Tq])
+
+
+def test_route_variants_ties(mka):
+    announce("route variant ties")
+    Q = torch.randn((1, 2, 50, 64), device="cuda").bfloat16()
+    W = torch.zeros((64, 3), device="cuda")
+    G1, idx = mka.mka_route_variant(Q, W, None, 3)
+    G2, _ = mka.mka_route_variant(Q, W, None, 2)
+    assert torch.all(idx == 0)
+    assert torch.equal(G1, torch.tensor([1.0, 0.0, 0.0], device="cuda").expand_as(G1))
+    assert torch.equal(G2, torch.tensor([0.5, 0.5, 0.0], device="cuda").expand_as(G2))
+
+
+@pytest.mark.parametrize("mode", [1, 2, 3])
+def test_fwd_bwd_with_variant_gates(mka, oracle, mode):
+    """The variants' gates through the route-fused forward and backward (gates given: no router
+    gradient), against the oracle fed with its own variant gates."""
+    announce(f"fwd+bwd with routing variant {mode}")
+    B, H, T, d = 1, 2, 150, 128
+    inp = si.prefill_inputs(B, H, T, T, d, dtype="bf16", seed=14, device="cuda", with_dO=True)
+    W = inp["W_r"] * 10.0
+    G, _ = mka.mka_route_variant(inp["Q"], W, inp["b_r"], mode)
+    O, LSE, _, _ = mka.mka_fused_attn_fwd(inp["Q"], inp["K"], inp["V"], None, None, G=G,
+                                          causal=True, scale=inp["scale"])
+    g = mka.mka_fused_attn_bwd(inp["dO"], inp["Q"], inp["K"], inp["V"], G, O, LSE, None,
+                               causal=True, scale=inp["scale"])
+    torch.cuda.synchronize()
+    Gref, _ = oracle.route_variant(inp["Q"].cpu(), W.cpu(), inp["b_r"].cpu(), mode)
+    Oref, LSEref = oracle.fwd(inp["Q"].cpu(), cpu_list(inp["K"]), cpu_list(inp["V"]), Gref,
+                              causal=True, tau=inp["scale"])
+    assert max_abs(O, Oref) <= BF16_ATOL
+    assert max_abs(LSE, LSEref) <= BF16_ATOL
+    ref = oracle.bwd(inp["dO"].cpu(), inp["Q"].cpu(), cpu_list(inp["K"]), cpu_list(inp["V"]), Gref,
+                     None, causal=True, tau=inp["scale"])
+    for name, x, r in [("dQ", g["dQ"], ref["dQ"])] + \
+            [(f"dK{l}", g["dK"][l], ref["dK"][l]) for l in range(3)] + \
+            [(f"dV{l}", g["dV"][l], ref["dV"][l]) for l in range(3)]:
+        assert max_abs(x, r) / max(1.0, float(np.abs(r).max())) <= BF16_ATOL, name
+
+
 # ------------------------------------------------------------------ forward, f32
 def test_fwd_f32_tiny_config(mka, oracle):
     """Config C1: B=1 H=2 d=64 Tq=128 causal, Q pre-scaled by 1/sqrt(64), scale 1, seed 0."""
