@@ -141,6 +141,35 @@ def mixture_fwd(Q, K, V, lam=None, causal=True, tau=1.0):
     return O, LSE
 
 
+def full_mka_fwd(Q, K, V, lam, causal=True, tau=1.0):
+    """Symbolic (full) MKA, Alg. 1: one softmax attention per memory, a_l = softmax(tau Q K_l^T) V_l
+    (every memory with its own length and bottom-right causal mask), combined at the output with
+    the per-QUERY gates: O[t] = sum_l lam[t,l] a_l[t].  A missing memory (None) contributes a_l = 0
+    (the algorithm's M_3 = 0 gives k_3 = v_3 = 0, hence a_3 = 0).  Returns O."""
+    Q, lam = f64(Q), f64(lam)
+    O = np.zeros_like(Q)
+    for l in range(3):
+        if K[l] is None or V[l] is None:
+            continue
+        a_l, _ = attn_fwd(Q, K[l], V[l], causal=causal, tau=tau)
+        O += lam[..., l:l + 1] * a_l
+    return O
+
+
+def prefix_mean(X):
+    """Causal prefix-mean summary, Alg. 1 (the L2 memory: M_2[t] = Summary(X[1..t]) with the
+    "prefix mean" choice): M[t] = (1/(t+1)) sum_{s<=t} X[s] along axis 2, one running sum in
+    ascending s.  Because the K/V projections are linear, the L2 keys/values are the prefix
+    mean of the L1 keys/values, which is how it is used here."""
+    X = f64(X)
+    out = np.empty_like(X)
+    run = np.zeros(X.shape[:2] + X.shape[3:])
+    for t in range(X.shape[2]):
+        run = run + X[:, :, t]
+        out[:, :, t] = run / (t + 1)
+    return out
+
+
 def attn_fwd_blockwise(Q, Kf, Vf, Bc, causal=True, tau=1.0):
     """Same result through the max-shift recursion over KV blocks of Bc slots."""
     Q, Kf, Vf = f64(Q), f64(Kf), f64(Vf)
