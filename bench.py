@@ -222,6 +222,15 @@ def main():
         msp = time_region(lambda: mka.mka_mixture_attn_fwd(
             inp3["Q"], [inp3["K"][0], None, None], [inp3["V"][0], None, None], None, causal=True,
             scale=inp3["scale"], O=O3, LSE=L3), 5, 2)
+        # symbolic (full) MKA of Alg. 1 on the same memories: three attentions + a combine pass
+        from paper_2603_20586_amd.binding import MKA_OP_FULL_MKA
+        wsf = torch.empty(mka.mka_workspace_bytes(MKA_OP_FULL_MKA, shp3), dtype=torch.uint8, device=dev)
+        msfull = time_region(lambda: mka.mka_full_attn_fwd(
+            inp3["Q"], inp3["K"], inp3["V"], G3, causal=True, scale=inp3["scale"], O=O3,
+            workspace=wsf), 5, 2)
+        del wsf
+        workloads["C3_full_mka_fwd"] = {"ms": msfull, "tflops": 3 * fl3 / msfull / 1e9,
+                                        "vs_route_fused": msfull / ms3}
         workloads["C3_gated_mixture_fwd"] = {"ms": msm, "tflops": 3 * fl3 / msm / 1e9}
         workloads["C3_plain_attention_fwd"] = {"ms": msp, "tflops": fl3 / msp / 1e9}
         rooflines["C3_mixture"] = roof_mfma(3 * fl3, msm, "mix_bf16_kernel")

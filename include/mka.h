@@ -60,7 +60,9 @@ typedef enum {
   MKA_OP_FWD = 1,              /* what mka_fused_attn_fwd should be given for this shape  */
   MKA_OP_DECODE = 2,
   MKA_OP_BWD = 3,
-  MKA_OP_FWD_MATERIALISED = 4  /* what makes mka_fused_attn_fwd write Kf, Vf (see there)   */
+  MKA_OP_FWD_MATERIALISED = 4, /* what makes mka_fused_attn_fwd write Kf, Vf (see there)   */
+  MKA_OP_FULL_MKA = 5,         /* mka_full_attn_fwd: three partial outputs [B,H,Tq,d]      */
+  MKA_OP_PREFIX_MEAN = 6       /* mka_prefix_mean: chunk sums                              */
 } mka_op;
 
 /* Problem shape of route / forward / backward. */
@@ -220,6 +222,30 @@ mka_status mka_fuse_kv(const void* const K[3], const void* const V[3], const flo
 mka_status mka_mixture_attn_fwd(const void* Q, const void* const K[3], const void* const V[3],
                                 const float* G, void* O, float* LSE, const mka_shape* shape,
                                 void* stream);
+
+/* Symbolic (full) MKA, Alg. 1 of the paper - the three-path variant that FastMKA replaces: one
+ * softmax attention per memory, mixed at the output with the gates of the QUERY rows:
+ *
+ *   a_l = softmax(scale Q K_l^T) V_l,      O[t] = sum_l G[t,l] a_l[t]
+ *
+ * Q, O [B,H,Tq,d]; K[l], V[l] [B,H,len[l],d] (device, bf16, 16-byte aligned; NULL entry or
+ * len[l] == 0: the memory is absent and contributes a_l = 0, as the algorithm's M_3 = 0 does);
+ * G [B,H,Tq,3] f32.  causal as for mka_mixture_attn_fwd (own bottom-right mask per memory,
+ * len[l] >= Tq).  workspace: mka_workspace_bytes(MKA_OP_FULL_MKA, shape) bytes, 256-byte
+ * aligned (the three partial outputs, bf16; scratch).  The launches are three plain attentions
+ * and one combine pass.  bf16 only, d in {64,128}; errors as for mka_fused_attn_fwd. */
+mka_status mka_full_attn_fwd(const void* Q, const void* const K[3], const void* const V[3],
+                             const float* G, void* O, const mka_shape* shape, void* workspace,
+                             size_t workspace_bytes, void* stream);
+
+/* Causal prefix-mean summary (Alg. 1: M_2[t] = Summary(X[1..t]), the "prefix mean" choice):
+ * M[b,h,t,:] = mean over s <= t of X[b,h,s,:].  X, M [B,H,S,d] (device, bf16, 16-byte aligned,
+ * M fully overwritten; B,H,S,d,dtype of the shape are read).  Applied to the L1 keys / values
+ * it gives the L2 keys / values of Alg. 1 (the projections are linear).  Sums are f32 in a fixed
+ * order (chunks of 64 rows); one rounding on store.  workspace:
+ * mka_workspace_bytes(MKA_OP_PREFIX_MEAN, shape) bytes, 256-byte aligned. */
+mka_status mka_prefix_mean(const void* X, void* M, const mka_shape* shape, void* workspace,
+                           size_t workspace_bytes, void* stream);
 
 /* Measurement helpers (not part of the method): the ceilings that the rooflines of the
  * attention kernels are quoted against besides the vendor peaks.

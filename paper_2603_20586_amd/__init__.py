@@ -16,7 +16,9 @@ from .binding import (  # noqa: F401
     mka_fused_attn_bwd,
     mka_fused_attn_decode,
     mka_fuse_kv,
+    mka_full_attn_fwd,
     mka_fused_attn_fwd,
+    mka_prefix_mean,
     mka_mixture_attn_fwd,
     mka_route,
     mka_route_variant,

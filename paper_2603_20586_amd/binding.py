@@ -12,6 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "libmka.so")
 
 MKA_F32, MKA_BF16 = 0, 1
 MKA_OP_ROUTE, MKA_OP_FWD, MKA_OP_DECODE, MKA_OP_BWD, MKA_OP_FWD_MATERIALISED = 0, 1, 2, 3, 4
+MKA_OP_FULL_MKA, MKA_OP_PREFIX_MEAN = 5, 6
 
 
 class MkaError(RuntimeError):
@@ -55,6 +56,12 @@ def lib() -> ctypes.CDLL:
         L.mka_route.restype = ctypes.c_int
         L.mka_route.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                 POINTER(MkaShape), c_void_p]
+        L.mka_full_attn_fwd.restype = ctypes.c_int
+        L.mka_full_attn_fwd.argtypes = [c_void_p, POINTER(_P3), POINTER(_P3), c_void_p, c_void_p,
+                                        POINTER(MkaShape), c_void_p, c_size_t, c_void_p]
+        L.mka_prefix_mean.restype = ctypes.c_int
+        L.mka_prefix_mean.argtypes = [c_void_p, c_void_p, POINTER(MkaShape), c_void_p, c_size_t,
+                                      c_void_p]
         L.mka_route_variant.restype = ctypes.c_int
         L.mka_route_variant.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p,
                                         POINTER(MkaShape), c_void_p]
@@ -316,6 +323,38 @@ def mka_mixture_attn_fwd(Q, K, V, G=None, causal=True, scale=1.0, want_lse=True,
     _check(lib().mka_mixture_attn_fwd(_ptr(Q), ctypes.byref(Kp), ctypes.byref(Vp), _ptr(G), _ptr(O),
                                       _ptr(LSE), ctypes.byref(s), _stream()), "mka_mixture_attn_fwd")
     return O, LSE
+
+
+def mka_full_attn_fwd(Q, K, V, G, causal=True, scale=1.0, O=None, workspace=None):
+    """Symbolic (full) MKA, Alg. 1: one attention per memory, outputs mixed with the gates of the
+    query rows G [B,H,Tq,3].  Returns O."""
+    _dev_check(Q, G, *K, *V)
+    B, H, Tq, d = Q.shape
+    len3 = [0 if k is None else k.shape[2] for k in K]
+    if O is None:
+        O = torch.empty_like(Q)
+    s = _shape(Q, max(len3 + [Tq]), len3, causal, scale)
+    if workspace is None:
+        workspace = _workspace(mka_workspace_bytes(MKA_OP_FULL_MKA, s), Q.device)
+    Kp, Vp = _p3(K), _p3(V)
+    _check(lib().mka_full_attn_fwd(_ptr(Q), ctypes.byref(Kp), ctypes.byref(Vp), _ptr(G), _ptr(O),
+                                   ctypes.byref(s), _ptr(workspace), workspace.numel(), _stream()),
+           "mka_full_attn_fwd")
+    return O
+
+
+def mka_prefix_mean(X, M=None, workspace=None):
+    """Causal prefix mean along the sequence axis of X [B,H,S,d] (the L2 summary of Alg. 1)."""
+    _dev_check(X, M)
+    B, H, S, d = X.shape
+    if M is None:
+        M = torch.empty_like(X)
+    s = _shape(X, S, None, False, 1.0)
+    if workspace is None:
+        workspace = _workspace(mka_workspace_bytes(MKA_OP_PREFIX_MEAN, s), X.device)
+    _check(lib().mka_prefix_mean(_ptr(X), _ptr(M), ctypes.byref(s), _ptr(workspace),
+                                 workspace.numel(), _stream()), "mka_prefix_mean")
+    return M
 
 
 def mka_ceiling_mfma(out, workgroups: int, iters: int) -> float:

@@ -74,6 +74,12 @@ size_t mka_workspace_bytes(mka_op op, const mka_shape* s) {
       return fwd_prefers_materialised(s) ? fwd_materialise_bytes(s) : 0;
     case MKA_OP_FWD_MATERIALISED:
       return fwd_materialise_bytes(s);
+    case MKA_OP_FULL_MKA:
+      if (s->dtype != MKA_BF16 || s->Tq <= 0) return 0;
+      return 3 * align256(bh * (size_t)s->Tq * (size_t)s->d * 2);
+    case MKA_OP_PREFIX_MEAN:
+      if (s->dtype != MKA_BF16 || s->S <= 0) return 0;
+      return mka::prefix_mean_workspace_bytes((int)bh, s->S, s->d);
     case MKA_OP_DECODE:
       return align256(bh * mka::kMaxSplits * (size_t)(s->d + 2) * sizeof(float));
     case MKA_OP_BWD:
@@ -235,6 +241,74 @@ mka_status mka_mixture_attn_fwd(const void* Q, const void* const K[3], const voi
   a.causal = shape->causal ? 1 : 0;
   a.scale = shape->scale;
   return mka::launch_mix_bf16(a, (hipStream_t)stream) == hipSuccess ? MKA_OK : MKA_ERR_LAUNCH;
+}
+
+mka_status mka_full_attn_fwd(const void* Q, const void* const K[3], const void* const V[3],
+                             const float* G, void* O, const mka_shape* shape, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+  if (!shape) return MKA_ERR_NULL;
+  if (shape->dtype != MKA_F32 && shape->dtype != MKA_BF16) return MKA_ERR_DTYPE;
+  if (shape->B < 0 || shape->H < 0 || shape->Tq < 0 || shape->d <= 0) return MKA_ERR_SHAPE;
+  if (shape->d != 64 && shape->d != 128) return MKA_ERR_UNSUPPORTED;
+  if (shape->dtype != MKA_BF16) return MKA_ERR_UNSUPPORTED;  // bf16 MFMA path only
+  if (!(shape->scale >= 0.f) || isinf(shape->scale)) return MKA_ERR_UNSUPPORTED;
+  if (!Q || !K || !V || !G || !O) return MKA_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(O) || (reinterpret_cast<uintptr_t>(G) & 3u)) return MKA_ERR_ALIGN;
+  bool present[3];
+  bool any = false;
+  for (int l = 0; l < 3; ++l) {
+    if (!aligned16(K[l]) || !aligned16(V[l])) return MKA_ERR_ALIGN;
+    if (shape->len[l] < 0) return MKA_ERR_SHAPE;
+    present[l] = K[l] && V[l] && shape->len[l] > 0;
+    if (present[l] && shape->causal && shape->len[l] < shape->Tq) return MKA_ERR_SHAPE;
+    if (present[l] && (long long)shape->len[l] * shape->d >= (1ll << 31)) return MKA_ERR_UNSUPPORTED;
+    any = any || present[l];
+  }
+  if (!any) return MKA_ERR_NULL;
+  if (shape->B == 0 || shape->H == 0 || shape->Tq == 0) return MKA_OK;
+  const size_t per = align256((size_t)shape->B * shape->H * (size_t)shape->Tq * (size_t)shape->d * 2);
+  if (!workspace || workspace_bytes < 3 * per) return MKA_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MKA_ERR_ALIGN;
+  hipStream_t hs = (hipStream_t)stream;
+  const void* A[3] = {nullptr, nullptr, nullptr};
+  for (int l = 0; l < 3; ++l) {
+    if (!present[l]) continue;
+    void* a_l = static_cast<char*>(workspace) + l * per;
+    mka::MixArgs a;
+    a.Q = Q;
+    a.K[0] = K[l]; a.V[0] = V[l]; a.S[0] = shape->len[l];
+    a.K[1] = a.K[2] = a.V[1] = a.V[2] = nullptr;
+    a.S[1] = a.S[2] = 0;
+    a.G = nullptr; a.O = a_l; a.LSE = nullptr;
+    a.BH = shape->B * shape->H; a.Tq = shape->Tq; a.d = shape->d;
+    a.causal = shape->causal ? 1 : 0;
+    a.scale = shape->scale;
+    if (mka::launch_mix_bf16(a, hs) != hipSuccess) return MKA_ERR_LAUNCH;
+    A[l] = a_l;
+  }
+  const long rows = (long)shape->B * shape->H * shape->Tq;
+  return mka::launch_full_combine(A, G, O, rows, shape->d, hs) == hipSuccess ? MKA_OK
+                                                                              : MKA_ERR_LAUNCH;
+}
+
+mka_status mka_prefix_mean(const void* X, void* M, const mka_shape* shape, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  if (!shape) return MKA_ERR_NULL;
+  if (shape->dtype != MKA_F32 && shape->dtype != MKA_BF16) return MKA_ERR_DTYPE;
+  if (shape->B < 0 || shape->H < 0 || shape->S < 0 || shape->d <= 0) return MKA_ERR_SHAPE;
+  if (shape->d != 64 && shape->d != 128) return MKA_ERR_UNSUPPORTED;
+  if (shape->dtype != MKA_BF16) return MKA_ERR_UNSUPPORTED;
+  if (!X || !M) return MKA_ERR_NULL;
+  if (!aligned16(X) || !aligned16(M)) return MKA_ERR_ALIGN;
+  const int BH = shape->B * shape->H;
+  if (BH == 0 || shape->S == 0) return MKA_OK;
+  if (!workspace || workspace_bytes < mka::prefix_mean_workspace_bytes(BH, shape->S, shape->d))
+    return MKA_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MKA_ERR_ALIGN;
+  return mka::launch_prefix_mean(X, M, BH, shape->S, shape->d, workspace, (hipStream_t)stream) ==
+                 hipSuccess
+             ? MKA_OK
+             : MKA_ERR_LAUNCH;
 }
 
 mka_status mka_fused_attn_decode(const void* q, const void* const k_new[3],

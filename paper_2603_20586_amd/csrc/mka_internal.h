@@ -64,6 +64,14 @@ struct MixArgs {
 };
 hipError_t launch_mix_bf16(const MixArgs& a, hipStream_t st);
 
+// full (three-path) MKA: O = sum_l G[:,l] * A_l over rows [B*H*Tq]; null A_l = level absent
+hipError_t launch_full_combine(const void* const A[3], const float* G, void* O, long rows, int d,
+                               hipStream_t st);
+// causal prefix mean along S of X [B*H,S,d] bf16 -> M; workspace of prefix_mean_workspace_bytes
+size_t prefix_mean_workspace_bytes(int BH, int S, int d);
+hipError_t launch_prefix_mean(const void* X, void* M, int BH, int S, int d, void* workspace,
+                              hipStream_t st);
+
 struct PrefuseArgs {
   const void* K[3];
   const void* V[3];
