@@ -170,6 +170,40 @@ def prefix_mean(X):
     return out
 
 
+def paged_gather(pool, table, seq_len, b, h):
+    """Rows 0..seq_len[b]-1 of sequence b, head h out of a paged pool [n_pages,H,P,d]: slot j
+    lives in page table[b][j // P] at row j % P."""
+    P = pool.shape[2]
+    n = int(seq_len[b])
+    out = np.empty((n, pool.shape[3]))
+    for j in range(n):
+        out[j] = pool[int(table[b, j // P]), h, j % P]
+    return out
+
+
+def paged_fused_decode(q, Kpool, Vpool, table, seq_len, tau=1.0):
+    """One decode step over the fused KV cache in a paged layout (what the paper caches, section
+    "Route-Fused MKA (FastMKA)", in the paged layout of its long-context runs): for every (b,h)
+    softmax attention of the single query row over the sequence's own slots, gathered through
+    the page table.  q [B,H,1,d]; returns (O [B,H,1,d], LSE [B,H]); an empty sequence gives
+    O = 0, LSE = -inf."""
+    q, Kpool, Vpool = f64(q), f64(Kpool), f64(Vpool)
+    table, seq_len = np.asarray(table), np.asarray(seq_len)
+    B, H, _, d = q.shape
+    O = np.zeros((B, H, 1, d))
+    LSE = np.full((B, H), -np.inf)
+    for b in range(B):
+        for h in range(H):
+            if seq_len[b] <= 0:
+                continue
+            Kd = paged_gather(Kpool, table, seq_len, b, h)[None, None]
+            Vd = paged_gather(Vpool, table, seq_len, b, h)[None, None]
+            o, l = attn_fwd(q[b:b + 1, h:h + 1], Kd, Vd, causal=False, tau=tau)
+            O[b, h] = o[0, 0]
+            LSE[b, h] = l[0, 0, 0]
+    return O, LSE
+
+
 def attn_fwd_blockwise(Q, Kf, Vf, Bc, causal=True, tau=1.0):
     """Same result through the max-shift recursion over KV blocks of Bc slots."""
     Q, Kf, Vf = f64(Q), f64(Kf), f64(Vf)
