@@ -303,6 +303,29 @@ def main():
                                   "unit": "GB/s", "frac": gbps / PEAK_HBM_GBPS, "traffic": None}
         del cc, ws4
         torch.cuda.empty_cache()
+        # the same decode shape over the fused KV cache in pages (one K and one V stream: a third
+        # of the bytes), shuffled page table, one step at S0 slots
+        P4 = 128
+        npg = (S0 + P4 - 1) // P4
+        g4 = torch.Generator(device=dev).manual_seed(5)
+        Kp4 = torch.randn((B4 * npg, H4, P4, d), generator=g4, device=dev, dtype=torch.float32).to(torch.bfloat16) \
+            if B4 * npg * H4 * P4 * d < (1 << 31) else None
+        if Kp4 is None:
+            Kp4 = torch.empty((B4 * npg, H4, P4, d), device=dev, dtype=torch.bfloat16)
+            for i in range(0, B4 * npg, 64):
+                Kp4[i:i + 64] = torch.randn((min(64, B4 * npg - i), H4, P4, d), generator=g4,
+                                            device=dev).to(torch.bfloat16)
+        Vp4 = Kp4.flip(0).contiguous()
+        tab4 = torch.randperm(B4 * npg, generator=g4, device=dev).reshape(B4, npg).to(torch.int32)
+        sl4 = torch.full((B4,), S0, dtype=torch.int32, device=dev)
+        wsp = torch.empty(64 * B4 * H4 * (d + 2) * 4, dtype=torch.uint8, device=dev)
+        msp4 = time_region(lambda: mka.mka_paged_fused_decode(
+            q4, Kp4, Vp4, tab4, sl4, scale=1.0 / math.sqrt(d), O=O4, want_lse=False, workspace=wsp), 5, 2)
+        bytesp = 2 * B4 * H4 * S0 * d * 2
+        workloads["C4_paged_fused_decode"] = {"ms_per_step": msp4, "gbps": bytesp / msp4 / 1e6,
+                                              "page_size": P4, "vs_raw_cache_decode": ms4 / msp4}
+        del Kp4, Vp4, wsp
+        torch.cuda.empty_cache()
 
     # ------------------------------------------------------------------ measured ceilings
     # a pure MFMA loop and a streaming read, written in this library: what the part sustains,

@@ -238,6 +238,37 @@ mka_status mka_full_attn_fwd(const void* Q, const void* const K[3], const void* 
                              const float* G, void* O, const mka_shape* shape, void* workspace,
                              size_t workspace_bytes, void* stream);
 
+/* Problem shape of a decode step over the paged fused-KV cache. */
+typedef struct {
+  int32_t B, H, d;
+  int32_t page_size;  /* slots per page: a power of two, 16 <= page_size <= 1024            */
+  int32_t n_pages;    /* pages in the pool                                                   */
+  int32_t max_pages;  /* columns of the page table                                           */
+  int32_t n_splits;   /* split-K factor along the slots, 1..64; 0 = let the library choose   */
+  float scale;        /* tau                                                                 */
+} mka_paged_shape;
+
+/* Decode over the fused (routed) KV cache in a paged layout - what the paper caches (section
+ * "Route-Fused MKA (FastMKA)": fused keys / values instead of raw token KV) in the layout it
+ * uses for long contexts (section "Experimental Setup": contiguous up to 32K, paged beyond):
+ *
+ *   O[b,h] = softmax(scale q[b,h] . Kf[b,h,0..len[b]-1]^T) Vf[b,h,0..len[b]-1]
+ *
+ *   q        in  [B,H,1,d] bf16
+ *   Kpool,Vpool in [n_pages,H,page_size,d] bf16: slot j of sequence b, head h lives in page
+ *               table[b][j / page_size] at row j % page_size (e.g. written by mka_fuse_kv row by
+ *               row as tokens arrive; filling the pool is the caller's)
+ *   table    in  [B,max_pages] int32, device;  seq_len in [B] int32, device
+ *   O        out [B,H,1,d] bf16;  LSE out [B,H] f32 or NULL
+ * A length above max_pages * page_size and a page id outside the pool are clamped (the kernel
+ * never reads outside the pool); a sequence of length 0 gives O = 0, LSE = -inf.
+ * workspace: 64 * B*H * (d+2) * 4 bytes cover every n_splits (256-byte aligned).  bf16 only, d
+ * in {64,128}.  Enqueues on `stream` and returns; allocates nothing. */
+mka_status mka_paged_fused_decode(const void* q, const void* Kpool, const void* Vpool,
+                                  const int32_t* table, const int32_t* seq_len, void* O, float* LSE,
+                                  const mka_paged_shape* shape, void* workspace,
+                                  size_t workspace_bytes, void* stream);
+
 /* Causal prefix-mean summary (Alg. 1: M_2[t] = Summary(X[1..t]), the "prefix mean" choice):
  * M[b,h,t,:] = mean over s <= t of X[b,h,s,:].  X, M [B,H,S,d] (device, bf16, 16-byte aligned,
  * M fully overwritten; B,H,S,d,dtype of the shape are read).  Applied to the L1 keys / values

@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     mka_fuse_kv,
     mka_full_attn_fwd,
     mka_fused_attn_fwd,
+    mka_paged_fused_decode,
     mka_prefix_mean,
     mka_mixture_attn_fwd,
     mka_route,

@@ -26,6 +26,12 @@ class MkaShape(ctypes.Structure):
                 ("len", c_int32 * 3), ("dtype", c_int32), ("causal", c_int32), ("scale", c_float)]
 
 
+class MkaPagedShape(ctypes.Structure):
+    _fields_ = [("B", c_int32), ("H", c_int32), ("d", c_int32), ("page_size", c_int32),
+                ("n_pages", c_int32), ("max_pages", c_int32), ("n_splits", c_int32),
+                ("scale", ctypes.c_float)]
+
+
 class MkaDecodeShape(ctypes.Structure):
     _fields_ = [("B", c_int32), ("H", c_int32), ("d", c_int32), ("cap", c_int32 * 3),
                 ("capG", c_int32), ("dtype", c_int32), ("n_splits", c_int32), ("scale", c_float)]
@@ -62,6 +68,10 @@ def lib() -> ctypes.CDLL:
         L.mka_prefix_mean.restype = ctypes.c_int
         L.mka_prefix_mean.argtypes = [c_void_p, c_void_p, POINTER(MkaShape), c_void_p, c_size_t,
                                       c_void_p]
+        L.mka_paged_fused_decode.restype = ctypes.c_int
+        L.mka_paged_fused_decode.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                             c_void_p, c_void_p, POINTER(MkaPagedShape), c_void_p,
+                                             c_size_t, c_void_p]
         L.mka_route_variant.restype = ctypes.c_int
         L.mka_route_variant.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_void_p, c_void_p,
                                         POINTER(MkaShape), c_void_p]
@@ -341,6 +351,27 @@ def mka_full_attn_fwd(Q, K, V, G, causal=True, scale=1.0, O=None, workspace=None
                                    ctypes.byref(s), _ptr(workspace), workspace.numel(), _stream()),
            "mka_full_attn_fwd")
     return O
+
+
+def mka_paged_fused_decode(q, Kpool, Vpool, table, seq_len, scale=1.0, n_splits=0, O=None,
+                           want_lse=True, workspace=None):
+    """One decode step over the fused KV cache in a paged pool [n_pages,H,P,d]; table [B,max_pages]
+    int32 and seq_len [B] int32 on the device.  Returns (O [B,H,1,d], LSE [B,H] or None)."""
+    _dev_check(q, Kpool, Vpool, table, seq_len, O)
+    B, H, _, d = q.shape
+    s = MkaPagedShape()
+    s.B, s.H, s.d = B, H, d
+    s.page_size, s.n_pages, s.max_pages = int(Kpool.shape[2]), int(Kpool.shape[0]), int(table.shape[1])
+    s.n_splits, s.scale = int(n_splits), float(scale)
+    if O is None:
+        O = torch.empty_like(q)
+    LSE = torch.empty((B, H), dtype=torch.float32, device=q.device) if want_lse else None
+    if workspace is None:
+        workspace = _workspace(64 * B * H * (d + 2) * 4, q.device)
+    _check(lib().mka_paged_fused_decode(_ptr(q), _ptr(Kpool), _ptr(Vpool), _ptr(table), _ptr(seq_len),
+                                        _ptr(O), _ptr(LSE), ctypes.byref(s), _ptr(workspace),
+                                        workspace.numel(), _stream()), "mka_paged_fused_decode")
+    return O, LSE
 
 
 def mka_prefix_mean(X, M=None, workspace=None):

@@ -291,6 +291,37 @@ mka_status mka_full_attn_fwd(const void* Q, const void* const K[3], const void* 
                                                                               : MKA_ERR_LAUNCH;
 }
 
+mka_status mka_paged_fused_decode(const void* q, const void* Kpool, const void* Vpool,
+                                  const int32_t* table, const int32_t* seq_len, void* O, float* LSE,
+                                  const mka_paged_shape* s, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+  if (!s) return MKA_ERR_NULL;
+  if (s->B < 0 || s->H < 0 || s->d <= 0 || s->n_pages <= 0 || s->max_pages <= 0) return MKA_ERR_SHAPE;
+  if (s->d != 64 && s->d != 128) return MKA_ERR_UNSUPPORTED;
+  const int P = s->page_size;
+  if (P < 16 || P > 1024 || (P & (P - 1))) return MKA_ERR_SHAPE;
+  if ((long long)s->max_pages * P >= (1ll << 31)) return MKA_ERR_UNSUPPORTED;
+  if (s->n_splits < 0 || s->n_splits > mka::kMaxSplits) return MKA_ERR_SHAPE;
+  if (!(s->scale >= 0.f) || isinf(s->scale)) return MKA_ERR_UNSUPPORTED;
+  if (!q || !Kpool || !Vpool || !table || !seq_len || !O) return MKA_ERR_NULL;
+  if (!aligned16(q) || !aligned16(Kpool) || !aligned16(Vpool) || !aligned16(O) ||
+      (reinterpret_cast<uintptr_t>(table) & 3u) || (reinterpret_cast<uintptr_t>(seq_len) & 3u) ||
+      (reinterpret_cast<uintptr_t>(LSE) & 3u))
+    return MKA_ERR_ALIGN;
+  const int BH = s->B * s->H;
+  if (BH == 0) return MKA_OK;
+  int ns = s->n_splits ? s->n_splits : mka::decode_auto_splits(BH, s->max_pages * P);
+  const size_t need = align256((size_t)BH * ns * (size_t)(s->d + 2) * sizeof(float));
+  if (!workspace || workspace_bytes < need) return MKA_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MKA_ERR_ALIGN;
+  mka::PagedDecodeArgs a;
+  a.q = q; a.Kpool = Kpool; a.Vpool = Vpool; a.table = table; a.seq_len = seq_len;
+  a.partial = static_cast<float*>(workspace); a.O = O; a.LSE = LSE;
+  a.B = s->B; a.H = s->H; a.d = s->d; a.P = P; a.max_pages = s->max_pages; a.n_pages = s->n_pages;
+  a.n_splits = ns; a.scale = s->scale;
+  return mka::launch_paged_decode(a, (hipStream_t)stream) == hipSuccess ? MKA_OK : MKA_ERR_LAUNCH;
+}
+
 mka_status mka_prefix_mean(const void* X, void* M, const mka_shape* shape, void* workspace,
                            size_t workspace_bytes, void* stream) {
   if (!shape) return MKA_ERR_NULL;

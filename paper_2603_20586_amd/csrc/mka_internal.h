@@ -72,6 +72,21 @@ size_t prefix_mean_workspace_bytes(int BH, int S, int d);
 hipError_t launch_prefix_mean(const void* X, void* M, int BH, int S, int d, void* workspace,
                               hipStream_t st);
 
+// decode over the fused KV cache in a paged pool [n_pages,H,P,d] (bf16)
+struct PagedDecodeArgs {
+  const void* q;           // [B,H,1,d]
+  const void* Kpool;
+  const void* Vpool;
+  const int32_t* table;    // [B,max_pages] device
+  const int32_t* seq_len;  // [B] device
+  float* partial;          // [B*H,n_splits,d+2]
+  void* O;                 // [B,H,1,d]
+  float* LSE;              // [B,H] or null
+  int B, H, d, P, max_pages, n_pages, n_splits;
+  float scale;
+};
+hipError_t launch_paged_decode(const PagedDecodeArgs& a, hipStream_t st);
+
 struct PrefuseArgs {
   const void* K[3];
   const void* V[3];
