@@ -4,8 +4,8 @@
 // The fused stream is what the paper caches; attention over it is plain softmax attention
 // (mka_mixture_attn_fwd with one memory and no gates), decode over it reads a third of the bytes.
 //
-// One thread = one 16-byte chunk of one slot: six 16-byte loads, the slot's three gates, f32
-// mix, one rounding to bf16, two 16-byte stores.  Bound by HBM: 6 reads + 2 writes of S*d*2
+// One thread = one 16-byte chunk of two slots: twelve 16-byte streaming loads issued at once, the
+// slots' gates, f32 mix, one rounding to bf16, four 16-byte stores.  Bound by HBM: 6 reads + 2 writes of S*d*2
 // bytes per (batch, head).
 #include "fuse_tile.h"
 #include "mka_dev.h"
@@ -15,29 +15,54 @@ namespace mka {
 
 namespace {
 
+constexpr int PF_U = 2;  // slots per thread
+
 template <int D>
 __global__ __launch_bounds__(256) void prefuse_kernel(
     const bf16* __restrict__ K0, const bf16* __restrict__ K1, const bf16* __restrict__ K2,
     const bf16* __restrict__ V0, const bf16* __restrict__ V1, const bf16* __restrict__ V2,
     const float* __restrict__ G, bf16* __restrict__ Kf, bf16* __restrict__ Vf, long rows, int S,
     int len0, int len1, int len2) {
-  constexpr int CPR = D / 8;
-  const long item = (long)blockIdx.x * 256 + threadIdx.x;
-  const long row = item / CPR;  // (b,h,slot) flattened
-  const int cc = (int)(item % CPR);
-  if (row >= rows) return;
-  const int j = (int)(row % S);
-  const long base = row - j;  // first row of the (b,h) block: always exists
-  const bool p0 = j < len0, p1 = j < len1, p2 = j < len2;
-  const long eoff = row * D + cc * 8, boff = base * D + cc * 8;
-  const Raw3 rk = load_raw3<false, long>(K0, K1, K2, boff, eoff, p0, p1, p2);
-  const Raw3 rv = load_raw3<false, long>(V0, V1, V2, boff, eoff, p0, p1, p2);
-  const float g0 = G[row * 3 + 0], g1 = G[row * 3 + 1], g2 = G[row * 3 + 2];
-  float kf[8], vf[8];
-  fuse8(rk, g0, g1, g2, kf);
-  fuse8(rv, g0, g1, g2, vf);
-  *reinterpret_cast<uint4*>(Kf + eoff) = pack8(kf);
-  *reinterpret_cast<uint4*>(Vf + eoff) = pack8(vf);
+  constexpr int CPR = D / 8, RPW = 256 / CPR;  // rows per workgroup and pass
+  const int cc = threadIdx.x % CPR;
+  const long row0 = (long)blockIdx.x * (RPW * PF_U) + threadIdx.x / CPR;
+  const bf16* Kp[3] = {K0, K1, K2};
+  const bf16* Vp[3] = {V0, V1, V2};
+  const int len[3] = {len0, len1, len2};
+  // all raw chunks (read once: streaming loads) and gates of the thread's slots first; an
+  // absent entry reads row 0 of its (b,h) block, which always exists, and is replaced by zeros
+  uint4 rk[PF_U][3], rv[PF_U][3];
+  float g[PF_U][3];
+#pragma unroll
+  for (int u = 0; u < PF_U; ++u) {
+    const long row = row0 + (long)u * RPW;
+    const long rc = row < rows ? row : rows - 1;
+    const int j = (int)(rc % S);
+#pragma unroll
+    for (int l = 0; l < 3; ++l) {
+      const long o = (j < len[l] ? rc : rc - j) * D + cc * 8;
+      rk[u][l] = load16_stream(Kp[l] + o);
+      rv[u][l] = load16_stream(Vp[l] + o);
+      g[u][l] = G[rc * 3 + l];
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < PF_U; ++u) {
+    const long row = row0 + (long)u * RPW;
+    if (row >= rows) continue;
+    const int j = (int)(row % S);
+    const uint4 z = make_uint4(0, 0, 0, 0);
+    Raw3 k3, v3;
+    k3.a = j < len0 ? rk[u][0] : z;  v3.a = j < len0 ? rv[u][0] : z;
+    k3.b = j < len1 ? rk[u][1] : z;  v3.b = j < len1 ? rv[u][1] : z;
+    k3.c = j < len2 ? rk[u][2] : z;  v3.c = j < len2 ? rv[u][2] : z;
+    float kf[8], vf[8];
+    fuse8(k3, g[u][0], g[u][1], g[u][2], kf);
+    fuse8(v3, g[u][0], g[u][1], g[u][2], vf);
+    const long eoff = row * D + cc * 8;
+    *reinterpret_cast<uint4*>(Kf + eoff) = pack8(kf);
+    *reinterpret_cast<uint4*>(Vf + eoff) = pack8(vf);
+  }
 }
 
 }  // namespace
@@ -58,8 +83,8 @@ hipError_t launch_prefuse(const PrefuseArgs& a, hipStream_t st) {
     Vp[l] = has ? a.V[l] : anyV;
     len[l] = has ? a.len[l] : 0;
   }
-  const int cpr = a.d / 8;
-  const unsigned grid = (unsigned)((rows * cpr + 255) / 256);
+  const int rows_per_wg = 256 / (a.d / 8) * PF_U;
+  const unsigned grid = (unsigned)((rows + rows_per_wg - 1) / rows_per_wg);
 #define MKA_PREFUSE(D)                                                                          \
   hipLaunchKernelGGL((prefuse_kernel<D>), dim3(grid), dim3(256), 0, st, (const bf16*)Kp[0],     \
                      (const bf16*)Kp[1], (const bf16*)Kp[2], (const bf16*)Vp[0],                \
