@@ -153,3 +153,45 @@ def test_ceiling_helpers_reject_bad_arguments_on_the_host(m):
     assert L.mka_ceiling_read(None, 1 << 20, None, None) == 2
     assert L.mka_ceiling_read(ctypes.c_void_p(4096), 64, None, None) == 2   # too small
     assert L.mka_ceiling_read(ctypes.c_void_p(4100), 1 << 20, None, None) == 4  # misaligned
+
+
+def test_widened_entry_points_reject_bad_arguments(m):
+    """Host-side validation of the entry points beyond the four core ones (no GPU work: every
+    call returns before a launch)."""
+    from paper_2603_20586_amd.binding import MkaPagedShape, _P3
+
+    L = m.lib()
+    p3 = _P3(FAKE, FAKE, FAKE)
+    s = _shape(m, d=128)
+    # full MKA: gates and workspace are required, f32 has no kernel, causal needs len >= Tq
+    full = lambda shp, g, ws, wsb: L.mka_full_attn_fwd(  # noqa: E731
+        FAKE, ctypes.byref(p3), ctypes.byref(p3), g, FAKE, ctypes.byref(shp), ws, wsb, None)
+    assert full(s, None, FAKE, 1 << 30) == 1
+    assert full(s, FAKE, None, 0) == 5
+    assert full(s, FAKE, FAKE, 16) == 5
+    assert full(_shape(m, d=128, dtype=0), FAKE, FAKE, 1 << 30) == 6
+    assert full(_shape(m, d=128, len=(8, 16, 16)), FAKE, FAKE, 1 << 30) == 2
+    assert m.mka_workspace_bytes(5, s) == 3 * 1 * 2 * 16 * 128 * 2
+    # prefix mean
+    pm = lambda shp, ws, wsb: L.mka_prefix_mean(FAKE, FAKE, ctypes.byref(shp), ws, wsb, None)  # noqa: E731
+    assert pm(s, None, 0) == 5
+    assert pm(_shape(m, d=96), FAKE, 1 << 20) == 6
+    assert L.mka_prefix_mean(None, FAKE, ctypes.byref(s), FAKE, 1 << 20, None) == 1
+    assert m.mka_workspace_bytes(6, s) > 0
+    # paged decode: page size a power of two >= 16, pool and table sizes positive
+    ps = MkaPagedShape()
+    ps.B, ps.H, ps.d, ps.page_size, ps.n_pages, ps.max_pages, ps.n_splits, ps.scale = 2, 2, 128, 64, 8, 4, 0, 0.1
+    paged = lambda shp, ws, wsb: L.mka_paged_fused_decode(  # noqa: E731
+        FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, ctypes.byref(shp), ws, wsb, None)
+    assert paged(ps, None, 0) == 5
+    ps.page_size = 48
+    assert paged(ps, FAKE, 1 << 30) == 2
+    ps.page_size = 8
+    assert paged(ps, FAKE, 1 << 30) == 2
+    ps.page_size, ps.n_pages = 64, 0
+    assert paged(ps, FAKE, 1 << 30) == 2
+    ps.n_pages, ps.d = 8, 96
+    assert paged(ps, FAKE, 1 << 30) == 6
+    ps.d = 128
+    assert L.mka_paged_fused_decode(FAKE, FAKE, FAKE, None, FAKE, FAKE, None, ctypes.byref(ps),
+                                    FAKE, 1 << 30, None) == 1
