@@ -116,7 +116,8 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
     bf16* __restrict__ dK1, bf16* __restrict__ dK2, bf16* __restrict__ dV0, bf16* __restrict__ dV1,
     bf16* __restrict__ dV2, bf16* __restrict__ Kf_out, bf16* __restrict__ Vf_out,
     float* __restrict__ dgate, int Tq, int S,
-    int len0, int len1, int len2, int causal, float c, float tau, int n_kvtiles, int BH) {
+    int len0, int len1, int len2, int causal, float c, float tau, int n_kvtiles, int BH,
+    int cls) {
   using L = BwdSmem<D>;
   constexpr int BR = L::BR, RSTR = L::RSTR;
   constexpr int CPR = D / 8, KK = D / 16, DB = D / 32, NT = 512;
@@ -136,9 +137,15 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   // the head's Q / dO tiles and dQ accumulator rows in that XCD's L2.  Tile 0 sees every query
   // row, so ascending tile order is heaviest first.
   const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3);
-  const int jt = slot % n_kvtiles;
-  const long bh = (long)(slot / n_kvtiles) * 8 + xcd;
-  if (bh >= BH) return;
+  // Order inside an XCD: classes of `cls` consecutive tiles; class by class, and inside a class
+  // head by head.  cls = n_kvtiles is head after head (the tiles of a head run together and
+  // share its Q / dO stream in L2); a small class puts the heavy tiles of ALL heads first, so
+  // that the work left for the end of the launch is light and the compute units finish together.
+  const int hpx = (BH + 7) / 8, per_class = hpx * cls;
+  const int r = slot % per_class;
+  const int jt = (slot / per_class) * cls + r % cls;
+  const long bh = (long)(r / cls) * 8 + xcd;
+  if (bh >= BH || jt >= n_kvtiles) return;
   const int J0 = jt * BCB;
   const int off = S - Tq;
   const long kvbase = bh * (long)S * D;
@@ -623,13 +630,24 @@ hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((bwd_main_kernel<D>), dim3((unsigned)((long)n_kvtiles * ((a.BH + 7) / 8) * 8)),
+  // Tile classes (see the kernel).  With a causal mask the weight of a tile falls with its index;
+  // on a grid of few workgroups per compute unit the heavy tiles of all heads go first (measured
+  // at B*H = 64, T = 2048: 11 % off the launch), on a large grid the tiles of a head stay
+  // together (the tail is short there and the shared Q / dO stream matters more).
+  const int hpx = (a.BH + 7) / 8;
+  int cls = n_kvtiles;
+  if (a.causal && (long)n_kvtiles * hpx * 8 <= 8 * 256) {
+    cls = 16 / hpx > 1 ? 16 / hpx : 1;
+    if (cls > n_kvtiles) cls = n_kvtiles;
+  }
+  const long n_classes = (n_kvtiles + cls - 1) / cls;
+  hipLaunchKernelGGL((bwd_main_kernel<D>), dim3((unsigned)(n_classes * cls * hpx * 8)),
                      dim3(512), smem, st, (const bf16*)a.dO, (const bf16*)a.Q,
                      (const bf16*)Kp[0], (const bf16*)Kp[1], (const bf16*)Kp[2],
                      (const bf16*)Vp[0], (const bf16*)Vp[1], (const bf16*)Vp[2], a.G, LSE2p, Dp, w.Tqp,
                      (bf16*)a.dK[0], (bf16*)a.dK[1], (bf16*)a.dK[2], (bf16*)a.dV[0],
                      (bf16*)a.dV[1], (bf16*)a.dV[2], Kf, Vf, dgate, a.Tq, a.S, a.len[0], a.len[1],
-                     a.len[2], a.causal, a.scale * kLog2e, a.scale, n_kvtiles, a.BH);
+                     a.len[2], a.causal, a.scale * kLog2e, a.scale, n_kvtiles, a.BH, cls);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
 

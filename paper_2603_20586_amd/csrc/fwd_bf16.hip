@@ -309,17 +309,10 @@ __device__ __forceinline__ void half_step(
   const uint4 pk0 = pack8(&p[0]), pk1 = pack8(&p[8]);
   const bf16x8 p0 = __builtin_bit_cast(bf16x8, pk0);
   const bf16x8 p1 = __builtin_bit_cast(bf16x8, pk1);
-  // row sum of the bf16-rounded P (what the PV product uses), two values per instruction
-  const bf16x2 ones = {(bf16)1.f, (bf16)1.f};
-  float psum = 0.f;
-  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.x), ones, psum, false);
-  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.y), ones, psum, false);
-  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.z), ones, psum, false);
-  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk0.w), ones, psum, false);
-  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.x), ones, psum, false);
-  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.y), ones, psum, false);
-  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.z), ones, psum, false);
-  psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk1.w), ones, psum, false);
+  // Row sum of P in f32, before the rounding to bf16.  Plain adds on purpose: v_dot2_f32_bf16
+  // cannot issue while an MFMA of either wave of the SIMD is in the matrix pipe.
+  const float psum = (((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]))) +
+                     (((p[8] + p[9]) + (p[10] + p[11])) + ((p[12] + p[13]) + (p[14] + p[15])));
   lsum = lsum * alpha + psum;
   __builtin_amdgcn_sched_barrier(0);
 
