@@ -91,10 +91,11 @@ struct BwdSmem {
   static constexpr int SBUF = BCB * BR;          // P^T tile: [slot][row], 64-byte rows, chunks rotated (bf16)
   static constexpr int OFF_P = NSLOT * SLOTB;    // bytes; two P^T tiles
   static constexpr int LOOP_END = OFF_P + 2 * SBUF * 2;
-  // set-up only: row-major Kf and Vf of the workgroup's 128 slots
-  static constexpr int OFF_KROW = 0;             // bf16 elements
-  static constexpr int OFF_VROW = BCB * RSTR;
-  static constexpr int SETUP_END = 2 * BCB * RSTR * 2;  // bytes
+  // set-up only: row-major Kf and Vf of the workgroup's 128 slots, behind the first three ring
+  // slots (whose tiles are requested before the set-up and land while it runs)
+  static constexpr int OFF_KROW = 3 * SLOTB / 2;  // bf16 elements
+  static constexpr int OFF_VROW = OFF_KROW + BCB * RSTR;
+  static constexpr int SETUP_END = 3 * SLOTB + 2 * BCB * RSTR * 2;  // bytes
   static constexpr int TOTAL = LOOP_END > SETUP_END ? LOOP_END : SETUP_END;  // bytes
 };
 
@@ -152,6 +153,58 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   const long qbase = bh * (long)Tq * D;
   const float* Gb = G + bh * (long)S * 3;
   const int jmine = J0 + 32 * sw + li;  // the slot this lane owns in S / dP / dVf^T / dKf^T
+
+  // first query tile that can see slot J0 (rows t with t + off >= J0)
+  int t_first = 0;
+  if (causal && J0 - off > 0) t_first = J0 - off;
+  const int n_qt = (Tq + BR - 1) / BR;
+  const int qt0 = t_first / BR;
+
+  // ---- staging: query tiles go from global memory straight into LDS (no registers hold data in
+  // flight), requested three iterations before their first use; every wave issues an equal
+  // share of a tile's load instructions (1 KiB each: lane i fills LDS row RPI q + i / CPR, chunk
+  // position i % CPR of instruction q, and picks the query row and chunk that belong there),
+  // wave 0 one more for the rows' LSE and D values.
+  constexpr int ROWB = D * 2, RPI = 64 / CPR;
+  constexpr int IPT = L::QB / 1024;  // load instructions per tensor and tile
+  constexpr int LPW = 2 * IPT / 8;   // per wave
+  const int n_tiles = n_qt - qt0;
+  const int uw = __builtin_amdgcn_readfirstlane(wave);
+  const char* Qb = reinterpret_cast<const char*>(Q + qbase);
+  const char* dOb = reinterpret_cast<const char*>(dO + qbase);
+  unsigned st_row[LPW], st_chunk[LPW];
+#pragma unroll
+  for (int e = 0; e < LPW; ++e) {
+    const int q = (8 * e + uw) % IPT;
+    const int r = RPI * q + lane / CPR;
+    st_row[e] = (unsigned)tile_row(r);
+    st_chunk[e] = 16u * (unsigned)((lane % CPR) ^ mx_swz<D>(r));
+  }
+  const float* ld_src = (lane < 32 ? LSE2p : Dp) + bh * (long)Tqp + (lane & 31);
+  const unsigned lds_base = (unsigned)(size_t)lds;
+  // tile k of this workgroup (past the last one: the last again, so that the counted waits stay
+  // exact) into ring slot `slot`; rows past the end repeat the last row (their LSE is +inf)
+  auto request = [&](int k, int slot) __attribute__((always_inline)) {
+    const int t0 = (qt0 + (k < n_tiles ? k : n_tiles - 1)) * BR;
+    const unsigned sb = lds_base + (unsigned)(slot * L::SLOTB);
+#pragma unroll
+    for (int e = 0; e < LPW; ++e) {
+      const int idx = 8 * e + uw, tensor = idx / IPT, q = idx % IPT;
+      const unsigned o = min((unsigned)t0 + st_row[e], (unsigned)(Tq - 1)) * (unsigned)ROWB + st_chunk[e];
+      mx_dma16(tensor ? dOb : Qb, o, sb + (unsigned)(tensor * L::QB + 1024 * q));
+    }
+    if (uw == 0) mx_dma4(ld_src + t0, sb + 2 * L::QB);
+  };
+  // before a barrier that publishes a tile: all but the two youngest tiles of this wave landed
+  auto wait_tile = [&]() __attribute__((always_inline)) {
+    if (uw == 0) mx_wait_loads<2 * (LPW + 1)>();
+    else mx_wait_loads<2 * LPW>();
+  };
+
+  // the first three query tiles fly while the set-up runs
+  request(0, 0);
+  request(1, 1);
+  request(2, 2);
 
   // ---- set-up: fuse the 128 slots once.  Item = (4 consecutive slots, 16-byte chunk).
   // [B*H,S,d] of the workspace has the layout of the K / V tensors: element offsets are shared.
@@ -219,53 +272,6 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
 
-  // first query tile that can see slot J0 (rows t with t + off >= J0)
-  int t_first = 0;
-  if (causal && J0 - off > 0) t_first = J0 - off;
-  const int n_qt = (Tq + BR - 1) / BR;
-  const int qt0 = t_first / BR;
-
-  // ---- staging: query tiles go from global memory straight into LDS (no registers hold data in
-  // flight), requested three iterations before their first use; every wave issues an equal
-  // share of a tile's load instructions (1 KiB each: lane i fills LDS row RPI q + i / CPR, chunk
-  // position i % CPR of instruction q, and picks the query row and chunk that belong there),
-  // wave 0 one more for the rows' LSE and D values.
-  constexpr int ROWB = D * 2, RPI = 64 / CPR;
-  constexpr int IPT = L::QB / 1024;  // load instructions per tensor and tile
-  constexpr int LPW = 2 * IPT / 8;   // per wave
-  const int n_tiles = n_qt - qt0;
-  const int uw = __builtin_amdgcn_readfirstlane(wave);
-  const char* Qb = reinterpret_cast<const char*>(Q + qbase);
-  const char* dOb = reinterpret_cast<const char*>(dO + qbase);
-  unsigned st_row[LPW], st_chunk[LPW];
-#pragma unroll
-  for (int e = 0; e < LPW; ++e) {
-    const int q = (8 * e + uw) % IPT;
-    const int r = RPI * q + lane / CPR;
-    st_row[e] = (unsigned)tile_row(r);
-    st_chunk[e] = 16u * (unsigned)((lane % CPR) ^ mx_swz<D>(r));
-  }
-  const float* ld_src = (lane < 32 ? LSE2p : Dp) + bh * (long)Tqp + (lane & 31);
-  const unsigned lds_base = (unsigned)(size_t)lds;
-  // tile k of this workgroup (past the last one: the last again, so that the counted waits stay
-  // exact) into ring slot `slot`; rows past the end repeat the last row (their LSE is +inf)
-  auto request = [&](int k, int slot) __attribute__((always_inline)) {
-    const int t0 = (qt0 + (k < n_tiles ? k : n_tiles - 1)) * BR;
-    const unsigned sb = lds_base + (unsigned)(slot * L::SLOTB);
-#pragma unroll
-    for (int e = 0; e < LPW; ++e) {
-      const int idx = 8 * e + uw, tensor = idx / IPT, q = idx % IPT;
-      const unsigned o = min((unsigned)t0 + st_row[e], (unsigned)(Tq - 1)) * (unsigned)ROWB + st_chunk[e];
-      mx_dma16(tensor ? dOb : Qb, o, sb + (unsigned)(tensor * L::QB + 1024 * q));
-    }
-    if (uw == 0) mx_dma4(ld_src + t0, sb + 2 * L::QB);
-  };
-  // before a barrier that publishes a tile: all but the two youngest tiles of this wave landed
-  auto wait_tile = [&]() __attribute__((always_inline)) {
-    if (uw == 0) mx_wait_loads<2 * (LPW + 1)>();
-    else mx_wait_loads<2 * LPW>();
-  };
-
   // lane constants of the LDS reads: A operand rows (slot li of a 32-row tile, head dims 8 g ..)
   // and transposed reads (k-step of 16 query rows, 32 head dims)
   const unsigned aq0 = mx_kfrag0<D>(swap23(li), g);
@@ -292,12 +298,8 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   //           dKf^T += Q^T dS
   //   role V: for tile it: S = Q Kf^T, P = exp2(c S - LSE), publishes P^T, dVf^T += dO^T P
   // so S is computed once, and every hand-over (P^T, requested tiles) crosses one barrier.
-  __syncthreads();  // the set-up buffers are dead
-  request(0, 0);
-  request(1, 1);
-  request(2, 2);
   wait_tile();
-  __syncthreads();  // tile 0 is complete
+  __syncthreads();  // tile 0 is complete; the set-up buffers are dead (the B operands are in registers)
 
   // chunk-rotated address of the lane's 16 bytes (8 query rows 16 h + 8 g ..) in a P^T tile
   const int Rl = 32 * sw + li;
