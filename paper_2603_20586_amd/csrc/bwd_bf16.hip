@@ -108,8 +108,10 @@ __device__ __forceinline__ int tile_row(int t) {
   return (t & 16) | ((t & 3) << 2) | ((t >> 2) & 3);
 }
 
+// One key tile (128 slots, index jt) of head bh: set-up, loop over the query tiles that see it,
+// epilogue.  Called by all 512 threads of the workgroup.
 template <int D>
-__global__ __launch_bounds__(512, 1) void bwd_main_kernel(
+__device__ __forceinline__ void bwd_main_tile(
     const bf16* __restrict__ dO, const bf16* __restrict__ Q, const bf16* __restrict__ K0,
     const bf16* __restrict__ K1, const bf16* __restrict__ K2, const bf16* __restrict__ V0,
     const bf16* __restrict__ V1, const bf16* __restrict__ V2, const float* __restrict__ G,
@@ -117,8 +119,7 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
     bf16* __restrict__ dK1, bf16* __restrict__ dK2, bf16* __restrict__ dV0, bf16* __restrict__ dV1,
     bf16* __restrict__ dV2, bf16* __restrict__ Kf_out, bf16* __restrict__ Vf_out,
     float* __restrict__ dgate, int Tq, int S,
-    int len0, int len1, int len2, int causal, float c, float tau, int n_kvtiles, int BH,
-    int cls) {
+    int len0, int len1, int len2, int causal, float c, float tau, int jt, long bh) {
   using L = BwdSmem<D>;
   constexpr int BR = L::BR, RSTR = L::RSTR;
   constexpr int CPR = D / 8, KK = D / 16, DB = D / 32, NT = 512;
@@ -134,19 +135,6 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
   const bool roleK = wave >= 4;
   const int sw = wave & 3;  // slot block of this wave
-  // all KV tiles of one (batch, head) run on ONE XCD (block index = 8 * slot + xcd): they share
-  // the head's Q / dO tiles and dQ accumulator rows in that XCD's L2.  Tile 0 sees every query
-  // row, so ascending tile order is heaviest first.
-  const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3);
-  // Order inside an XCD: classes of `cls` consecutive tiles; class by class, and inside a class
-  // head by head.  cls = n_kvtiles is head after head (the tiles of a head run together and
-  // share its Q / dO stream in L2); a small class puts the heavy tiles of ALL heads first, so
-  // that the work left for the end of the launch is light and the compute units finish together.
-  const int hpx = (BH + 7) / 8, per_class = hpx * cls;
-  const int r = slot % per_class;
-  const int jt = (slot / per_class) * cls + r % cls;
-  const long bh = (long)(r / cls) * 8 + xcd;
-  if (bh >= BH || jt >= n_kvtiles) return;
   const int J0 = jt * BCB;
   const int off = S - Tq;
   const long kvbase = bh * (long)S * D;
@@ -505,6 +493,38 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   }
 }
 
+template <int D>
+__global__ __launch_bounds__(512, 1) void bwd_main_kernel(
+    const bf16* __restrict__ dO, const bf16* __restrict__ Q, const bf16* __restrict__ K0,
+    const bf16* __restrict__ K1, const bf16* __restrict__ K2, const bf16* __restrict__ V0,
+    const bf16* __restrict__ V1, const bf16* __restrict__ V2, const float* __restrict__ G,
+    const float* __restrict__ LSE2p, const float* __restrict__ Dp, int Tqp, bf16* __restrict__ dK0,
+    bf16* __restrict__ dK1, bf16* __restrict__ dK2, bf16* __restrict__ dV0, bf16* __restrict__ dV1,
+    bf16* __restrict__ dV2, bf16* __restrict__ Kf_out, bf16* __restrict__ Vf_out,
+    float* __restrict__ dgate, int Tq, int S,
+    int len0, int len1, int len2, int causal, float c, float tau, int n_kvtiles, int BH,
+    int pair) {
+  // All KV tiles of one (batch, head) run on ONE XCD (block index = 8 * slot + xcd): they share
+  // the head's Q / dO tiles in that XCD's L2.  Tile 0 sees every query row, so ascending tile
+  // order is heaviest first.
+  // pair: a workgroup takes tile jt and then its mirror tile n_kvtiles-1-jt.  Under a causal mask
+  // the two see the same number of query tiles in total, so all workgroups weigh the same and
+  // the compute units finish together; and there are half as many workgroups to start.
+  const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3);
+  const int n_first = pair ? (n_kvtiles + 1) / 2 : n_kvtiles;
+  const int jt0 = slot % n_first, jt1 = n_kvtiles - 1 - jt0;
+  const long bh = (long)(slot / n_first) * 8 + xcd;
+  if (bh >= BH) return;
+  const int n_pass = (pair && jt1 != jt0) ? 2 : 1;
+#pragma unroll 1
+  for (int pass = 0; pass < n_pass; ++pass) {
+    if (pass) __syncthreads();  // the first tile's epilogue staging is dead
+    bwd_main_tile<D>(dO, Q, K0, K1, K2, V0, V1, V2, G, LSE2p, Dp, Tqp, dK0, dK1, dK2, dV0, dV1, dV2,
+                     Kf_out, Vf_out, dgate, Tq, S, len0, len1, len2, causal, c, tau,
+                     pass ? jt1 : jt0, bh);
+  }
+}
+
 // ------------------------------------------------------------------ router-gradient partials
 // Per-workgroup partial sums of Q^T dg and dg in a fixed order.
 template <int D>
@@ -632,24 +652,20 @@ hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  // Tile classes (see the kernel).  With a causal mask the weight of a tile falls with its index;
-  // on a grid of few workgroups per compute unit the heavy tiles of all heads go first (measured
-  // at B*H = 64, T = 2048: 11 % off the launch), on a large grid the tiles of a head stay
-  // together (the tail is short there and the shared Q / dO stream matters more).
+  // Work distribution (see the kernel): under a causal mask a workgroup takes a heavy key tile
+  // and its light mirror tile (measured at B*H = 64, T = 2048: 6 % off the backward pass against
+  // one tile per workgroup; persistent workgroups with a static share each were 10 % slower).
   const int hpx = (a.BH + 7) / 8;
-  int cls = n_kvtiles;
-  if (a.causal && (long)n_kvtiles * hpx * 8 <= 8 * 256) {
-    cls = 16 / hpx > 1 ? 16 / hpx : 1;
-    if (cls > n_kvtiles) cls = n_kvtiles;
-  }
-  const long n_classes = (n_kvtiles + cls - 1) / cls;
-  hipLaunchKernelGGL((bwd_main_kernel<D>), dim3((unsigned)(n_classes * cls * hpx * 8)),
+  const int pair = (a.causal && n_kvtiles > 1) ? 1 : 0;
+  const int n_first = pair ? (n_kvtiles + 1) / 2 : n_kvtiles;
+  const unsigned nwg = (unsigned)((long)n_first * hpx * 8);
+  hipLaunchKernelGGL((bwd_main_kernel<D>), dim3(nwg),
                      dim3(512), smem, st, (const bf16*)a.dO, (const bf16*)a.Q,
                      (const bf16*)Kp[0], (const bf16*)Kp[1], (const bf16*)Kp[2],
                      (const bf16*)Vp[0], (const bf16*)Vp[1], (const bf16*)Vp[2], a.G, LSE2p, Dp, w.Tqp,
                      (bf16*)a.dK[0], (bf16*)a.dK[1], (bf16*)a.dK[2], (bf16*)a.dV[0],
                      (bf16*)a.dV[1], (bf16*)a.dV[2], Kf, Vf, dgate, a.Tq, a.S, a.len[0], a.len[1],
-                     a.len[2], a.causal, a.scale * kLog2e, a.scale, n_kvtiles, a.BH, cls);
+                     a.len[2], a.causal, a.scale * kLog2e, a.scale, n_kvtiles, a.BH, pair);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
 
