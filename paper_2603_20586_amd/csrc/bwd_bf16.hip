@@ -132,7 +132,11 @@ __device__ __forceinline__ void bwd_main_tile(
   // dP -> dS -> dKf^T.  A wave so holds one
   // accumulator set and one B operand instead of two, which is what lets two waves share a SIMD
   // and hide each other's LDS / MFMA latency.
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
+  // (opaque: the lane constants derived from it are recomputed per call instead of being kept
+  // alive across the two tiles of a workgroup)
+  int tid_ = threadIdx.x;
+  asm volatile("" : "+v"(tid_));
+  const int tid = tid_, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
   const bool roleK = wave >= 4;
   const int sw = wave & 3;  // slot block of this wave
   const int J0 = jt * BCB;
@@ -515,13 +519,12 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   const int jt0 = slot % n_first, jt1 = n_kvtiles - 1 - jt0;
   const long bh = (long)(slot / n_first) * 8 + xcd;
   if (bh >= BH) return;
-  const int n_pass = (pair && jt1 != jt0) ? 2 : 1;
-#pragma unroll 1
-  for (int pass = 0; pass < n_pass; ++pass) {
-    if (pass) __syncthreads();  // the first tile's epilogue staging is dead
+  bwd_main_tile<D>(dO, Q, K0, K1, K2, V0, V1, V2, G, LSE2p, Dp, Tqp, dK0, dK1, dK2, dV0, dV1, dV2,
+                   Kf_out, Vf_out, dgate, Tq, S, len0, len1, len2, causal, c, tau, jt0, bh);
+  if (pair && jt1 != jt0) {
+    __syncthreads();  // the first tile's epilogue staging is dead
     bwd_main_tile<D>(dO, Q, K0, K1, K2, V0, V1, V2, G, LSE2p, Dp, Tqp, dK0, dK1, dK2, dV0, dV1, dV2,
-                     Kf_out, Vf_out, dgate, Tq, S, len0, len1, len2, causal, c, tau,
-                     pass ? jt1 : jt0, bh);
+                     Kf_out, Vf_out, dgate, Tq, S, len0, len1, len2, causal, c, tau, jt1, bh);
   }
 }
 

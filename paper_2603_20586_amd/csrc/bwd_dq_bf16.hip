@@ -126,35 +126,25 @@ __device__ __forceinline__ void dq_unit(F1&& mid1, F2&& mid2, bf16x8 (&fr)[D / 1
   }
 }
 
+// One tile of BR query rows (index qt) of head bh.  Called by all threads of the workgroup.
 template <int D>
-__global__ __launch_bounds__(DQ_NT, 1) void bwd_dq_kernel(
+__device__ __forceinline__ void bwd_dq_tile(
     const bf16* __restrict__ Q, const bf16* __restrict__ dO, const bf16* __restrict__ Kf,
     const bf16* __restrict__ Vf, const float* __restrict__ LSE2p, const float* __restrict__ Dp,
     const float* __restrict__ dgate, const float* __restrict__ W_r, bf16* __restrict__ dQ,
-    float tau, int Tq, int Tqp, int S, int causal, float c, int n_qtiles, int BH,
-    int interleave) {
+    float tau, int Tq, int Tqp, int S, int causal, float c, int qt, long bh) {
   using SM = DqSmem<D>;
   constexpr int BR = DQ_BR, BC = DQ_BC, ROWB = SM::ROWB;
   constexpr int KK = D / 16, DB = D / 32, CPR = D / 8, PF = KK / 2;
   extern __shared__ __attribute__((aligned(1024))) unsigned char dq_smem_raw[];
   char* smem = reinterpret_cast<char*>(dq_smem_raw);
 
-  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, li = lane & 31;
+  // (opaque: the lane constants derived from it are recomputed per call instead of being kept
+  // alive across the two tiles of a workgroup)
+  int tid_ = threadIdx.x;
+  asm volatile("" : "+v"(tid_));
+  const int tid = tid_, lane = tid & 63, g = lane >> 5, li = lane & 31;
   const int wave = tid >> 6;
-  // all query tiles of one (batch, head) on ONE XCD (block index = 8 * slot + xcd), heaviest
-  // tiles first; heads interleaved on small grids (shorter causal tail)
-  const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3);
-  int qt, hl;
-  if (interleave) {
-    const int hpx = (BH + 7) / 8;
-    qt = n_qtiles - 1 - slot / hpx;
-    hl = slot % hpx;
-  } else {
-    qt = n_qtiles - 1 - slot % n_qtiles;
-    hl = slot / n_qtiles;
-  }
-  const long bh = (long)hl * 8 + xcd;
-  if (bh >= BH) return;
   const int tw0 = qt * BR + wave * 32;  // first row of this wave
   const int tq = tw0 + li;              // this lane's row
 
@@ -324,10 +314,46 @@ __global__ __launch_bounds__(DQ_NT, 1) void bwd_dq_kernel(
 }
 
 template <int D>
+__global__ __launch_bounds__(DQ_NT, 1) void bwd_dq_kernel(
+    const bf16* __restrict__ Q, const bf16* __restrict__ dO, const bf16* __restrict__ Kf,
+    const bf16* __restrict__ Vf, const float* __restrict__ LSE2p, const float* __restrict__ Dp,
+    const float* __restrict__ dgate, const float* __restrict__ W_r, bf16* __restrict__ dQ,
+    float tau, int Tq, int Tqp, int S, int causal, float c, int n_qtiles, int BH,
+    int interleave, int pair) {
+  // all query tiles of one (batch, head) on ONE XCD (block index = 8 * slot + xcd), heaviest
+  // tiles first; heads interleaved on small grids (shorter causal tail).
+  // pair: a workgroup takes query tile qt and then its mirror tile n_qtiles-1-qt; under a causal
+  // mask the two see the same number of K/V tiles in total, so all workgroups weigh the same,
+  // and half as many are started.
+  const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3);
+  const int n_first = pair ? (n_qtiles + 1) / 2 : n_qtiles;
+  int qt0, hl;
+  if (interleave) {
+    const int hpx = (BH + 7) / 8;
+    qt0 = n_qtiles - 1 - slot / hpx;
+    hl = slot % hpx;
+  } else {
+    qt0 = n_qtiles - 1 - slot % n_first;
+    hl = slot / n_first;
+  }
+  const long bh = (long)hl * 8 + xcd;
+  if (bh >= BH) return;
+  const int qt1 = n_qtiles - 1 - qt0;
+  bwd_dq_tile<D>(Q, dO, Kf, Vf, LSE2p, Dp, dgate, W_r, dQ, tau, Tq, Tqp, S, causal, c, qt0, bh);
+  if (pair && qt1 != qt0) {
+    __syncthreads();  // the first tile's output staging is dead
+    bwd_dq_tile<D>(Q, dO, Kf, Vf, LSE2p, Dp, dgate, W_r, dQ, tau, Tq, Tqp, S, causal, c, qt1, bh);
+  }
+}
+
+template <int D>
 hipError_t launch_dq_t(const BwdDqArgs& a, hipStream_t st) {
   const int n_qtiles = (a.Tq + DQ_BR - 1) / DQ_BR;
-  const long nblocks = (long)n_qtiles * ((a.BH + 7) / 8) * 8;
-  const int interleave = nblocks <= 2 * 256 ? 1 : 0;
+  // under a causal mask a workgroup takes a heavy and a light query tile (see the kernel)
+  const int pair = (a.causal && n_qtiles > 1) ? 1 : 0;
+  const int n_first = pair ? (n_qtiles + 1) / 2 : n_qtiles;
+  const long nblocks = (long)n_first * ((a.BH + 7) / 8) * 8;
+  const int interleave = (!pair && nblocks <= 2 * 256) ? 1 : 0;
   const size_t smem = (size_t)DqSmem<D>::TOTAL;
   static bool attr_set = false;
   if (!attr_set) {
@@ -339,7 +365,7 @@ hipError_t launch_dq_t(const BwdDqArgs& a, hipStream_t st) {
   hipLaunchKernelGGL((bwd_dq_kernel<D>), dim3((unsigned)nblocks), dim3(DQ_NT), smem, st,
                      (const bf16*)a.Q, (const bf16*)a.dO, (const bf16*)a.Kf, (const bf16*)a.Vf,
                      a.LSE2p, a.Dp, a.dgate, a.W_r, (bf16*)a.dQ, a.scale, a.Tq, a.Tqp, a.S, a.causal, a.scale * kLog2e, n_qtiles, a.BH,
-                     interleave);
+                     interleave, pair);
   return hipGetLastError();
 }
 

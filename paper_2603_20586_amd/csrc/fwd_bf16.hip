@@ -417,37 +417,26 @@ __device__ __forceinline__ void run_tiles(bf16* smem, const bf16* __restrict__ P
   __syncthreads();  // every wave is done with the tile buffers (the epilogue reuses them)
 }
 
+// One tile of BR query rows (index qt) of head bh.  Called by all threads of the workgroup.
 template <int D>
-__global__ __launch_bounds__(FW_NW * 64, 1) void fwd_bf16_kernel(
+__device__ __forceinline__ void fwd_tile(
     const bf16* __restrict__ Q, const bf16* __restrict__ K0, const bf16* __restrict__ K1,
     const bf16* __restrict__ K2, const bf16* __restrict__ V0, const bf16* __restrict__ V1,
     const bf16* __restrict__ V2, const float* __restrict__ G, bf16* __restrict__ O,
     float* __restrict__ LSE, int Tq, int S, int len0, int len1, int len2, int causal, float c,
-    float tau, int n_qtiles, int BH, int interleave) {
+    float tau, int qt, long bh) {
   constexpr int BR = FW_NW * 32, BC = FW_BC;
   constexpr int KK = D / 16, DB = D / 32;
   extern __shared__ __attribute__((aligned(16))) unsigned char fw_smem_raw[];
   bf16* smem = reinterpret_cast<bf16*>(fw_smem_raw);
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
+  // (opaque: the lane constants derived from it are recomputed per call instead of being kept
+  // alive across the two tiles of a workgroup)
+  int tid_ = threadIdx.x;
+  asm volatile("" : "+v"(tid_));
+  const int tid = tid_, wave = tid >> 6, lane = tid & 63, g = lane >> 5, li = lane & 31;
   const bool grpV = wave >= 4;  // waves 4-7 fuse the V half, waves 0-3 the K half
   const int tg = tid & (FW_NG - 1);
-  // Workgroups are handed to the 8 XCDs round-robin by block index.  All query tiles of one
-  // (batch, head) are given to ONE XCD (block index = 8 * slot + xcd), so that the workgroups
-  // that stream the same K/V tiles share that XCD's L2; heavy (late) query tiles go first so
-  // that the causal tail is short.
-  const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3);
-  int qt, hl;
-  if (interleave) {  // small grids: heaviest tiles of ALL the XCD's heads first (shorter tail)
-    const int hpx = (BH + 7) / 8;
-    qt = n_qtiles - 1 - slot / hpx;
-    hl = slot % hpx;
-  } else {           // large grids: one head after the other (best L2 reuse of its K/V tiles)
-    qt = n_qtiles - 1 - slot % n_qtiles;
-    hl = slot / n_qtiles;
-  }
-  const long bh = (long)hl * 8 + xcd;
-  if (bh >= BH) return;  // the head count need not be a multiple of 8
   const int off = S - Tq;
   const int tw0 = qt * BR + wave * 32;  // first row of this wave
   const int tq = tw0 + li;              // this lane's row
@@ -522,14 +511,54 @@ __global__ __launch_bounds__(FW_NW * 64, 1) void fwd_bf16_kernel(
 }
 
 template <int D>
+__global__ __launch_bounds__(FW_NW * 64, 1) void fwd_bf16_kernel(
+    const bf16* __restrict__ Q, const bf16* __restrict__ K0, const bf16* __restrict__ K1,
+    const bf16* __restrict__ K2, const bf16* __restrict__ V0, const bf16* __restrict__ V1,
+    const bf16* __restrict__ V2, const float* __restrict__ G, bf16* __restrict__ O,
+    float* __restrict__ LSE, int Tq, int S, int len0, int len1, int len2, int causal, float c,
+    float tau, int n_qtiles, int BH, int interleave, int pair) {
+  // Workgroups are handed to the 8 XCDs round-robin by block index.  All query tiles of one
+  // (batch, head) are given to ONE XCD (block index = 8 * slot + xcd), so that the workgroups
+  // that stream the same K/V tiles share that XCD's L2; heavy (late) query tiles go first so
+  // that the causal tail is short.
+  // pair: a workgroup takes query tile qt and then its mirror tile n_qtiles-1-qt; under a causal
+  // mask the two see the same number of K/V tiles in total, so all workgroups weigh the same,
+  // and half as many are started.
+  const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3);
+  const int n_first = pair ? (n_qtiles + 1) / 2 : n_qtiles;
+  int qt0, hl;
+  if (interleave) {  // small grids: heaviest tiles of ALL the XCD's heads first (shorter tail)
+    const int hpx = (BH + 7) / 8;
+    qt0 = n_qtiles - 1 - slot / hpx;
+    hl = slot % hpx;
+  } else {           // large grids: one head after the other (best L2 reuse of its K/V tiles)
+    qt0 = n_qtiles - 1 - slot % n_first;
+    hl = slot / n_first;
+  }
+  const long bh = (long)hl * 8 + xcd;
+  if (bh >= BH) return;  // the head count need not be a multiple of 8
+  const int qt1 = n_qtiles - 1 - qt0;
+  fwd_tile<D>(Q, K0, K1, K2, V0, V1, V2, G, O, LSE, Tq, S, len0, len1, len2, causal, c, tau, qt0,
+              bh);
+  if (pair && qt1 != qt0) {
+    __syncthreads();  // the first tile's output staging is dead
+    fwd_tile<D>(Q, K0, K1, K2, V0, V1, V2, G, O, LSE, Tq, S, len0, len1, len2, causal, c, tau, qt1,
+                bh);
+  }
+}
+
+template <int D>
 static hipError_t launch_fwd_t(const FwdArgs& a, const void* const Kp[3], const void* const Vp[3],
                                hipStream_t st) {
   constexpr int BR = FW_NW * 32;
   const int n_qtiles = (a.Tq + BR - 1) / BR;
-  const long nblocks = (long)n_qtiles * ((a.BH + 7) / 8) * 8;
-  // at most 2 workgroups per compute unit (256 CUs): the causal tail dominates, interleave heads
-  // (beyond that the heads' K/V streams evict each other from the L2 and HBM reads triple)
-  const int interleave = nblocks <= 2 * 256 ? 1 : 0;
+  // under a causal mask a workgroup takes a heavy and a light query tile (see the kernel)
+  const int pair = (a.causal && n_qtiles > 1) ? 1 : 0;
+  const int n_first = pair ? (n_qtiles + 1) / 2 : n_qtiles;
+  const long nblocks = (long)n_first * ((a.BH + 7) / 8) * 8;
+  // unpaired and at most 2 workgroups per compute unit (256 CUs): the tail dominates, interleave
+  // heads (beyond that the heads' K/V streams evict each other from the L2 and HBM reads triple)
+  const int interleave = (!pair && nblocks <= 2 * 256) ? 1 : 0;
   const size_t smem = (size_t)FwdSmem<D>::TOTAL * sizeof(bf16);
   static bool attr_set = false;
   if (!attr_set) {
@@ -542,7 +571,7 @@ static hipError_t launch_fwd_t(const FwdArgs& a, const void* const Kp[3], const 
                      (const bf16*)a.Q, (const bf16*)Kp[0], (const bf16*)Kp[1], (const bf16*)Kp[2],
                      (const bf16*)Vp[0], (const bf16*)Vp[1], (const bf16*)Vp[2], a.G, (bf16*)a.O,
                      a.LSE, a.Tq, a.S, a.len[0], a.len[1], a.len[2], a.causal,
-                     a.scale * kLog2e, a.scale, n_qtiles, a.BH, interleave);
+                     a.scale * kLog2e, a.scale, n_qtiles, a.BH, interleave, pair);
   return hipGetLastError();
 }
 

@@ -216,13 +216,15 @@ __device__ __forceinline__ void mx_half_step(FA&& mid_a, FB&& mid_b, f32x16 (&s_
   }
 }
 
+// One tile of BR query rows (index qt) of head bh against the whole stream of K/V tiles.  Called
+// by all threads of the workgroup.
 template <int D, int R>
-__global__ __launch_bounds__(MixShape<R>::NT, 1) void mix_bf16_kernel(
+__device__ __forceinline__ void mix_tile(
     const bf16* __restrict__ Q, const bf16* __restrict__ K0, const bf16* __restrict__ K1,
     const bf16* __restrict__ K2, const bf16* __restrict__ V0, const bf16* __restrict__ V1,
     const bf16* __restrict__ V2, const float* __restrict__ G, bf16* __restrict__ O,
-    float* __restrict__ LSE, int Tq, int S0, int S1, int S2, int causal, float c, int n_qtiles,
-    int BH, int interleave) {
+    float* __restrict__ LSE, int Tq, int S0, int S1, int S2, int causal, float c, int qt,
+    long bh) {
   using SM = MixSmem<D>;
   constexpr int NW = MixShape<R>::NW;
   constexpr int BR = MX_BR, BC = MX_BC, ROWB = SM::ROWB;
@@ -230,22 +232,12 @@ __global__ __launch_bounds__(MixShape<R>::NT, 1) void mix_bf16_kernel(
   extern __shared__ __attribute__((aligned(1024))) unsigned char mx_smem_raw[];
   char* smem = reinterpret_cast<char*>(mx_smem_raw);
 
-  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, li = lane & 31;
+  // (opaque: the lane constants derived from it are recomputed per call instead of being kept
+  // alive across the two tiles of a workgroup)
+  int tid_ = threadIdx.x;
+  asm volatile("" : "+v"(tid_));
+  const int tid = tid_, lane = tid & 63, g = lane >> 5, li = lane & 31;
   const int wave = tid >> 6;  // left divergent on purpose: uniform mask branches cost registers
-  // all query tiles of one (batch, head) on ONE XCD (block index = 8 * slot + xcd), heaviest
-  // tiles first; heads interleaved on small grids (shorter causal tail)
-  const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3);
-  int qt, hl;
-  if (interleave) {
-    const int hpx = (BH + 7) / 8;
-    qt = n_qtiles - 1 - slot / hpx;
-    hl = slot % hpx;
-  } else {
-    qt = n_qtiles - 1 - slot % n_qtiles;
-    hl = slot / n_qtiles;
-  }
-  const long bh = (long)hl * 8 + xcd;
-  if (bh >= BH) return;
   const int tw0 = qt * BR + wave * (32 * R);  // first row of this wave
   // row block rb of the wave: rows tw0 + 32 rb ..; this lane's row there is tw0 + 32 rb + li
 
@@ -481,11 +473,48 @@ __global__ __launch_bounds__(MixShape<R>::NT, 1) void mix_bf16_kernel(
 }
 
 template <int D, int R>
+__global__ __launch_bounds__(MixShape<R>::NT, 1) void mix_bf16_kernel(
+    const bf16* __restrict__ Q, const bf16* __restrict__ K0, const bf16* __restrict__ K1,
+    const bf16* __restrict__ K2, const bf16* __restrict__ V0, const bf16* __restrict__ V1,
+    const bf16* __restrict__ V2, const float* __restrict__ G, bf16* __restrict__ O,
+    float* __restrict__ LSE, int Tq, int S0, int S1, int S2, int causal, float c, int n_qtiles,
+    int BH, int interleave, int pair) {
+  // all query tiles of one (batch, head) on ONE XCD (block index = 8 * slot + xcd), heaviest
+  // tiles first; heads interleaved on small grids (shorter causal tail).
+  // pair: a workgroup takes query tile qt and then its mirror tile n_qtiles-1-qt; under a causal
+  // mask the two see the same number of K/V tiles in total, so all workgroups weigh the same,
+  // and half as many are started.
+  const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3);
+  const int n_first = pair ? (n_qtiles + 1) / 2 : n_qtiles;
+  int qt0, hl;
+  if (interleave) {
+    const int hpx = (BH + 7) / 8;
+    qt0 = n_qtiles - 1 - slot / hpx;
+    hl = slot % hpx;
+  } else {
+    qt0 = n_qtiles - 1 - slot % n_first;
+    hl = slot / n_first;
+  }
+  const long bh = (long)hl * 8 + xcd;
+  if (bh >= BH || qt0 < n_qtiles - n_first) return;
+  const int qt1 = n_qtiles - 1 - qt0;
+  mix_tile<D, R>(Q, K0, K1, K2, V0, V1, V2, G, O, LSE, Tq, S0, S1, S2, causal, c, qt0, bh);
+  if (pair && qt1 != qt0) {
+    __syncthreads();  // the first tile's output staging is dead
+    mix_tile<D, R>(Q, K0, K1, K2, V0, V1, V2, G, O, LSE, Tq, S0, S1, S2, causal, c, qt1, bh);
+  }
+}
+
+template <int D, int R>
 hipError_t launch_mix_t(const MixArgs& a, hipStream_t st) {
   constexpr int BR = MX_BR;
   const int n_qtiles = (a.Tq + BR - 1) / BR;
-  const long nblocks = (long)n_qtiles * ((a.BH + 7) / 8) * 8;
-  const int interleave = nblocks <= 2 * 256 ? 1 : 0;
+  // under a causal mask a workgroup takes a heavy and a light query tile (see the kernel;
+  // measured at T = 4096, B*H = 128: 10 % off the launch)
+  const int pair = (a.causal && n_qtiles > 1) ? 1 : 0;
+  const int n_first = pair ? (n_qtiles + 1) / 2 : n_qtiles;
+  const long nblocks = (long)n_first * ((a.BH + 7) / 8) * 8;
+  const int interleave = (!pair && nblocks <= 2 * 256) ? 1 : 0;
   const size_t smem = (size_t)MixSmem<D>::TOTAL;
   static bool attr_set = false;
   if (!attr_set) {
@@ -512,7 +541,7 @@ hipError_t launch_mix_t(const MixArgs& a, hipStream_t st) {
                      (const bf16*)a.Q, (const bf16*)Kp[0], (const bf16*)Kp[1], (const bf16*)Kp[2],
                      (const bf16*)Vp[0], (const bf16*)Vp[1], (const bf16*)Vp[2], a.G, (bf16*)a.O,
                      a.LSE, a.Tq, Sp[0], Sp[1], Sp[2], a.causal, a.scale * kLog2e, n_qtiles, a.BH,
-                     interleave);
+                     interleave, pair);
   return hipGetLastError();
 }
 
