@@ -98,13 +98,13 @@ def pmc(src, dst, cmd):
 
 # roofline key of bench.py -> [(kernel, workgroups of its launch at that workload), ...]: the
 # kernels that carry the line's algorithmic work; their traffic is summed
-TRAFFIC_KEYS = {
-    "C2_fwd": [("mka::fwd_bf16_kernel<128>", 512)],       # 64 heads x 8 query tiles
-    "C3_fwd_folded": [("mka::fwd_bf16_kernel<128>", 1024)],  # 32 heads x 32 query tiles
-    "C2_bwd": [("mka::bwd_main_kernel<128>", 1024),       # 64 heads x 16 KV tiles
-               ("mka::bwd_dq_kernel<128>", 512)],         # 64 heads x 8 query tiles
-    "C5_bwd": [("mka::bwd_main_kernel<128>", 4096),       # 128 heads x 32 KV tiles
-               ("mka::bwd_dq_kernel<128>", 2048)],        # 128 heads x 16 query tiles
+TRAFFIC_KEYS = {   # causal launches: one workgroup per PAIR of tiles
+    "C2_fwd": [("mka::fwd_bf16_kernel<128>", 256)],       # 64 heads x 8/2 query tiles
+    "C3_fwd_folded": [("mka::fwd_bf16_kernel<128>", 512)],   # 32 heads x 32/2 query tiles
+    "C2_bwd": [("mka::bwd_main_kernel<128>", 512),        # 64 heads x 16/2 KV tiles
+               ("mka::bwd_dq_kernel<128>", 256)],         # 64 heads x 8/2 query tiles
+    "C5_bwd": [("mka::bwd_main_kernel<128>", 2048),       # 128 heads x 32/2 KV tiles
+               ("mka::bwd_dq_kernel<128>", 1024)],        # 128 heads x 16/2 query tiles
     "C4_decode": [("mka::decode_split_kernel<bf32,16,128>", 2048)],  # 4 splits x 512 heads
 }
 
