@@ -52,6 +52,7 @@ def _check(mka, oracle, Q, K, V, G, causal, scale):
     (200, (260, 70, 1), False),       # non-causal, a one-slot memory
     (257, (257, None, 300), True),    # a memory absent
     (64, (64, None, None), True),     # one memory, one tile
+    (520, (520, 600, None), True),    # three query tiles: a heavy / light pair and the middle one
     (1, (1, 1, 1), True), (1, (70, 3, 129), False)])
 def test_mixture_shapes(mka, oracle, d, Tq, S3, causal):
     announce(f"mixture d={d} Tq={Tq} S={S3} causal={causal}")

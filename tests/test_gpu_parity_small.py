@@ -160,6 +160,7 @@ def test_fwd_f32_shapes(mka, oracle, d, Tq, S, causal, len3):
     (257, 257, True, [257, 100, 0]),  # absent levels
     (150, 150, True, None),      # three kv tiles: every stage of the tile pipeline's ramp-up
     (40, 250, True, [250, 250, 130]),  # a level that ends in the middle of a tile
+    (520, 520, True, None),      # three q tiles: a heavy / light pair and the middle tile alone
     (1, 1, True, None), (1, 70, True, None)])
 @pytest.mark.parametrize("materialise", [False, True])
 def test_fwd_bf16_shapes(mka, oracle, d, Tq, S, causal, len3, materialise):
@@ -312,6 +313,7 @@ def _check_bwd(mka, oracle, inp, S, len3, causal, Gprev=None, use_router=True):
     (150, 190, False, None),         # non-causal
     (257, 257, True, [257, 100, 0]),  # absent levels: zero gradients there
     (32, 32, True, None), (96, 96, True, None), (97, 161, True, None),  # 1, 3, 4 query tiles
+    (520, 520, True, None),          # 5 kv tiles, 3 dQ tiles: pairs plus a middle tile alone
     (1, 1, True, None), (64, 128, True, None)])
 def test_bwd_bf16_shapes(mka, oracle, d, Tq, S, causal, len3):
     announce(f"bwd bf16 d={d} Tq={Tq} S={S} causal={causal} len={len3}")
