@@ -50,7 +50,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not provided "
-              "(every (batch, head) is independent, see DESIGN.md on sharding)", file=sys.stderr)
+              "(every (batch, head) is independent: the path would shard over batch x heads)", file=sys.stderr)
         sys.exit(2)
 
     import torch
