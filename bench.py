@@ -302,6 +302,25 @@ def main():
         rooflines["C4_decode"] = {"kernel": "decode_split_kernel (+append/combine in the events)",
                                   "bound": "hbm", "achieved": gbps, "peak": PEAK_HBM_GBPS,
                                   "unit": "GB/s", "frac": gbps / PEAK_HBM_GBPS, "traffic": None}
+        # the same caches with hard top-1 gates (one level per slot): the kernel loads only the
+        # selected level's rows, a third of the K / V bytes
+        sel = torch.randint(0, 3, (B4, H4, S0), device=dev)
+        cc["Gc"].zero_()
+        cc["Gc"][:, :, :S0] = torch.nn.functional.one_hot(sel, 3).to(torch.float32)
+        del sel
+
+        def run64_top1():
+            ln4[:] = [S0, S0, S0]
+            for _ in range(nst):
+                mka.mka_fused_attn_decode(q4, [k4, None, None], [v4, None, None], cc["Kc"],
+                                          cc["Vc"], cc["Gc"], ln4, cc["W_r"], cc["b_r"],
+                                          scale=cc["scale"], workspace=ws4, O=O4, want_lse=False,
+                                          want_idx=False, routing=3)
+
+        ms4h = time_region(run64_top1, 2, 1) / nst
+        bytes4h = 2 * B4 * H4 * s_avg * d * 2 + 12 * B4 * H4 * s_avg
+        workloads["C4_decode_top1_routing"] = {"ms_per_step": ms4h, "gbps": bytes4h / ms4h / 1e6,
+                                               "vs_soft_routing": ms4 / ms4h}
         del cc, ws4
         torch.cuda.empty_cache()
         # the same decode shape over the fused KV cache in pages (one K and one V stream: a third

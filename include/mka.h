@@ -85,6 +85,7 @@ typedef struct {
   int32_t dtype;    /* mka_dtype of q, k_new, v_new, caches, O                        */
   int32_t n_splits; /* split-K factor along the slots; 0 = let the library choose     */
   float scale;      /* tau                                                            */
+  int32_t routing;  /* mka_routing of the new slot's gate (0 = MKA_ROUTE_SOFT)         */
 } mka_decode_shape;
 
 /* Bytes of device scratch the given operation needs (0 if none, and 0 for an
@@ -166,7 +167,12 @@ mka_status mka_fused_attn_fwd(const void* Q, const void* const K[3], const void*
  *   len      in/out  HOST array of 3: valid slots per level before / after the call
  *   W_r,b_r  in      router (W_r required)
  *   O        out     [B,H,1,d];  LSE out [B,H] f32 or NULL;  idx_out out [B,H] int32 or NULL
- * At least one level must be appended. */
+ * At least one level must be appended.
+ * shape->routing selects how the new slot's gate is formed from its logits (paper: section
+ * "Routing Mechanism Ablation"; see mka_route_variant; an unknown value gives
+ * MKA_ERR_UNSUPPORTED).  With hard routing (MKA_ROUTE_TOP2, MKA_ROUTE_TOP1) the attention does
+ * not load the K / V rows of a level whose cached gate is exactly zero - they cannot contribute
+ * - so a cache written with top-1 gates is read at a third of the bytes. */
 mka_status mka_fused_attn_decode(const void* q, const void* const k_new[3],
                                  const void* const v_new[3], void* const Kc[3], void* const Vc[3],
                                  float* Gc, int32_t len[3], const float* W_r, const float* b_r,

@@ -271,6 +271,39 @@ def decode(q, k_new, v_new, Kc, Vc, Gc, len3, W_r, b_r=None, tau=1.0):
     return O, LSE, idx
 
 
+def decode_variant(q, k_new, v_new, Kc, Vc, Gc, len3, W_r, b_r=None, mode=ROUTE_SOFT, tau=1.0):
+    """One decode step whose new slot is gated by a routing variant (paper: section "Routing
+    Mechanism Ablation"); same in-place contract as `decode`.  Written out of the pinned pieces:
+    append the new entries at slot j_new = max(len), gate of the new slot = route_variant on q,
+    then the route-fused forward (Alg. 2 steps 6-9) of the one query row over slots 0..j_new
+    (bottom-right causal mask: the row sees every slot, itself included)."""
+    q = f64(q)
+    B, H, _, d = q.shape
+    j_new = int(max(len3))
+    for l in range(3):
+        if k_new[l] is not None:
+            if len3[l] != j_new or j_new >= Kc[l].shape[2]:
+                raise ValueError("inconsistent append or cache full")
+            Kc[l][:, :, j_new] = f64(k_new[l])[:, :, 0]
+            Vc[l][:, :, j_new] = f64(v_new[l])[:, :, 0]
+            len3[l] = j_new + 1
+    S = j_new + 1
+    g_new, idx = route_variant(q, W_r, b_r, mode)     # [B,H,1,3], [B,H,1]
+    Gc[:, :, j_new] = g_new[:, :, 0]
+    K = [None if a is None else np.ascontiguousarray(a[:, :, :S]) for a in Kc]
+    V = [None if a is None else np.ascontiguousarray(a[:, :, :S]) for a in Vc]
+    # a level shorter than S contributes nothing beyond its length (the caches may hold anything there)
+    for l in range(3):
+        if K[l] is not None:
+            K[l][:, :, len3[l]:] = 0.0
+            V[l][:, :, len3[l]:] = 0.0
+    ref = next(a for a in K if a is not None)
+    K = [np.zeros_like(ref) if a is None else a for a in K]
+    V = [np.zeros_like(ref) if a is None else a for a in V]
+    O, LSE = fwd(q, K, V, np.ascontiguousarray(Gc[:, :, :S]), len3=list(len3), causal=True, tau=tau)
+    return O, LSE, idx[:, :, 0]
+
+
 def bwd(dO, Q, K, V, G, W_r, len3=None, causal=True, tau=1.0, want_dG=False):
     """Gradients of sum(dO*O).  Returns dict with dQ, dK (triple), dV (triple), dW_r, db_r[, dG]."""
     dO, Q, G, W_r = f64(dO), f64(Q), f64(G), f64(W_r)

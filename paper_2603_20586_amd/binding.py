@@ -34,7 +34,8 @@ class MkaPagedShape(ctypes.Structure):
 
 class MkaDecodeShape(ctypes.Structure):
     _fields_ = [("B", c_int32), ("H", c_int32), ("d", c_int32), ("cap", c_int32 * 3),
-                ("capG", c_int32), ("dtype", c_int32), ("n_splits", c_int32), ("scale", c_float)]
+                ("capG", c_int32), ("dtype", c_int32), ("n_splits", c_int32), ("scale", c_float),
+                ("routing", c_int32)]
 
 
 _P3 = c_void_p * 3
@@ -235,9 +236,10 @@ def mka_fused_attn_fwd(Q, K, V, W_r=None, b_r=None, G=None, len3=None, causal=Tr
 
 def mka_fused_attn_decode(q, k_new, v_new, Kc, Vc, Gc, len3, W_r, b_r=None, scale=1.0,
                           n_splits=0, workspace=None, O=None, LSE=None, idx=None, want_lse=True,
-                          want_idx=True):
+                          want_idx=True, routing=0):
     """One decode step; caches and `len3` (a python list of 3 ints) are updated in place.
-    Returns (O [B,H,1,d], LSE [B,H] or None, idx [B,H] or None)."""
+    `routing`: MKA_ROUTE_* of the new slot's gate (hard modes read only the levels whose cached
+    gate is not zero).  Returns (O [B,H,1,d], LSE [B,H] or None, idx [B,H] or None)."""
     _dev_check(q, W_r, b_r, Gc, *k_new, *v_new, *Kc, *Vc)
     B, H, _, d = q.shape
     s = MkaDecodeShape()
@@ -248,6 +250,7 @@ def mka_fused_attn_decode(q, k_new, v_new, Kc, Vc, Gc, len3, W_r, b_r=None, scal
     s.dtype = _dtype_code(q)
     s.n_splits = int(n_splits)
     s.scale = float(scale)
+    s.routing = int(routing)
     if workspace is None:
         qs = MkaShape()
         qs.B, qs.H, qs.d, qs.S, qs.Tq, qs.dtype = B, H, d, s.capG, 1, s.dtype

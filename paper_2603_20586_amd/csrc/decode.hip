@@ -64,7 +64,7 @@ __global__ __launch_bounds__(64) void decode_append_kernel(
     const T* __restrict__ vn2, T* __restrict__ Kc0, T* __restrict__ Kc1, T* __restrict__ Kc2,
     T* __restrict__ Vc0, T* __restrict__ Vc1, T* __restrict__ Vc2, float* __restrict__ Gc,
     const float* __restrict__ W_r, const float* __restrict__ b_r, int32_t* __restrict__ idx,
-    int cap0, int cap1, int cap2, int capG, int j_new) {
+    int cap0, int cap1, int cap2, int capG, int j_new, int routing) {
   const long bh = blockIdx.x;
   const int lane = threadIdx.x;
   __shared__ double sg[3];
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(64) void decode_append_kernel(
   __syncthreads();
   if (lane == 0) {
     float lam[3];
-    const int best = gates_from_logits(sg[0], sg[1], sg[2], lam);
+    const int best = gates_variant(sg[0], sg[1], sg[2], routing, lam);
     float* out = Gc + (bh * capG + j_new) * 3;
     out[0] = lam[0];
     out[1] = lam[1];
@@ -101,7 +101,11 @@ __global__ __launch_bounds__(64) void decode_append_kernel(
 }
 
 // partial layout per (bh, split): acc[0..D-1], m (log2 units), z
-template <typename T, int D, int U>
+// SKIP (hard routing, section "Routing Mechanism Ablation"): a level whose cached gate is exactly
+// zero cannot contribute to the slot, so its K / V rows are not loaded (the load is predicated
+// per lane group: with top-1 gates a third of the bytes is read).  The gates of a trip are then
+// needed before its row loads are issued: they are fetched one trip ahead.
+template <typename T, int D, int U, bool SKIP>
 __global__ __launch_bounds__(256) void decode_split_kernel(
     const T* __restrict__ q, const T* __restrict__ K0, const T* __restrict__ K1,
     const T* __restrict__ K2, const T* __restrict__ V0, const T* __restrict__ V1,
@@ -152,11 +156,48 @@ __global__ __launch_bounds__(256) void decode_split_kernel(
   // instead and its bits are replaced by zero (never multiplied by a zero gate, so stale NaN /
   // Inf bits in unused cache rows cannot leak).  FULL = every slot of the trip exists at every
   // level: no predicates at all.
+  // gates of the trip that starts at `base` (a slot past the end of the slice reads row 0)
+  float gpre[U][3];
+  auto load_gates = [&](int base) __attribute__((always_inline)) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int j = base + u * STEP + wave * SPI + sub;
+      const char* gj = gp + (j < j_hi ? (unsigned)j * 12u : 0u);
+      gpre[u][0] = *reinterpret_cast<const float*>(gj);
+      gpre[u][1] = *reinterpret_cast<const float*>(gj + 4);
+      gpre[u][2] = *reinterpret_cast<const float*>(gj + 8);
+    }
+  };
+  if (SKIP) load_gates(j_lo);
   auto trip = [&](int base, auto full_c) __attribute__((always_inline)) {
     constexpr bool FULL = decltype(full_c)::value;
     uint4 rk[U][3], rv[U][3];
     float g[U][3];
     bool ok[U];
+    if (SKIP) {
+      const uint4 zero = make_uint4(0, 0, 0, 0);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int j = base + u * STEP + wave * SPI + sub;
+        ok[u] = FULL || j < j_hi;
+        const unsigned rowb = (unsigned)j * (unsigned)(D * sizeof(T));
+        const int lens[3] = {len0, len1, len2};
+        const char* kb[3] = {k0, k1, k2};
+        const char* vb[3] = {v0, v1, v2};
+#pragma unroll
+        for (int l = 0; l < 3; ++l) {
+          const bool present = FULL || (ok[u] && j < lens[l]);
+          g[u][l] = present ? gpre[u][l] : 0.f;
+          rk[u][l] = zero;
+          rv[u][l] = zero;
+          if (g[u][l] != 0.f) {  // only these lanes issue the loads
+            rk[u][l] = load16_stream(kb[l] + rowb);
+            rv[u][l] = load16_stream(vb[l] + rowb);
+          }
+        }
+      }
+      load_gates(base + STEP * U);  // for the next trip
+    } else {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int j = base + u * STEP + wave * SPI + sub;
@@ -180,6 +221,7 @@ __global__ __launch_bounds__(256) void decode_split_kernel(
         if (!p1) { rk[u][1] = zero; rv[u][1] = zero; g[u][1] = 0.f; }
         if (!p2) { rk[u][2] = zero; rv[u][2] = zero; g[u][2] = 0.f; }
       }
+    }
     }
     float s[U];
 #pragma unroll
@@ -297,7 +339,7 @@ hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t st) {
                      (const T*)a.v_new[0], (const T*)a.v_new[1], (const T*)a.v_new[2],
                      (T*)a.Kc[0], (T*)a.Kc[1], (T*)a.Kc[2], (T*)a.Vc[0], (T*)a.Vc[1],
                      (T*)a.Vc[2], a.Gc, a.W_r, a.b_r, a.idx, a.cap[0], a.cap[1], a.cap[2], a.capG,
-                     a.j_new);
+                     a.j_new, a.routing);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   // a level without memory borrows another level's buffer (and capacity) and has length 0: the
@@ -318,11 +360,18 @@ hipError_t launch_decode_t(const DecodeArgs& a, hipStream_t st) {
   int chunk = (a.S + a.n_splits - 1) / a.n_splits;
   chunk = (chunk + GRAN - 1) / GRAN * GRAN;
   const float c = a.scale * kLog2e;
-  hipLaunchKernelGGL((decode_split_kernel<T, D, U>), dim3(a.n_splits, a.BH), dim3(256), 0, st,
-                     (const T*)a.q, (const T*)Kp[0], (const T*)Kp[1], (const T*)Kp[2],
-                     (const T*)Vp[0], (const T*)Vp[1], (const T*)Vp[2], a.Gc, a.partial,
-                     a.S, a.Kc[0] && a.Vc[0] ? a.len[0] : 0, a.Kc[1] && a.Vc[1] ? a.len[1] : 0,
-                     a.Kc[2] && a.Vc[2] ? a.len[2] : 0, capp[0], capp[1], capp[2], a.capG, chunk, c);
+  const int l0 = a.Kc[0] && a.Vc[0] ? a.len[0] : 0, l1 = a.Kc[1] && a.Vc[1] ? a.len[1] : 0,
+            l2 = a.Kc[2] && a.Vc[2] ? a.len[2] : 0;
+  if (a.routing == 2 || a.routing == 3)  // hard routing: gate-aware loads
+    hipLaunchKernelGGL((decode_split_kernel<T, D, U, true>), dim3(a.n_splits, a.BH), dim3(256), 0,
+                       st, (const T*)a.q, (const T*)Kp[0], (const T*)Kp[1], (const T*)Kp[2],
+                       (const T*)Vp[0], (const T*)Vp[1], (const T*)Vp[2], a.Gc, a.partial, a.S, l0,
+                       l1, l2, capp[0], capp[1], capp[2], a.capG, chunk, c);
+  else
+    hipLaunchKernelGGL((decode_split_kernel<T, D, U, false>), dim3(a.n_splits, a.BH), dim3(256), 0,
+                       st, (const T*)a.q, (const T*)Kp[0], (const T*)Kp[1], (const T*)Kp[2],
+                       (const T*)Vp[0], (const T*)Vp[1], (const T*)Vp[2], a.Gc, a.partial, a.S, l0,
+                       l1, l2, capp[0], capp[1], capp[2], a.capG, chunk, c);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3(a.BH), dim3(D), 0, st, a.partial,

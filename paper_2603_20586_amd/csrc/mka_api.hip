@@ -354,6 +354,7 @@ mka_status mka_fused_attn_decode(const void* q, const void* const k_new[3],
   if (s->d != 64 && s->d != 128) return MKA_ERR_UNSUPPORTED;
   if (!(s->scale >= 0.f) || isinf(s->scale)) return MKA_ERR_UNSUPPORTED;
   if (s->n_splits > mka::kMaxSplits) return MKA_ERR_UNSUPPORTED;
+  if (s->routing < MKA_ROUTE_SOFT || s->routing > MKA_ROUTE_TOP1) return MKA_ERR_UNSUPPORTED;
   if (!q || !k_new || !v_new || !Kc || !Vc || !Gc || !len || !W_r || !O) return MKA_ERR_NULL;
   const long long bh = (long long)s->B * s->H;
   if (bh > 65535) return MKA_ERR_UNSUPPORTED;  // grid.y
@@ -393,7 +394,7 @@ mka_status mka_fused_attn_decode(const void* q, const void* const k_new[3],
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MKA_ERR_ALIGN;
   a.q = q; a.Gc = Gc; a.W_r = W_r; a.b_r = b_r; a.O = O; a.LSE = LSE; a.idx = idx_out;
   a.BH = (int)bh; a.d = s->d; a.capG = s->capG; a.j_new = j_new;
-  a.scale = s->scale; a.bf16 = s->dtype == MKA_BF16;
+  a.scale = s->scale; a.bf16 = s->dtype == MKA_BF16; a.routing = s->routing;
   a.partial = static_cast<float*>(workspace);
   if (mka::launch_decode(a, (hipStream_t)stream) != hipSuccess) return MKA_ERR_LAUNCH;
   for (int l = 0; l < 3; ++l) len[l] = a.len[l];

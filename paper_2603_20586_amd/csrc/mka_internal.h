@@ -118,6 +118,7 @@ struct DecodeArgs {
   int n_splits;
   float scale;
   bool bf16;
+  int routing;     // how the new slot's gate is formed; hard modes switch on gate-aware loads
   float* partial;  // workspace [BH, n_splits, d + 2]
 };
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t st);

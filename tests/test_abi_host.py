@@ -140,6 +140,7 @@ def test_decode_rejects_bad_arguments(m):
     assert call(capG=8)[0] == 2                           # gate cache full
     assert call(ws=None, wsb=0)[0] == 5
     assert call(d=100)[0] == 6
+    assert call(routing=4)[0] == 6 and call(routing=-1)[0] == 6   # unknown routing variant
     rc, ln = call(dtype=9)
     assert rc == 3 and ln == [8, 8, 8]                    # lengths untouched on error
 

@@ -241,6 +241,57 @@ def test_decode_steps(mka, oracle, dtype, d, n_splits):
         assert np.array_equal(to_np(c["Kc"][0]), Kc_o[0])  # appended entries, bit for bit
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 128)])
+@pytest.mark.parametrize("mode", [1, 2, 3])   # fixed 1/3, hard top-2, hard top-1
+@pytest.mark.parametrize("n_splits", [0, 3])
+def test_decode_routing_variants(mka, oracle, dtype, d, mode, n_splits):
+    """Decode steps whose new slot is gated by a routing variant, over a gate cache written by
+    the same variant (hard modes: the kernel skips the loads of zero-gated levels; the oracle
+    multiplies by the zero).  Every level gets an entry, so all three are live."""
+    announce(f"decode routing mode={mode} {dtype} d={d} n_splits={n_splits}")
+    B, H, S0, steps = 2, 3, 333, 3
+    c = si.decode_caches(B, H, d, S0, cap_extra=steps, dtype=dtype, seed=23, device="cuda")
+    # all three levels full up to S0 (the generator leaves levels 2 and 3 at S0 already)
+    assert list(c["len"]) == [S0, S0, S0]
+    # gates of the old slots: the variant's gates of random query rows
+    qold = (torch.randn((B, H, S0, d), device="cuda") * (3.0 if mode > 1 else 1.0)).to(c["Kc"][0].dtype)
+    Gold, _ = mka.mka_route_variant(qold, c["W_r"], c["b_r"], mode=mode)
+    c["Gc"][:, :, :S0] = Gold
+    for l in (1, 2):  # room for the appended entries of levels 2 and 3
+        c["Kc"][l] = torch.cat([c["Kc"][l], torch.zeros_like(c["Kc"][l][:, :, :steps])], 2).contiguous()
+        c["Vc"][l] = torch.cat([c["Vc"][l], torch.zeros_like(c["Vc"][l][:, :, :steps])], 2).contiguous()
+    Kc_o = [to_np(x).copy() for x in c["Kc"]]
+    Vc_o = [to_np(x).copy() for x in c["Vc"]]
+    Gc_o = to_np(c["Gc"]).copy()
+    len_g, len_o = [S0] * 3, [S0] * 3
+    tol = (lambda x, r: max_abs(x, r) <= BF16_ATOL) if dtype == "bf16" else \
+        (lambda x, r: rel_err(x, r) <= F32_RTOL)
+    for step in range(steps):
+        kn, vn = [], []
+        for l in range(3):
+            q, k1, v1 = si.decode_step_inputs(B, H, d, 3 * step + l, dtype=dtype, seed=23, device="cuda")
+            kn.append(k1)
+            vn.append(v1)
+        q = q * (3.0 if mode > 1 else 1.0)
+        O, LSE, idx = mka.mka_fused_attn_decode(q, kn, vn, c["Kc"], c["Vc"], c["Gc"], len_g,
+                                                c["W_r"], c["b_r"], scale=c["scale"],
+                                                n_splits=n_splits, routing=mode)
+        torch.cuda.synchronize()
+        Oref, LSEref, idxref = oracle.decode_variant(
+            q.cpu(), [x.cpu() for x in kn], [x.cpu() for x in vn], Kc_o, Vc_o, Gc_o, len_o,
+            c["W_r"].cpu(), c["b_r"].cpu(), mode=mode, tau=c["scale"])
+        assert len_g == len_o == [S0 + step + 1] * 3
+        np.testing.assert_array_equal(idx.cpu().numpy(), idxref)
+        assert tol(O, Oref), (step, max_abs(O, Oref))
+        assert tol(LSE, LSEref[:, :, 0])
+        assert max_abs(c["Gc"], Gc_o) <= GATE_ATOL
+        if mode == 3:   # one-hot, exactly
+            g_new = to_np(c["Gc"])[:, :, S0 + step]
+            assert np.array_equal(g_new, np.eye(3)[idxref])
+        for l in range(3):
+            assert np.array_equal(to_np(c["Kc"][l]), Kc_o[l])
+
+
 def test_decode_equals_last_prefill_row(mka):
     """Property: a decode step over caches filled by a prefill == the prefill's last row."""
     announce("decode vs prefill row")

@@ -113,3 +113,78 @@ def test_top1_routed_attention_is_attention_over_the_selected_memory(oracle, cau
     Oref, LSEref = oracle.attn_fwd(Q, Ks, Vs, causal=causal, tau=0.6)
     np.testing.assert_allclose(O, Oref, atol=1e-13)
     np.testing.assert_allclose(LSE, LSEref, atol=1e-13)
+
+
+# ------------------------------------------------------------------ decode with a routing variant
+def _decode_problem(rng, B, H, d, S0, cap, lens=None):
+    Kc = [np.ascontiguousarray(rng.standard_normal((B, H, cap, d))) for _ in range(3)]
+    Vc = [np.ascontiguousarray(rng.standard_normal((B, H, cap, d))) for _ in range(3)]
+    q = rng.standard_normal((B, H, 1, d))
+    kn = [rng.standard_normal((B, H, 1, d)) for _ in range(3)]
+    vn = [rng.standard_normal((B, H, 1, d)) for _ in range(3)]
+    W = rng.standard_normal((d, 3)) * 2
+    b = rng.standard_normal(3)
+    return q, kn, vn, Kc, Vc, W, b, (list(lens) if lens else [S0, S0, S0])
+
+
+def test_decode_variant_soft_is_the_decode_oracle(oracle):
+    """The composition (append, variant gate, forward of one row) against the stand-alone decode
+    oracle, which is pinned on its own: soft routing must give the same step, also with a level
+    that lags behind and gets no entry."""
+    import copy
+    rng = np.random.default_rng(21)
+    for lens, drop in (([5, 5, 5], None), ([5, 3, 5], 1)):
+        q, kn, vn, Kc, Vc, W, b, l1 = _decode_problem(rng, 2, 2, 8, 5, 9, lens)
+        if drop is not None:
+            kn[drop] = None
+            vn[drop] = None
+        Gc = rng.random((2, 2, 9, 3))
+        Gc /= Gc.sum(-1, keepdims=True)
+        Kc2, Vc2, Gc2, l2 = copy.deepcopy(Kc), copy.deepcopy(Vc), Gc.copy(), list(l1)
+        O1, L1, i1 = oracle.decode(q, kn, vn, Kc, Vc, Gc, l1, W, b, tau=0.3)
+        O2, L2, i2 = oracle.decode_variant(q, kn, vn, Kc2, Vc2, Gc2, l2, W, b, mode=SOFT, tau=0.3)
+        np.testing.assert_allclose(O2, O1, atol=1e-14)
+        np.testing.assert_allclose(L2, L1, atol=1e-14)
+        np.testing.assert_array_equal(i2, i1)
+        np.testing.assert_array_equal(Gc2, Gc)
+        assert l1 == l2
+        for a, c in zip(Kc + Vc, Kc2 + Vc2):
+            np.testing.assert_array_equal(a, c)
+
+
+def test_decode_top1_is_attention_over_the_selected_rows(oracle):
+    """With one-hot gates in the cache and a top-1 gate for the new slot, the step is plain
+    attention of q over the stream that holds, slot by slot, the selected level's row."""
+    rng = np.random.default_rng(22)
+    B, H, d, S0, cap = 1, 3, 8, 6, 8
+    q, kn, vn, Kc, Vc, W, b, lens = _decode_problem(rng, B, H, d, S0, cap)
+    sel_old = rng.integers(0, 3, size=(B, H, S0))
+    Gc = np.zeros((B, H, cap, 3))
+    Gc[:, :, :S0] = np.eye(3)[sel_old]
+    O, LSE, idx = oracle.decode_variant(q, kn, vn, Kc, Vc, Gc, lens, W, b, mode=TOP1, tau=0.7)
+    logits = q[:, :, 0] @ W + b
+    np.testing.assert_array_equal(idx, logits.argmax(-1))
+    np.testing.assert_array_equal(Gc[:, :, S0], np.eye(3)[idx])       # the new slot's gate
+    sel = np.concatenate([sel_old, idx[..., None]], -1)[..., None]     # [B,H,S0+1,1]
+    S = S0 + 1
+    Ks = np.choose(sel, [a[:, :, :S] for a in Kc])
+    Vs = np.choose(sel, [a[:, :, :S] for a in Vc])
+    Oref, Lref = oracle.attn_fwd(q, Ks, Vs, causal=False, tau=0.7)
+    np.testing.assert_allclose(O, Oref, atol=1e-13)
+    np.testing.assert_allclose(LSE, Lref, atol=1e-13)
+    assert lens == [S, S, S]
+
+
+def test_decode_top2_gate_of_the_new_slot_by_hand(oracle):
+    # one head, d = 3, W = I: the logits are q.  q = (ln 4, ln 2, 0) -> top-2 gate (2/3, 1/3, 0)
+    q = np.array([np.log(4.0), np.log(2.0), 0.0]).reshape(1, 1, 1, 3)
+    Kc = [np.zeros((1, 1, 2, 3)) for _ in range(3)]
+    Vc = [np.zeros((1, 1, 2, 3)) for _ in range(3)]
+    Gc = np.zeros((1, 1, 2, 3))
+    one = [np.ones((1, 1, 1, 3)) * (l + 1) for l in range(3)]
+    lens = [0, 0, 0]
+    O, LSE, idx = oracle.decode_variant(q, one, one, Kc, Vc, Gc, lens, np.eye(3), None, mode=TOP2)
+    np.testing.assert_allclose(Gc[0, 0, 0], [2 / 3, 1 / 3, 0.0], atol=1e-15)
+    # a single slot: O is its fused value row = 2/3 * 1 + 1/3 * 2 = 4/3 in every component
+    np.testing.assert_allclose(O[0, 0, 0], 4 / 3, atol=1e-14)
+    assert idx[0, 0] == 0 and lens == [1, 1, 1]
