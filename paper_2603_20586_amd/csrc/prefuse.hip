@@ -4,8 +4,8 @@
 // The fused stream is what the paper caches; attention over it is plain softmax attention
 // (mka_mixture_attn_fwd with one memory and no gates), decode over it reads a third of the bytes.
 //
-// One thread = one 16-byte chunk of two slots: twelve 16-byte streaming loads issued at once, the
-// slots' gates, f32 mix, one rounding to bf16, four 16-byte stores.  Bound by HBM: 6 reads + 2 writes of S*d*2
+// One thread = one 16-byte chunk of two slots: the slots' gates, then up to twelve 16-byte
+// streaming loads issued at once, f32 mix, one rounding to bf16, four 16-byte stores.  Bound by HBM: 6 reads + 2 writes of S*d*2
 // bytes per (batch, head).
 #include "fuse_tile.h"
 #include "mka_dev.h"
@@ -29,10 +29,20 @@ __global__ __launch_bounds__(256) void prefuse_kernel(
   const bf16* Kp[3] = {K0, K1, K2};
   const bf16* Vp[3] = {V0, V1, V2};
   const int len[3] = {len0, len1, len2};
-  // all raw chunks (read once: streaming loads) and gates of the thread's slots first; an
-  // absent entry reads row 0 of its (b,h) block, which always exists, and is replaced by zeros
+  // the gates of the thread's slots first, then all raw chunks that count (read once: streaming
+  // loads); an absent entry is zeros
   uint4 rk[PF_U][3], rv[PF_U][3];
   float g[PF_U][3];
+  // a level whose gate is exactly zero (hard routing, section "Routing Mechanism Ablation")
+  // cannot contribute and is not loaded: top-1 gates halve the traffic (2 reads + 2 writes per
+  // element instead of 6 + 2); with soft gates the dependent gate load costs nothing measurable
+#pragma unroll
+  for (int u = 0; u < PF_U; ++u) {
+    const long row = row0 + (long)u * RPW;
+    const long rc = row < rows ? row : rows - 1;
+#pragma unroll
+    for (int l = 0; l < 3; ++l) g[u][l] = G[rc * 3 + l];
+  }
 #pragma unroll
   for (int u = 0; u < PF_U; ++u) {
     const long row = row0 + (long)u * RPW;
@@ -40,10 +50,13 @@ __global__ __launch_bounds__(256) void prefuse_kernel(
     const int j = (int)(rc % S);
 #pragma unroll
     for (int l = 0; l < 3; ++l) {
-      const long o = (j < len[l] ? rc : rc - j) * D + cc * 8;
-      rk[u][l] = load16_stream(Kp[l] + o);
-      rv[u][l] = load16_stream(Vp[l] + o);
-      g[u][l] = G[rc * 3 + l];
+      rk[u][l] = make_uint4(0, 0, 0, 0);
+      rv[u][l] = make_uint4(0, 0, 0, 0);
+      if (j < len[l] && g[u][l] != 0.f) {
+        const long o = rc * D + cc * 8;
+        rk[u][l] = load16_stream(Kp[l] + o);
+        rv[u][l] = load16_stream(Vp[l] + o);
+      }
     }
   }
 #pragma unroll

@@ -124,6 +124,27 @@ def test_fuse_kv_against_the_oracle(mka, oracle, d, S, len3):
     assert max_abs(Kf, Kr) <= BF16_ATOL and max_abs(Vf, Vr) <= BF16_ATOL
 
 
+@pytest.mark.parametrize("mode", [2, 3])   # hard top-2, hard top-1: gates with exact zeros
+def test_fuse_kv_with_hard_gates(mka, oracle, mode):
+    """Zero-gated levels are not loaded by the kernel; the oracle multiplies by the zero.  With
+    top-1 gates the fused row is the selected level's row, bit for bit."""
+    announce(f"fuse_kv hard gates mode={mode}")
+    S, d = 300, 128
+    inp = si.prefill_inputs(2, 2, S, S, d, dtype="bf16", seed=43, device="cuda")
+    G, idx = mka.mka_route_variant(inp["Q"], inp["W_r"] * 20.0, inp["b_r"], mode=mode)
+    assert int((G == 0).sum()) == 2 * 2 * S * (mode - 1)   # one (top-2) or two (top-1) zeros per slot
+    Kf, Vf = mka.mka_fuse_kv(inp["K"], inp["V"], G)
+    torch.cuda.synchronize()
+    Kr = oracle.fuse(cpu_list(inp["K"]), G.cpu())
+    Vr = oracle.fuse(cpu_list(inp["V"]), G.cpu())
+    assert max_abs(Kf, Kr) <= BF16_ATOL and max_abs(Vf, Vr) <= BF16_ATOL
+    if mode == 3:
+        sel = idx.long()[..., None, None].expand(-1, -1, -1, 1, d)      # [B,H,S,1,d]
+        Ks = torch.stack(inp["K"], 3).gather(3, sel)[:, :, :, 0]
+        Vs = torch.stack(inp["V"], 3).gather(3, sel)[:, :, :, 0]
+        assert torch.equal(Kf, Ks) and torch.equal(Vf, Vs)
+
+
 def test_prefuse_then_plain_attention_equals_the_folded_forward(mka, oracle):
     """The materialised alternative to in-kernel fusion: same fused bf16 stream, so the two GPU
     paths agree far inside the bound, and both match the oracle's route-fused forward."""
