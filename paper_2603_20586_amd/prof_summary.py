@@ -22,19 +22,35 @@ import re
 import sys
 
 
+def _template_args(mangled: str) -> str:
+    """'IDF16bLi128ELi4ELb1EE...' -> '<bf16,128,4,true>' (the argument kinds this library uses)."""
+    if not mangled.startswith("I"):
+        return ""
+    i, args = 1, []
+    while i < len(mangled) and mangled[i] != "E":
+        if mangled.startswith("DF16b", i):
+            args.append("bf16")
+            i += 5
+        elif mangled[i] == "f":
+            args.append("f32")
+            i += 1
+        elif mangled[i] == "L":                       # literal: L <type letter> <value> E
+            j = mangled.index("E", i)
+            kind, val = mangled[i + 1], mangled[i + 2:j]
+            args.append(("true" if val == "1" else "false") if kind == "b" else val)
+            i = j + 1
+        else:
+            return ""                                 # something else: leave the name bare
+    return "<" + ",".join(args) + ">"
+
+
 def short(name: str) -> str:
     """Readable kernel name (c++filt does not know every mangling of the bf16 type)."""
     m = re.match(r"_ZN3mka(?:12_GLOBAL__N_1)?(\d+)", name)
     if m:
         n = int(m.group(1))
         start = m.end()
-        base = name[start:start + n]
-        t = re.match(r"I(.*?)E", name[start + n:])
-        tp = ""
-        if t:
-            tp = "<" + t.group(1).replace("DF16b", "bf16,").replace("Li", "").replace("E", ",") \
-                .replace("f", "f32,").strip(",") + ">"
-        return "mka::" + base + tp
+        return "mka::" + name[start:start + n] + _template_args(name[start + n:])
     name = name.replace("(anonymous namespace)::", "")
     return name.split("(")[0].replace("void ", "")[:80]
 
@@ -105,7 +121,7 @@ TRAFFIC_KEYS = {   # causal launches: one workgroup per PAIR of tiles
                ("mka::bwd_dq_kernel<128>", 256)],         # 64 heads x 8/2 query tiles
     "C5_bwd": [("mka::bwd_main_kernel<128>", 2048),       # 128 heads x 32/2 KV tiles
                ("mka::bwd_dq_kernel<128>", 1024)],        # 128 heads x 16/2 query tiles
-    "C4_decode": [("mka::decode_split_kernel<bf32,16,128>", 2048)],  # 4 splits x 512 heads
+    "C4_decode": [("mka::decode_split_kernel<bf16,128,4,false>", 2048)],  # 4 splits x 512 heads
 }
 
 
