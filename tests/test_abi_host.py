@@ -196,3 +196,19 @@ def test_widened_entry_points_reject_bad_arguments(m):
     ps.d = 128
     assert L.mka_paged_fused_decode(FAKE, FAKE, FAKE, None, FAKE, FAKE, None, ctypes.byref(ps),
                                     FAKE, 1 << 30, None) == 1
+
+
+def test_profile_summary_kernel_names():
+    """Host logic of the profile summaries: mangled kernel names keep every template argument
+    (two instantiations of one kernel must not be merged into one line)."""
+    from paper_2603_20586_amd.prof_summary import short
+
+    a = short("_ZN3mka12_GLOBAL__N_119decode_split_kernelIDF16bLi128ELi4ELb1EEEvPKT_S4_")
+    b = short("_ZN3mka12_GLOBAL__N_119decode_split_kernelIDF16bLi128ELi4ELb0EEEvPKT_S4_")
+    assert a == "mka::decode_split_kernel<bf16,128,4,true>"
+    assert b == "mka::decode_split_kernel<bf16,128,4,false>"
+    assert short("_ZN3mka12_GLOBAL__N_119decode_split_kernelIfLi64ELi4ELb0EEEvPKT_") == \
+        "mka::decode_split_kernel<f32,64,4,false>"
+    assert short("_ZN3mka12_GLOBAL__N_117bwd_reduce_kernelEPKfiiPfS3_") == "mka::bwd_reduce_kernel"
+    assert short("_ZN3mka12route_kernelIDF16bLi128EEEvPKT_PKfS5_PfPiliii") == "mka::route_kernel<bf16,128>"
+    assert short("void at::native::foo<int>(int)") == "at::native::foo<int>"
