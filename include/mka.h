@@ -190,7 +190,8 @@ mka_status mka_fused_attn_decode(const void* q, const void* const k_new[3],
  * Every output is a fixed-order sum: the same call gives the same bits (dQ is
  * accumulated in registers by a query-stationary kernel, dW_r/db_r by a
  * two-stage reduction).  The workspace (mka_workspace_bytes(MKA_OP_BWD, shape))
- * holds the f32 dQ accumulator, padded D / LSE rows and the fused Kf / Vf stream. */
+ * holds the padded D / LSE rows, the gate gradients, the router-gradient partial sums and the
+ * fused Kf / Vf stream. */
 mka_status mka_fused_attn_bwd(const void* dO, const void* Q, const void* const K[3],
                               const void* const V[3], const float* G, const void* O,
                               const float* LSE, const float* W_r, void* dQ, void* const dK[3],
@@ -201,7 +202,8 @@ mka_status mka_fused_attn_bwd(const void* dO, const void* Q, const void* const K
  * paper caches): Kf[j] = sum_l [j < len[l]] G[j,l] K_l[j], Vf likewise, mixed in f32 and rounded
  * once to bf16.  K[l], V[l], Kf, Vf [B,H,S,d] (device, bf16, 16-byte aligned; Kf/Vf are fully
  * overwritten; a NULL K[l]/V[l] or slots j >= len[l] contribute the zero vector and the gates
- * are not renormalised); G [B,H,S,3] f32 gates of the slots.  Reads shape->B,H,S,d,len,dtype.
+ * are not renormalised; a level whose gate G[j,l] is exactly zero - hard routing - is not read
+ * at that slot); G [B,H,S,3] f32 gates of the slots.  Reads shape->B,H,S,d,len,dtype.
  * Attention over the result is plain softmax attention: mka_mixture_attn_fwd with one memory
  * and G = NULL; it equals mka_fused_attn_fwd on the raw memories up to rounding order.
  * Enqueues on `stream` and returns; allocates nothing.  bf16 only, d in {64,128}. */
