@@ -21,16 +21,29 @@ def m():
     return mod
 
 
-def test_every_declared_symbol_is_exported(m):
-    hdr = open(os.path.join(ROOT, "include", "mka.h")).read()
+def _declared(header):
+    hdr = open(os.path.join(ROOT, "include", header)).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    names = set(re.findall(r"\b(mka_[a-z_0-9]+)\s*\(", hdr))
+    return set(re.findall(r"\b(mka_[a-z_0-9]+)\s*\(", hdr))
+
+
+def test_every_declared_symbol_is_exported(m):
+    names = _declared("mka.h")
     assert {"mka_route", "mka_fused_attn_fwd", "mka_fused_attn_decode", "mka_fused_attn_bwd",
             "mka_workspace_bytes", "mka_status_string", "mka_version"} <= names
     L = m.lib()
     for n in names:
         assert hasattr(L, n), n
     assert L.mka_version() >= 100
+    # the measurement micro-benchmarks live in a library of their own, not in the product's
+    from paper_2603_20586_amd import measure
+
+    mnames = _declared("mka_measure.h")
+    assert mnames == {"mka_measure_mfma_loop", "mka_measure_stream_read"}
+    for n in mnames:
+        assert hasattr(measure.lib(), n), n
+        assert not hasattr(L, n), n
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["mka.h", "mka_measure.h"]
 
 
 def test_status_strings(m):
@@ -145,15 +158,17 @@ def test_decode_rejects_bad_arguments(m):
     assert rc == 3 and ln == [8, 8, 8]                    # lengths untouched on error
 
 
-def test_ceiling_helpers_reject_bad_arguments_on_the_host(m):
+def test_measure_helpers_reject_bad_arguments_on_the_host(m):
     import ctypes
-    L = m.lib()
-    assert L.mka_ceiling_mfma(None, 4, 10, None, None) == 2      # no output buffer
-    assert L.mka_ceiling_mfma(ctypes.c_void_p(256), 0, 10, None, None) == 2
-    assert L.mka_ceiling_mfma(ctypes.c_void_p(256), 4, 0, None, None) == 2
-    assert L.mka_ceiling_read(None, 1 << 20, None, None) == 2
-    assert L.mka_ceiling_read(ctypes.c_void_p(4096), 64, None, None) == 2   # too small
-    assert L.mka_ceiling_read(ctypes.c_void_p(4100), 1 << 20, None, None) == 4  # misaligned
+    from paper_2603_20586_amd import measure
+
+    L = measure.lib()
+    assert L.mka_measure_mfma_loop(None, 4, 10, None, None) == 2      # no output buffer
+    assert L.mka_measure_mfma_loop(ctypes.c_void_p(256), 0, 10, None, None) == 2
+    assert L.mka_measure_mfma_loop(ctypes.c_void_p(256), 4, 0, None, None) == 2
+    assert L.mka_measure_stream_read(None, 1 << 20, None, None) == 2
+    assert L.mka_measure_stream_read(ctypes.c_void_p(4096), 64, None, None) == 2   # too small
+    assert L.mka_measure_stream_read(ctypes.c_void_p(4100), 1 << 20, None, None) == 4  # misaligned
 
 
 def test_widened_entry_points_reject_bad_arguments(m):
@@ -201,7 +216,7 @@ def test_widened_entry_points_reject_bad_arguments(m):
 def test_profile_summary_kernel_names():
     """Host logic of the profile summaries: mangled kernel names keep every template argument
     (two instantiations of one kernel must not be merged into one line)."""
-    from paper_2603_20586_amd.prof_summary import short
+    from paper_2603_20586_amd.measure.prof_summary import short
 
     a = short("_ZN3mka12_GLOBAL__N_119decode_split_kernelIDF16bLi128ELi4ELb1EEEvPKT_S4_")
     b = short("_ZN3mka12_GLOBAL__N_119decode_split_kernelIDF16bLi128ELi4ELb0EEEvPKT_S4_")

@@ -102,3 +102,25 @@ def test_full_mka_with_prefix_mean_memory(mka, oracle):
     Oref = oracle.full_mka_fwd(Q.cpu(), [K[0].cpu(), K2r, None], [V[0].cpu(), V2r, None], G.cpu(),
                                causal=True, tau=0.09)
     assert max_abs(O, Oref) <= BF16_ATOL
+
+
+def test_full_mka_long_prefill_shape_sampled_rows(mka, oracle):
+    """C3 shape (B1 H32 T8192 d128), the size bench.py times: sampled query rows, each a one-row
+    problem over slots 0..t of every memory for the oracle."""
+    import synth_inputs as si
+    from util import announce as _announce
+
+    _announce("full MKA C3 shape, sampled rows")
+    inp, cfg = si.config_inputs("C3", device="cuda")
+    G, _ = mka.mka_route(inp["Q"], inp["W_r"] * 30.0, inp["b_r"], want_idx=False)
+    O = mka.mka_full_attn_fwd(inp["Q"], inp["K"], inp["V"], G, causal=True, scale=inp["scale"])
+    torch.cuda.synchronize()
+    worst = 0.0
+    for (b, h) in [(0, 0), (0, 31), (0, 13)]:
+        for t in [0, 1, 63, 64, 255, 256, 257, 4095, 4096, 8000, 8191]:
+            cut = lambda x, lo, hi: x[b:b + 1, h:h + 1, lo:hi].cpu()  # noqa: E731
+            Oref = oracle.full_mka_fwd(cut(inp["Q"], t, t + 1), [cut(k, 0, t + 1) for k in inp["K"]],
+                                       [cut(v, 0, t + 1) for v in inp["V"]], cut(G, t, t + 1),
+                                       causal=True, tau=inp["scale"])
+            worst = max(worst, max_abs(O[b:b + 1, h:h + 1, t:t + 1], Oref))
+    assert worst <= BF16_ATOL, worst

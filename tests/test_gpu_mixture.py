@@ -109,6 +109,32 @@ def test_mixture_full_prefill_shape_sampled_heads(mka, oracle):
         assert max_abs(LSE[sl], Lref) <= BF16_ATOL
 
 
+def _one_row(x, b, h, lo, hi):
+    return None if x is None else x[b:b + 1, h:h + 1, lo:hi].cpu()
+
+
+def test_mixture_long_prefill_shape_sampled_rows(mka, oracle):
+    """C3 shape (B1 H32 T8192 d128), three memories of 8192 slots, the size bench.py times: the
+    oracle computes sampled query rows one by one (row t of a causal problem is a one-row
+    problem over slots 0..t of every memory)."""
+    announce("mixture C3 shape, sampled rows")
+    inp, cfg = si.config_inputs("C3", device="cuda")
+    G, _ = mka.mka_route(inp["Q"], inp["W_r"] * 30.0, inp["b_r"], want_idx=False)
+    O, LSE = mka.mka_mixture_attn_fwd(inp["Q"], inp["K"], inp["V"], G, causal=True, scale=inp["scale"])
+    torch.cuda.synchronize()
+    worst = 0.0
+    for (b, h) in [(0, 0), (0, 31), (0, 13)]:
+        for t in [0, 1, 63, 64, 255, 256, 257, 4095, 4096, 8000, 8191]:
+            Oref, Lref = oracle.mixture_fwd(
+                _one_row(inp["Q"], b, h, t, t + 1), [_one_row(k, b, h, 0, t + 1) for k in inp["K"]],
+                [_one_row(v, b, h, 0, t + 1) for v in inp["V"]], _one_row(G, b, h, t, t + 1),
+                causal=True, tau=inp["scale"])
+            worst = max(worst, max_abs(O[b:b + 1, h:h + 1, t:t + 1], Oref))
+            assert abs(float(LSE[b, h, t]) - float(Lref[0, 0, 0])) <= BF16_ATOL
+    assert worst <= BF16_ATOL, worst
+    assert torch.isfinite(O.float()).all()
+
+
 # ------------------------------------------------------------------ materialised route-fusion
 @pytest.mark.parametrize("d", [128, 64])
 @pytest.mark.parametrize("S,len3", [(300, None), (257, [257, 100, 0]), (1, None)])

@@ -56,11 +56,15 @@ def test_C2_prefill_full(mka, oracle):
         assert max_abs(LSE[sl], LSEref) <= BF16_ATOL
 
 
-def test_C3_long_prefill_sampled_rows(mka, oracle):
-    announce("C3 long prefill full size, sampled rows")
+@pytest.mark.parametrize("materialise", [None, False], ids=["library-default-route", "folded-route"])
+def test_C3_long_prefill_sampled_rows(mka, oracle, materialise):
+    """Both forward routes at the full C3 size: the one the library picks by itself for this shape
+    (Kf, Vf materialised once, then plain attention) and the folded kernel (fusion inside the
+    attention kernel's tile loads, no workspace)."""
+    announce(f"C3 long prefill full size, sampled rows, materialise={materialise}")
     inp, cfg = si.config_inputs("C3", device="cuda")
     O, LSE, G, idx = mka.mka_fused_attn_fwd(inp["Q"], inp["K"], inp["V"], inp["W_r"], inp["b_r"],
-                                            causal=True, scale=inp["scale"])
+                                            causal=True, scale=inp["scale"], materialise=materialise)
     torch.cuda.synchronize()
     Gref, idxref = oracle.route(inp["Q"].cpu(), inp["W_r"].cpu(), inp["b_r"].cpu())
     np.testing.assert_array_equal(idx.cpu().numpy(), idxref)
@@ -72,49 +76,70 @@ def test_C3_long_prefill_sampled_rows(mka, oracle):
     assert torch.isfinite(O.float()).all()
 
 
-def test_C5_training_sampled_heads(mka, oracle):
-    announce("C5 training full size, sampled heads")
+def test_C5_forward_folded_route_sampled_heads(mka, oracle):
+    """The folded forward kernel at the full C5 size (the library's default there is the
+    materialised route, which the training test below runs): two whole heads."""
+    announce("C5 forward, folded route, sampled heads")
+    inp, cfg = si.config_inputs("C5", device="cuda")
+    O, LSE, G, idx = mka.mka_fused_attn_fwd(inp["Q"], inp["K"], inp["V"], inp["W_r"], inp["b_r"],
+                                            causal=True, scale=inp["scale"], materialise=False)
+    torch.cuda.synchronize()
+    for (b, h) in [(0, 0), (5, 9)]:
+        sl = (slice(b, b + 1), slice(h, h + 1))
+        Oref, LSEref, Gref, idxref = oracle.fwd_routed(
+            inp["Q"][sl].cpu(), [k[sl].cpu() for k in inp["K"]], [v[sl].cpu() for v in inp["V"]],
+            inp["W_r"].cpu(), inp["b_r"].cpu(), causal=True, tau=inp["scale"])
+        np.testing.assert_array_equal(idx[sl].cpu().numpy(), idxref)
+        assert max_abs(O[sl], Oref) <= BF16_ATOL
+        assert max_abs(LSE[sl], LSEref) <= BF16_ATOL
+
+
+def test_C5_training_all_heads(mka, oracle):
+    """Config C5 in full: dQ, dK_l, dV_l of all 128 heads on the raw 2e-2, dW_r / db_r of the whole
+    problem on the normalised 2e-2 (about a minute of oracle time on the machine's host cores)."""
+    announce("C5 training full size, all heads")
     inp, cfg = si.config_inputs("C5", device="cuda")
     O, LSE, G, idx = mka.mka_fused_attn_fwd(inp["Q"], inp["K"], inp["V"], inp["W_r"], inp["b_r"],
                                             causal=True, scale=inp["scale"])
     g = mka.mka_fused_attn_bwd(inp["dO"], inp["Q"], inp["K"], inp["V"], G, O, LSE, inp["W_r"],
                                causal=True, scale=inp["scale"])
     torch.cuda.synchronize()
-    heads = [(0, 0), (7, 15)]
-    refs = {}
-    for (b, h) in heads:
-        sl = (slice(b, b + 1), slice(h, h + 1))
+    # Router gradients of the configured problem: they sum over all 128 heads and 524 288 rows
+    # (two-stage fixed-order reduction on the GPU).  The oracle runs every head, one batch entry
+    # (16 heads) at a time to bound its memory, and its per-head sums are added in fp64.
+    B = cfg["B"]
+    dW_ref = np.zeros((cfg["d"], 3))
+    db_ref = np.zeros(3)
+    for b in range(B):
+        sl = slice(b, b + 1)
+        print(f"[case] C5 oracle backward, batch entry {b + 1}/{B}", flush=True)
         Gref, _ = oracle.route(inp["Q"][sl].cpu(), inp["W_r"].cpu(), inp["b_r"].cpu())
         ref = oracle.bwd(inp["dO"][sl].cpu(), inp["Q"][sl].cpu(), [k[sl].cpu() for k in inp["K"]],
                          [v[sl].cpu() for v in inp["V"]], Gref, inp["W_r"].cpu(), causal=True,
                          tau=inp["scale"])
-        refs[(b, h)] = ref
-        assert max_abs(g["dQ"][sl], ref["dQ"]) <= BF16_ATOL
-        for l in range(3):
-            assert max_abs(g["dK"][l][sl], ref["dK"][l]) <= BF16_ATOL
-            assert max_abs(g["dV"][l][sl], ref["dV"][l]) <= BF16_ATOL
-    # router gradients sum over ALL heads; check them on the two-head sub-problem instead, where
-    # the oracle's sum is available (same kernels, same per-head work)
-    b0, h0 = heads[0]
-    b1, h1 = heads[1]
-    pick = lambda x: torch.stack([x[b0, h0], x[b1, h1]], 0)[None].contiguous()  # noqa: E731
-    sub = dict(Q=pick(inp["Q"]), K=[pick(k) for k in inp["K"]], V=[pick(v) for v in inp["V"]],
-               dO=pick(inp["dO"]))
-    Os, Ls, Gs, _ = mka.mka_fused_attn_fwd(sub["Q"], sub["K"], sub["V"], inp["W_r"], inp["b_r"],
-                                           causal=True, scale=inp["scale"])
-    gs = mka.mka_fused_attn_bwd(sub["dO"], sub["Q"], sub["K"], sub["V"], Gs, Os, Ls, inp["W_r"],
-                                causal=True, scale=inp["scale"])
-    torch.cuda.synchronize()
-    dW_ref = refs[heads[0]]["dW_r"] + refs[heads[1]]["dW_r"]
-    db_ref = refs[heads[0]]["db_r"] + refs[heads[1]]["db_r"]
-    assert rel_err(gs["dW_r"], dW_ref) <= BF16_ATOL, rel_err(gs["dW_r"], dW_ref)
-    assert max_abs(gs["db_r"], db_ref) <= BF16_ATOL * max(1.0, float(np.abs(dW_ref).max()))
-    # and the full-size reduction is finite and deterministic (fixed-order two-stage sum)
+        dW_ref += ref["dW_r"]
+        db_ref += ref["db_r"]
+        if True:  # every head's dQ / dK_l / dV_l on the raw bound while the reference is here
+            assert max_abs(g["dQ"][sl], ref["dQ"]) <= BF16_ATOL
+            for l in range(3):
+                assert max_abs(g["dK"][l][sl], ref["dK"][l]) <= BF16_ATOL
+                assert max_abs(g["dV"][l][sl], ref["dV"][l]) <= BF16_ATOL
+        del ref
+    # sums of 524 288 rows: judged on the scale-normalised error of each gradient's own reference
+    eW = max_abs(g["dW_r"], dW_ref) / max(1.0, float(np.abs(dW_ref).max()))
+    eb = max_abs(g["db_r"], db_ref) / max(1.0, float(np.abs(db_ref).max()))
+    print(f"[case] C5 dW_r normalised error {eW:.3e} (max|ref| {np.abs(dW_ref).max():.3e}), "
+          f"db_r {eb:.3e} (max|ref| {np.abs(db_ref).max():.3e})", flush=True)
+    assert eW <= BF16_ATOL, eW
+    assert eb <= BF16_ATOL, eb
+    # the same call again gives the same bits (fixed-order sums everywhere)
     g2 = mka.mka_fused_attn_bwd(inp["dO"], inp["Q"], inp["K"], inp["V"], G, O, LSE, inp["W_r"],
                                 causal=True, scale=inp["scale"])
     torch.cuda.synchronize()
-    assert torch.isfinite(g["dW_r"]).all() and torch.isfinite(g["db_r"]).all()
-    assert float((g["db_r"].double().sum()).abs()) <= 1e-2 * float(g["dW_r"].abs().max() + 1)
+    assert torch.equal(g2["dW_r"], g["dW_r"]) and torch.equal(g2["db_r"], g["db_r"])
+    assert torch.equal(g2["dQ"], g["dQ"])
+    for l in range(3):
+        assert torch.equal(g2["dK"][l], g["dK"][l]) and torch.equal(g2["dV"][l], g["dV"][l])
 
 
 def test_C4_decode_full_sampled_heads(mka, oracle):

@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import synth_inputs as si
-from util import BF16_ATOL, F32_RTOL, GATE_ATOL, announce, cpu_list, max_abs, rel_err, to_np
+from util import (BF16_ATOL, F32_RTOL, GATE_ATOL, announce, cpu_list, max_abs, rel_err, to_np)
 
 pytestmark = pytest.mark.gpu
 
@@ -113,7 +113,7 @@ def test_fwd_bwd_with_variant_gates(mka, oracle, mode):
     for name, x, r in [("dQ", g["dQ"], ref["dQ"])] + \
             [(f"dK{l}", g["dK"][l], ref["dK"][l]) for l in range(3)] + \
             [(f"dV{l}", g["dV"][l], ref["dV"][l]) for l in range(3)]:
-        assert max_abs(x, r) / max(1.0, float(np.abs(r).max())) <= BF16_ATOL, name
+        assert max_abs(x, r) <= BF16_ATOL, (name, max_abs(x, r))
 
 
 # ------------------------------------------------------------------ forward, f32
@@ -318,7 +318,7 @@ def test_decode_equals_last_prefill_row(mka):
 
 
 # ------------------------------------------------------------------ backward, bf16 MFMA
-def _check_bwd(mka, oracle, inp, S, len3, causal, Gprev=None, use_router=True):
+def _check_bwd(mka, oracle, inp, S, len3, causal, Gprev=None, use_router=True, stress=False):
     W = inp["W_r"] if use_router else None
     if use_router:
         O, LSE, G, idx = mka.mka_fused_attn_fwd(
@@ -338,40 +338,62 @@ def _check_bwd(mka, oracle, inp, S, len3, causal, Gprev=None, use_router=True):
     ref = oracle.bwd(inp["dO"].cpu(), inp["Q"].cpu(), cpu_list(inp["K"]), cpu_list(inp["V"]), Gref,
                      inp["W_r"].cpu() if use_router else None, len3=len3, causal=causal,
                      tau=inp["scale"])
-    # The bound is 2e-2 at unit scale.  A gradient of magnitude m is stored in bf16 with a
-    # quantisation step of m * 2^-8, which alone exceeds 2e-2 once m > 5 (short rows with a
-    # scaled-up router reach 7 here), so the bound scales with max(1, max|ref|).
-    def scaled(x, r):
-        return max_abs(x, r) / max(1.0, float(np.abs(r).max()) if r.size else 1.0)
-    errs = {"dQ": scaled(g["dQ"], ref["dQ"])}
+    # Contract: raw max-abs 2e-2 on dQ, dK_l, dV_l.  Only the labelled stress cases (router scaled
+    # up tenfold) are judged on the error normalised by the gradient's own scale, see there.
+    errs = {"dQ": (g["dQ"], ref["dQ"])}
     for l in range(3):
-        errs[f"dK{l}"] = scaled(g["dK"][l], ref["dK"][l])
-        errs[f"dV{l}"] = scaled(g["dV"][l], ref["dV"][l])
-    for k, v in errs.items():
-        assert v <= BF16_ATOL, (k, v, errs)
+        errs[f"dK{l}"] = (g["dK"][l], ref["dK"][l])
+        errs[f"dV{l}"] = (g["dV"][l], ref["dV"][l])
+    raw = {k: max_abs(x, r) for k, (x, r) in errs.items()}
+    scale = {k: max(1.0, float(np.abs(r).max()) if r.size else 1.0) for k, (x, r) in errs.items()}
+    if True:
+        print("[case] raw max-abs / max|ref|: " +
+              ", ".join(f"{k} {raw[k]:.4f}/{scale[k]:.2f}" for k in raw), flush=True)
+    for k in errs:
+        assert raw[k] <= BF16_ATOL * (scale[k] if stress else 1.0), (k, raw, scale)
     if use_router:
-        # the router gradients sum B*H*Tq rows, so their size grows with the problem: they are
-        # judged on the scale-normalised error max|x-r| / max|r|
-        assert rel_err(g["dW_r"], ref["dW_r"]) <= BF16_ATOL, rel_err(g["dW_r"], ref["dW_r"])
-        assert max_abs(g["db_r"], ref["db_r"]) <= BF16_ATOL * max(1.0, float(np.abs(ref["dW_r"]).max()))
-    return errs
+        # the router gradients sum B*H*Tq rows, so their size grows with the problem: each is
+        # judged on the scale-normalised error max|x-r| / max(1, max|r|) of its own reference
+        assert max_abs(g["dW_r"], ref["dW_r"]) <= BF16_ATOL * max(1.0, float(np.abs(ref["dW_r"]).max())), raw
+        assert max_abs(g["db_r"], ref["db_r"]) <= BF16_ATOL * max(1.0, float(np.abs(ref["db_r"]).max())), raw
+    return raw
 
 
-@pytest.mark.parametrize("d", [128, 64])
-@pytest.mark.parametrize("Tq,S,causal,len3", [
+BWD_SHAPES = [
     (200, 200, True, None),          # two kv tiles, ragged tails
     (130, 333, True, None),          # cache prefix: only the last 130 slots have router grads
     (150, 190, False, None),         # non-causal
     (257, 257, True, [257, 100, 0]),  # absent levels: zero gradients there
     (32, 32, True, None), (96, 96, True, None), (97, 161, True, None),  # 1, 3, 4 query tiles
     (520, 520, True, None),          # 5 kv tiles, 3 dQ tiles: pairs plus a middle tile alone
-    (1, 1, True, None), (64, 128, True, None)])
+    (1, 1, True, None), (64, 128, True, None)]
+
+
+@pytest.mark.parametrize("d", [128, 64])
+@pytest.mark.parametrize("Tq,S,causal,len3", BWD_SHAPES)
 def test_bwd_bf16_shapes(mka, oracle, d, Tq, S, causal, len3):
+    """Router as in the benchmark configs (W_r ~ N(0, 0.02^2)): raw max-abs 2e-2."""
     announce(f"bwd bf16 d={d} Tq={Tq} S={S} causal={causal} len={len3}")
+    inp = si.prefill_inputs(2, 2, Tq, S, d, dtype="bf16", seed=13, device="cuda", with_dO=True)
+    Gprev = torch.softmax(torch.randn((2, 2, S, 3), device="cuda"), -1)
+    _check_bwd(mka, oracle, inp, S, len3, causal, Gprev=Gprev)
+
+
+@pytest.mark.parametrize("d", [128, 64])
+@pytest.mark.parametrize("Tq,S,causal,len3", BWD_SHAPES)
+def test_bwd_bf16_scaled_router_stress(mka, oracle, d, Tq, S, causal, len3):
+    """Stress case, labelled: router weights scaled up tenfold, so that the gates are far from
+    uniform and the path through the router, dg W_r^T, carries most of dQ (|dQ| reaches ~7 on
+    short rows).  dg is built from differences of 128-term dot products of dKf / dVf with the
+    raw rows, so the bf16-path error of dKf / dVf enters it as an absolute error, and W_r - ten
+    times the configs' - multiplies it into dQ: the error grows with the gradient's own scale
+    (measured raw max-abs up to 0.031 at max|dQ| ~ 7, i.e. 0.4 %).  Judged on max|x - r| / max(1, max|r|) <= 2e-2; the raw and the
+    scale figures of every case are printed."""
+    announce(f"bwd bf16 stress (W_r x 10) d={d} Tq={Tq} S={S} causal={causal} len={len3}")
     inp = si.prefill_inputs(2, 2, Tq, S, d, dtype="bf16", seed=13, device="cuda", with_dO=True)
     inp["W_r"] = inp["W_r"] * 10.0
     Gprev = torch.softmax(torch.randn((2, 2, S, 3), device="cuda"), -1)
-    _check_bwd(mka, oracle, inp, S, len3, causal, Gprev=Gprev)
+    _check_bwd(mka, oracle, inp, S, len3, causal, Gprev=Gprev, stress=True)
 
 
 def test_bwd_same_call_same_bits(mka):
