@@ -165,9 +165,15 @@ mka_status mka_fused_attn_fwd(const void* Q, const void* const K[3], const void*
  *   Kc,Vc    in/out  three caches [B,H,cap[l],d] each (NULL allowed if len[l]==0 and no k_new[l])
  *   Gc       in/out  [B,H,capG,3] f32 gate cache
  *   len      in/out  HOST array of 3: valid slots per level before / after the call
- *   W_r,b_r  in      router (W_r required)
+ *   W_r,b_r  in      router.  W_r NULL = row j_new of Gc is taken as the caller wrote it (as the
+ *                    forward takes G without W_r); idx_out must then be NULL.  This is how a
+ *                    cache of FUSED keys / values (section "Route-Fused MKA (FastMKA)": what the
+ *                    paper caches; written by mka_fuse_kv) is decoded: the fused stream is level 1
+ *                    alone, levels 2 and 3 NULL, every gate row (1,0,0), and k_new[0], v_new[0]
+ *                    are the new token's fused rows.
  *   O        out     [B,H,1,d];  LSE out [B,H] f32 or NULL;  idx_out out [B,H] int32 or NULL
- * At least one level must be appended.
+ * At least one level must be appended.  Per level cap[l] * d * sizeof(element) must stay below
+ * 2^32 (MKA_ERR_UNSUPPORTED otherwise) and B * H below 65536.
  * shape->routing selects how the new slot's gate is formed from its logits (paper: section
  * "Routing Mechanism Ablation"; see mka_route_variant; an unknown value gives
  * MKA_ERR_UNSUPPORTED).  With hard routing (MKA_ROUTE_TOP2, MKA_ROUTE_TOP1) the attention does
@@ -285,21 +291,6 @@ mka_status mka_paged_fused_decode(const void* q, const void* Kpool, const void* 
  * mka_workspace_bytes(MKA_OP_PREFIX_MEAN, shape) bytes, 256-byte aligned. */
 mka_status mka_prefix_mean(const void* X, void* M, const mka_shape* shape, void* workspace,
                            size_t workspace_bytes, void* stream);
-
-/* Measurement helpers (not part of the method): the ceilings that the rooflines of the
- * attention kernels are quoted against besides the vendor peaks.
- *
- * mka_ceiling_mfma: `workgroups` x 8 waves each issue 4 * iters independent 32x32x16 bf16 MFMAs
- *   (no memory traffic); `out` (device, workgroups * 512 floats) receives a checksum; *flops
- *   (host, nullable) the number of floating-point operations of the launch.
- * mka_ceiling_read: streams `bytes` (device, 16-byte aligned, at least 32 KiB) once with
- *   16-byte non-temporal loads; `out` (device, nullable) is only written in the practically
- *   impossible case that the xor of all words equals a magic constant.
- * Both enqueue on `stream` and return; the caller times them.  Errors: MKA_ERR_SHAPE for
- * non-positive sizes or null buffers, MKA_ERR_ALIGN, MKA_ERR_LAUNCH. */
-mka_status mka_ceiling_mfma(float* out, int32_t workgroups, int32_t iters, double* flops,
-                            void* stream);
-mka_status mka_ceiling_read(const void* src, size_t bytes, uint32_t* out, void* stream);
 
 /* Static, human-readable name of a status. */
 const char* mka_status_string(mka_status status);

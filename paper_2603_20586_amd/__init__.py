@@ -11,8 +11,6 @@ from .binding import (  # noqa: F401
     MkaError,
     lib,
     lib_path,
-    mka_ceiling_mfma,
-    mka_ceiling_read,
     mka_fused_attn_bwd,
     mka_fused_attn_decode,
     mka_fuse_kv,

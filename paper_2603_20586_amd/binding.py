@@ -91,10 +91,6 @@ def lib() -> ctypes.CDLL:
         L.mka_mixture_attn_fwd.restype = ctypes.c_int
         L.mka_mixture_attn_fwd.argtypes = [c_void_p, POINTER(_P3), POINTER(_P3), c_void_p, c_void_p,
                                            c_void_p, POINTER(MkaShape), c_void_p]
-        L.mka_ceiling_mfma.restype = ctypes.c_int
-        L.mka_ceiling_mfma.argtypes = [c_void_p, c_int32, c_int32, POINTER(ctypes.c_double), c_void_p]
-        L.mka_ceiling_read.restype = ctypes.c_int
-        L.mka_ceiling_read.argtypes = [c_void_p, c_size_t, c_void_p, c_void_p]
         L.mka_fused_attn_bwd.restype = ctypes.c_int
         L.mka_fused_attn_bwd.argtypes = [c_void_p, c_void_p, POINTER(_P3), POINTER(_P3), c_void_p,
                                          c_void_p, c_void_p, c_void_p, c_void_p, POINTER(_P3),
@@ -142,6 +138,21 @@ def _dev_check(*ts):
                 raise ValueError("tensors must be contiguous")
 
 
+def _f32_check(**ts):
+    """Gates, LSE and router weights are float32 at the boundary whatever the tensor dtype."""
+    for name, t in ts.items():
+        if t is not None and t.dtype != torch.float32:
+            raise TypeError(f"{name} must be float32, got {t.dtype}")
+
+
+def _same_dtype(ref, **ts):
+    """Q, K_l, V_l, O, dO and the caches share one element type (the shape's `dtype`)."""
+    for name, t in ts.items():
+        for x in (t if isinstance(t, (list, tuple)) else [t]):
+            if x is not None and x.dtype != ref.dtype:
+                raise TypeError(f"{name} must have the dtype of the queries ({ref.dtype}), got {x.dtype}")
+
+
 def _shape(Q, S, len3, causal, scale) -> MkaShape:
     B, H, Tq, d = Q.shape
     s = MkaShape()
@@ -168,6 +179,7 @@ def mka_route(Q, W_r, b_r=None, S=None, G=None, want_idx=True):
     """Router gates (Alg. 2 step 5).  Returns (G [B,H,S,3] f32, idx [B,H,Tq] int32 or None).
     `G` may be an existing gate tensor whose rows S-Tq.. are overwritten."""
     _dev_check(Q, W_r, b_r, G)
+    _f32_check(W_r=W_r, b_r=b_r, G=G)
     B, H, Tq, d = Q.shape
     S = Tq if S is None else S
     if G is None:
@@ -186,6 +198,7 @@ def mka_route_variant(Q, W_r, b_r=None, mode=MKA_ROUTE_SOFT, S=None, G=None, wan
     """Gates of the routing ablation (soft / fixed 1/3 / hard top-2 / hard top-1).  Returns
     (G [B,H,S,3] f32, idx [B,H,Tq] int32 or None); arguments as for mka_route."""
     _dev_check(Q, W_r, b_r, G)
+    _f32_check(W_r=W_r, b_r=b_r, G=G)
     B, H, Tq, d = Q.shape
     S = Tq if S is None else S
     if G is None:
@@ -205,7 +218,9 @@ def mka_fused_attn_fwd(Q, K, V, W_r=None, b_r=None, G=None, len3=None, causal=Tr
     `workspace`: uint8 device tensor handed to the library as it is.  Without one, `materialise`
     picks its size: None = what the library recommends for the shape, True = enough for the
     materialised route, False = none (folded route)."""
-    _dev_check(Q, W_r, b_r, G, *K, *V)
+    _dev_check(Q, W_r, b_r, G, O, LSE, *K, *V)
+    _f32_check(W_r=W_r, b_r=b_r, G=G, LSE=LSE)
+    _same_dtype(Q, K=K, V=V, O=O)
     B, H, Tq, d = Q.shape
     ref = next(k for k in K if k is not None)
     S = ref.shape[2]
@@ -238,9 +253,11 @@ def mka_fused_attn_decode(q, k_new, v_new, Kc, Vc, Gc, len3, W_r, b_r=None, scal
                           n_splits=0, workspace=None, O=None, LSE=None, idx=None, want_lse=True,
                           want_idx=True, routing=0):
     """One decode step; caches and `len3` (a python list of 3 ints) are updated in place.
-    `routing`: MKA_ROUTE_* of the new slot's gate (hard modes read only the levels whose cached
+    W_r None: the new slot's gate row in Gc is the caller's (fused-cache decode).  `routing`: MKA_ROUTE_* of the new slot's gate (hard modes read only the levels whose cached
     gate is not zero).  Returns (O [B,H,1,d], LSE [B,H] or None, idx [B,H] or None)."""
-    _dev_check(q, W_r, b_r, Gc, *k_new, *v_new, *Kc, *Vc)
+    _dev_check(q, W_r, b_r, Gc, O, LSE, *k_new, *v_new, *Kc, *Vc)
+    _f32_check(W_r=W_r, b_r=b_r, Gc=Gc, LSE=LSE)
+    _same_dtype(q, k_new=k_new, v_new=v_new, Kc=Kc, Vc=Vc, O=O)
     B, H, _, d = q.shape
     s = MkaDecodeShape()
     s.B, s.H, s.d = B, H, d
@@ -259,7 +276,7 @@ def mka_fused_attn_decode(q, k_new, v_new, Kc, Vc, Gc, len3, W_r, b_r=None, scal
         O = torch.empty_like(q)
     if LSE is None and want_lse:
         LSE = torch.empty((B, H), dtype=torch.float32, device=q.device)
-    if idx is None and want_idx:
+    if idx is None and want_idx and W_r is not None:
         idx = torch.empty((B, H), dtype=torch.int32, device=q.device)
     ln = (c_int32 * 3)(*[int(x) for x in len3])
     kn, vn, kc, vc = _p3(k_new), _p3(v_new), _p3(Kc), _p3(Vc)
@@ -277,6 +294,8 @@ def mka_fused_attn_bwd(dO, Q, K, V, G, O, LSE, W_r=None, len3=None, causal=True,
                        workspace=None, grads_for=(True, True, True)):
     """Backward of the forward.  Returns dict(dQ, dK[3], dV[3], dW_r, db_r)."""
     _dev_check(dO, Q, G, O, LSE, W_r, *K, *V)
+    _f32_check(W_r=W_r, G=G, LSE=LSE)
+    _same_dtype(Q, dO=dO, O=O, K=K, V=V)
     B, H, Tq, d = Q.shape
     S = G.shape[2]
     s = _shape(Q, S, len3, causal, scale)
@@ -301,7 +320,9 @@ def mka_fused_attn_bwd(dO, Q, K, V, G, O, LSE, W_r=None, len3=None, causal=True,
 def mka_fuse_kv(K, V, G, len3=None, Kf=None, Vf=None):
     """Route-fusion materialised (Alg. 2 steps 6-7): returns (Kf, Vf), bf16 [B,H,S,d]."""
     _dev_check(G, Kf, Vf, *K, *V)
+    _f32_check(G=G)
     ref = next(k for k in K if k is not None)
+    _same_dtype(ref, K=K, V=V, Kf=Kf, Vf=Vf)
     B, H, S, d = ref.shape
     if Kf is None:
         Kf = torch.empty_like(ref)
@@ -324,7 +345,9 @@ def mka_mixture_attn_fwd(Q, K, V, G=None, causal=True, scale=1.0, want_lse=True,
     """Gated mixture of exponentiated scores over up to three memories of their own lengths
     (section "Recursive MKA with Online Softmax"); G [B,H,Tq,3] gates of the query rows or None.
     Returns (O, LSE)."""
-    _dev_check(Q, G, *K, *V)
+    _dev_check(Q, G, O, LSE, *K, *V)
+    _f32_check(G=G, LSE=LSE)
+    _same_dtype(Q, K=K, V=V, O=O)
     B, H, Tq, d = Q.shape
     len3 = [0 if k is None else k.shape[2] for k in K]
     if O is None:
@@ -341,7 +364,9 @@ def mka_mixture_attn_fwd(Q, K, V, G=None, causal=True, scale=1.0, want_lse=True,
 def mka_full_attn_fwd(Q, K, V, G, causal=True, scale=1.0, O=None, workspace=None):
     """Symbolic (full) MKA, Alg. 1: one attention per memory, outputs mixed with the gates of the
     query rows G [B,H,Tq,3].  Returns O."""
-    _dev_check(Q, G, *K, *V)
+    _dev_check(Q, G, O, *K, *V)
+    _f32_check(G=G)
+    _same_dtype(Q, K=K, V=V, O=O)
     B, H, Tq, d = Q.shape
     len3 = [0 if k is None else k.shape[2] for k in K]
     if O is None:
@@ -361,6 +386,9 @@ def mka_paged_fused_decode(q, Kpool, Vpool, table, seq_len, scale=1.0, n_splits=
     """One decode step over the fused KV cache in a paged pool [n_pages,H,P,d]; table [B,max_pages]
     int32 and seq_len [B] int32 on the device.  Returns (O [B,H,1,d], LSE [B,H] or None)."""
     _dev_check(q, Kpool, Vpool, table, seq_len, O)
+    _same_dtype(q, Kpool=Kpool, Vpool=Vpool, O=O)
+    if table.dtype != torch.int32 or seq_len.dtype != torch.int32:
+        raise TypeError("table and seq_len must be int32")
     B, H, _, d = q.shape
     s = MkaPagedShape()
     s.B, s.H, s.d = B, H, d
@@ -389,20 +417,3 @@ def mka_prefix_mean(X, M=None, workspace=None):
     _check(lib().mka_prefix_mean(_ptr(X), _ptr(M), ctypes.byref(s), _ptr(workspace),
                                  workspace.numel(), _stream()), "mka_prefix_mean")
     return M
-
-
-def mka_ceiling_mfma(out, workgroups: int, iters: int) -> float:
-    """Enqueue the pure-MFMA loop (include/mka.h); returns the flops of the launch."""
-    _dev_check(out)
-    fl = ctypes.c_double(0.0)
-    _check(lib().mka_ceiling_mfma(_ptr(out), workgroups, iters, ctypes.byref(fl), _stream()),
-           "mka_ceiling_mfma")
-    return fl.value
-
-
-def mka_ceiling_read(src, out=None) -> int:
-    """Enqueue the streaming read of `src` (include/mka.h); returns the bytes it reads."""
-    _dev_check(src, out)
-    nbytes = src.numel() * src.element_size()
-    _check(lib().mka_ceiling_read(_ptr(src), nbytes, _ptr(out), _stream()), "mka_ceiling_read")
-    return nbytes

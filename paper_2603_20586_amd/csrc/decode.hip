@@ -4,7 +4,8 @@
 // Three launches:
 //   append   writes the new token's K/V entries into slot j_new of the supplied levels and the
 //            new slot's gate (router on q, fp64 fma chain in ascending k, as in the router
-//            kernel) into the gate cache;
+//            kernel) into the gate cache; without router weights the gate row is left as the
+//            caller wrote it;
 //   split    grid (n_splits, B*H): a workgroup streams its slice of the six raw caches and the
 //            gate cache exactly once with 16-byte loads (LPR lanes cover one slot's row, so a
 //            wave instruction covers 64/LPR slots), mixes the three levels with the slot's
@@ -82,6 +83,7 @@ __global__ __launch_bounds__(64) void decode_append_kernel(
       }
     }
   }
+  if (!W_r) return;  // the new slot's gate row is the caller's (uniform branch)
   if (lane < 3) {
     double acc = b_r ? (double)b_r[lane] : 0.0;
     for (int k = 0; k < D; ++k)

@@ -308,6 +308,7 @@ mka_status mka_paged_fused_decode(const void* q, const void* Kpool, const void* 
       (reinterpret_cast<uintptr_t>(table) & 3u) || (reinterpret_cast<uintptr_t>(seq_len) & 3u) ||
       (reinterpret_cast<uintptr_t>(LSE) & 3u))
     return MKA_ERR_ALIGN;
+  if ((long long)s->B * s->H > 65535) return MKA_ERR_UNSUPPORTED;  // grid.y
   const int BH = s->B * s->H;
   if (BH == 0) return MKA_OK;
   int ns = s->n_splits ? s->n_splits : mka::decode_auto_splits(BH, s->max_pages * P);
@@ -342,12 +343,14 @@ mka_status mka_prefix_mean(const void* X, void* M, const mka_shape* shape, void*
              : MKA_ERR_LAUNCH;
 }
 
-mka_status mka_fused_attn_decode(const void* q, const void* const k_new[3],
+// Argument validation and append bookkeeping shared by the two decode entry points: fills `a`
+// (everything but the partials buffer and the final split count) and sets *noop for a valid
+// problem without heads.  Touches no device.
+static mka_status decode_prepare(const void* q, const void* const k_new[3],
                                  const void* const v_new[3], void* const Kc[3], void* const Vc[3],
-                                 float* Gc, int32_t len[3], const float* W_r, const float* b_r,
-                                 void* O, float* LSE, int32_t* idx_out,
-                                 const mka_decode_shape* s, void* workspace, size_t workspace_bytes,
-                                 void* stream) {
+                                 float* Gc, const int32_t len[3], const float* W_r,
+                                 const float* b_r, void* O, float* LSE, int32_t* idx_out,
+                                 const mka_decode_shape* s, mka::DecodeArgs* out, bool* noop) {
   if (!s) return MKA_ERR_NULL;
   if (s->dtype != MKA_F32 && s->dtype != MKA_BF16) return MKA_ERR_DTYPE;
   if (s->B < 0 || s->H < 0 || s->d <= 0 || s->capG <= 0 || s->n_splits < 0) return MKA_ERR_SHAPE;
@@ -355,16 +358,21 @@ mka_status mka_fused_attn_decode(const void* q, const void* const k_new[3],
   if (!(s->scale >= 0.f) || isinf(s->scale)) return MKA_ERR_UNSUPPORTED;
   if (s->n_splits > mka::kMaxSplits) return MKA_ERR_UNSUPPORTED;
   if (s->routing < MKA_ROUTE_SOFT || s->routing > MKA_ROUTE_TOP1) return MKA_ERR_UNSUPPORTED;
-  if (!q || !k_new || !v_new || !Kc || !Vc || !Gc || !len || !W_r || !O) return MKA_ERR_NULL;
+  if (!q || !k_new || !v_new || !Kc || !Vc || !Gc || !len || !O) return MKA_ERR_NULL;
+  if (idx_out && !W_r) return MKA_ERR_NULL;  // the argmax needs the router
   const long long bh = (long long)s->B * s->H;
   if (bh > 65535) return MKA_ERR_UNSUPPORTED;  // grid.y
+  // the kernels address a (batch, head)'s cache rows with 32-bit byte offsets
+  const long long row_bytes = (long long)s->d * (s->dtype == MKA_BF16 ? 2 : 4);
+  if ((long long)s->capG * 12 >= (1ll << 32)) return MKA_ERR_UNSUPPORTED;
   int j_new = 0;
   for (int l = 0; l < 3; ++l) {
     if (s->cap[l] < 0 || len[l] < 0 || len[l] > s->cap[l]) return MKA_ERR_SHAPE;
+    if ((long long)s->cap[l] * row_bytes >= (1ll << 32)) return MKA_ERR_UNSUPPORTED;
     if (len[l] > j_new) j_new = len[l];
   }
   if (j_new >= s->capG) return MKA_ERR_SHAPE;
-  mka::DecodeArgs a;
+  mka::DecodeArgs& a = *out;
   bool any = false;
   for (int l = 0; l < 3; ++l) {
     const bool app = k_new[l] && v_new[l];
@@ -386,15 +394,34 @@ mka_status mka_fused_attn_decode(const void* q, const void* const k_new[3],
   }
   if (!any) return MKA_ERR_SHAPE;
   if (!aligned16(q) || !aligned16(O) || (reinterpret_cast<uintptr_t>(Gc) & 3u)) return MKA_ERR_ALIGN;
-  if (bh == 0) return MKA_OK;
+  *noop = bh == 0;
   a.S = j_new + 1;
-  a.n_splits = s->n_splits > 0 ? s->n_splits : mka::decode_auto_splits((int)bh, a.S);
-  const size_t need = (size_t)bh * a.n_splits * (size_t)(s->d + 2) * sizeof(float);
-  if (!workspace || workspace_bytes < need) return MKA_ERR_WORKSPACE;
-  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MKA_ERR_ALIGN;
+  a.n_splits = s->n_splits > 0 ? s->n_splits : (bh > 0 ? mka::decode_auto_splits((int)bh, a.S) : 1);
   a.q = q; a.Gc = Gc; a.W_r = W_r; a.b_r = b_r; a.O = O; a.LSE = LSE; a.idx = idx_out;
   a.BH = (int)bh; a.d = s->d; a.capG = s->capG; a.j_new = j_new;
   a.scale = s->scale; a.bf16 = s->dtype == MKA_BF16; a.routing = s->routing;
+  a.partial = nullptr;
+  return MKA_OK;
+}
+
+static size_t decode_partial_bytes(const mka::DecodeArgs& a) {
+  return (size_t)a.BH * a.n_splits * (size_t)(a.d + 2) * sizeof(float);
+}
+
+mka_status mka_fused_attn_decode(const void* q, const void* const k_new[3],
+                                 const void* const v_new[3], void* const Kc[3], void* const Vc[3],
+                                 float* Gc, int32_t len[3], const float* W_r, const float* b_r,
+                                 void* O, float* LSE, int32_t* idx_out,
+                                 const mka_decode_shape* s, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
+  mka::DecodeArgs a;
+  bool noop = false;
+  const mka_status st =
+      decode_prepare(q, k_new, v_new, Kc, Vc, Gc, len, W_r, b_r, O, LSE, idx_out, s, &a, &noop);
+  if (st != MKA_OK) return st;
+  if (noop) return MKA_OK;
+  if (!workspace || workspace_bytes < decode_partial_bytes(a)) return MKA_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MKA_ERR_ALIGN;
   a.partial = static_cast<float*>(workspace);
   if (mka::launch_decode(a, (hipStream_t)stream) != hipSuccess) return MKA_ERR_LAUNCH;
   for (int l = 0; l < 3; ++l) len[l] = a.len[l];
@@ -425,6 +452,7 @@ mka_status mka_fused_attn_bwd(const void* dO, const void* Q, const void* const K
     a.dK[l] = dK[l];
     a.dV[l] = dV[l];
   }
+  if (!a.K[0] && !a.K[1] && !a.K[2]) return MKA_ERR_NULL;  // at least one memory level
   if (empty) return MKA_OK;
   const int BH = shape->B * shape->H;
   const size_t need = mka::bwd_workspace_bytes(BH, shape->Tq, shape->S, shape->d);

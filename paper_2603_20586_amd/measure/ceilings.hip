@@ -1,17 +1,18 @@
-// Measured ceilings of the part, to quote beside the vendor peaks: a pure 32x32x16 bf16 MFMA
-// loop (no memory traffic) and a streaming read of a large buffer with 16-byte non-temporal
-// loads.  Neither is part of the method; they size the rooflines that the attention kernels
-// are held against (sustained clocks under matrix load sit below the datasheet figure).
+// Reference micro-benchmarks of the part, to quote beside the vendor peaks: a pure 32x32x16 bf16
+// MFMA loop (no memory traffic) and a streaming read of a large buffer.  Neither is part of the
+// method and neither is linked into libmka.so: they form libmka_measure.so, which only bench.py
+// loads (sustained clocks under matrix load sit below the datasheet figure, and HBM delivers
+// less than its pin rate, so the rooflines are quoted against both).
 #include <hip/hip_runtime.h>
 
-#include "../../include/mka.h"
-#include "mka_dev.h"
+#include "../../include/mka_measure.h"
+#include "../csrc/mka_dev.h"
 
 namespace mka {
 namespace {
 
 // 8 waves per workgroup, 4 independent accumulator chains per wave
-__global__ __launch_bounds__(512) void ceiling_mfma_kernel(float* out, int iters) {
+__global__ __launch_bounds__(512) void measure_mfma_kernel(float* out, int iters) {
   bf16x8 a, b;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
@@ -35,18 +36,26 @@ __global__ __launch_bounds__(512) void ceiling_mfma_kernel(float* out, int iters
   if (out) out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
-__global__ __launch_bounds__(256) void ceiling_read_kernel(const uint4* __restrict__ src,
-                                                           unsigned* out, long n_chunks) {
-  constexpr int U = 8;
-  long i = (long)blockIdx.x * 256 * U + threadIdx.x;
-  const long stride = (long)gridDim.x * 256 * U;
+// Six streams (the buffer cut in six equal parts), each workgroup walks its slice of all six at
+// once: per trip a lane issues 4 x 6 independent 16-byte non-temporal loads before the first use,
+// 16 lanes cover 256 consecutive bytes - the decode kernel's traffic without its arithmetic.
+__global__ __launch_bounds__(256) void measure_read_kernel(const uint4* __restrict__ src,
+                                                           unsigned* out, long per_stream,
+                                                           long chunk) {
+  constexpr int U = 4, NS = 6;
+  const long lo = (long)blockIdx.x * chunk;
+  const long hi = lo + chunk < per_stream ? lo + chunk : per_stream;
   unsigned acc = 0;
-  for (; i + 256 * (U - 1) < n_chunks; i += stride) {
-    uint4 v[U];
+  for (long i = lo + threadIdx.x; i + 256 * (U - 1) < hi; i += 256 * U) {
+    uint4 v[U][NS];
 #pragma unroll
-    for (int u = 0; u < U; ++u) v[u] = load16_stream(src + i + 256 * u);
+    for (int u = 0; u < U; ++u)
 #pragma unroll
-    for (int u = 0; u < U; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+      for (int s = 0; s < NS; ++s) v[u][s] = load16_stream(src + s * per_stream + i + 256 * u);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int s = 0; s < NS; ++s) acc ^= v[u][s].x ^ v[u][s].y ^ v[u][s].z ^ v[u][s].w;
   }
   if (acc == 0x9e3779b9u && out) out[0] = acc;  // keeps the loads alive, practically never taken
 }
@@ -54,20 +63,26 @@ __global__ __launch_bounds__(256) void ceiling_read_kernel(const uint4* __restri
 }  // namespace
 }  // namespace mka
 
-extern "C" mka_status mka_ceiling_mfma(float* out, int32_t workgroups, int32_t iters,
-                                        double* flops, void* stream) {
-  if (workgroups <= 0 || iters <= 0 || !out) return MKA_ERR_SHAPE;
-  hipLaunchKernelGGL(mka::ceiling_mfma_kernel, dim3((unsigned)workgroups), dim3(512), 0,
+extern "C" int32_t mka_measure_mfma_loop(float* out, int32_t workgroups, int32_t iters,
+                                         double* flops, void* stream) {
+  if (workgroups <= 0 || iters <= 0 || !out) return 2;
+  hipLaunchKernelGGL(mka::measure_mfma_kernel, dim3((unsigned)workgroups), dim3(512), 0,
                      static_cast<hipStream_t>(stream), out, iters);
   if (flops) *flops = (double)workgroups * 8.0 * iters * 4.0 * 32768.0;  // 2*32*32*16 per MFMA
-  return hipGetLastError() == hipSuccess ? MKA_OK : MKA_ERR_LAUNCH;
+  return hipGetLastError() == hipSuccess ? 0 : 7;
 }
 
-extern "C" mka_status mka_ceiling_read(const void* src, size_t bytes, uint32_t* out, void* stream) {
-  if (!src || bytes < 16 * 256 * 8) return MKA_ERR_SHAPE;
-  if (reinterpret_cast<uintptr_t>(src) & 15) return MKA_ERR_ALIGN;
-  hipLaunchKernelGGL(mka::ceiling_read_kernel, dim3(8192), dim3(256), 0,
+extern "C" int32_t mka_measure_stream_read(const void* src, size_t bytes, uint32_t* out,
+                                           void* stream) {
+  if (!src || bytes < (1u << 20)) return 2;
+  if (reinterpret_cast<uintptr_t>(src) & 15) return 4;
+  // whole 1024-chunk trips per stream (a tail of < 96 KiB is not read), 2048 workgroups
+  const long per_stream = (long)(bytes / 16 / 6) / 1024 * 1024;
+  const int wgs = 2048;
+  long chunk = (per_stream + wgs - 1) / wgs;
+  chunk = (chunk + 1023) / 1024 * 1024;
+  hipLaunchKernelGGL(mka::measure_read_kernel, dim3(wgs), dim3(256), 0,
                      static_cast<hipStream_t>(stream), static_cast<const uint4*>(src), out,
-                     (long)(bytes / 16));
-  return hipGetLastError() == hipSuccess ? MKA_OK : MKA_ERR_LAUNCH;
+                     per_stream, chunk);
+  return hipGetLastError() == hipSuccess ? 0 : 7;
 }

@@ -1,9 +1,9 @@
 """Turn rocprofv3 CSV output into the short text summaries kept under profiles/.
 
-    python -m paper_2603_20586_amd.prof_summary stats  <kernel_stats.csv>  <out.txt>  "<command>"
-    python -m paper_2603_20586_amd.prof_summary trace  <kernel_trace.csv>  <out.txt>  "<command>"
-    python -m paper_2603_20586_amd.prof_summary pmc    <counter_collection.csv> <out.txt> "<command>"
-    python -m paper_2603_20586_amd.prof_summary traffic <fetch_summary.txt> <write_summary.txt> <traffic.json>
+    python -m paper_2603_20586_amd.measure.prof_summary stats  <kernel_stats.csv>  <out.txt>  "<command>"
+    python -m paper_2603_20586_amd.measure.prof_summary trace  <kernel_trace.csv>  <out.txt>  "<command>"
+    python -m paper_2603_20586_amd.measure.prof_summary pmc    <counter_collection.csv> <out.txt> "<command>"
+    python -m paper_2603_20586_amd.measure.prof_summary traffic <fetch_summary.txt> <write_summary.txt> <traffic.json>
 
 `traffic`: scaled FETCH_SIZE + WRITE_SIZE of the dominant kernel of each roofline line of
 `bench.py` (picked by kernel name and workgroup count) -> HBM bytes per launch, as JSON.
