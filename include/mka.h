@@ -186,6 +186,28 @@ mka_status mka_fused_attn_decode(const void* q, const void* const k_new[3],
                                  const mka_decode_shape* shape, void* workspace,
                                  size_t workspace_bytes, void* stream);
 
+/* mka_fused_attn_decode for callers that cannot allocate or hand over device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * results and errors as mka_fused_attn_decode, without the workspace: the split-K partials live
+ * in a fixed buffer of MKA_DECODE_STATIC_SCRATCH_BYTES inside the library's device image (every
+ * GPU the library runs on holds its own copy until the process ends).  The call allocates
+ * nothing and frees nothing.
+ *  - limit: B * H * n_splits * (d + 2) * 4 bytes must fit the buffer.  With n_splits = 0 the
+ *    library lowers its own split count until it fits; an explicit n_splits that does not fit,
+ *    or a B * H that does not fit with one split, gives MKA_ERR_WORKSPACE and nothing runs.
+ *    (Config C4 - B 16, H 32, d 128, 4 splits - needs 1.02 MiB.)
+ *  - every call on a GPU shares that GPU's buffer and the buffer keeps the last call's contents:
+ *    each call overwrites the partials it reads (nothing has to start at zero), but calls whose
+ *    execution overlaps on one GPU - different streams, or a captured graph replayed while
+ *    another call runs - race on it.  Serialise them on one stream. */
+#define MKA_DECODE_STATIC_SCRATCH_BYTES (8u << 20)
+mka_status mka_fused_attn_decode_static(const void* q, const void* const k_new[3],
+                                        const void* const v_new[3], void* const Kc[3],
+                                        void* const Vc[3], float* Gc, int32_t len[3],
+                                        const float* W_r, const float* b_r, void* O, float* LSE,
+                                        int32_t* idx_out, const mka_decode_shape* shape,
+                                        void* stream);
+
 /* Backward of mka_fused_attn_fwd (chain rule through Alg. 2 steps 5-9) for the
  * loss sum(dO * O): gradients w.r.t. Q, every K_l, V_l, and the router.
  *   dO,Q,O in  [B,H,Tq,d];  K,V in three [B,H,S,d];  G in [B,H,S,3];  LSE in [B,H,Tq]

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     lib_path,
     mka_fused_attn_bwd,
     mka_fused_attn_decode,
+    mka_fused_attn_decode_static,
     mka_fuse_kv,
     mka_full_attn_fwd,
     mka_fused_attn_fwd,

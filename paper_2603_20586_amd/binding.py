@@ -85,6 +85,11 @@ def lib() -> ctypes.CDLL:
                                             POINTER(_P3), c_void_p, POINTER(c_int32 * 3),
                                             c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                             POINTER(MkaDecodeShape), c_void_p, c_size_t, c_void_p]
+        L.mka_fused_attn_decode_static.restype = ctypes.c_int
+        L.mka_fused_attn_decode_static.argtypes = [c_void_p, POINTER(_P3), POINTER(_P3), POINTER(_P3),
+                                                   POINTER(_P3), c_void_p, POINTER(c_int32 * 3),
+                                                   c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                                   POINTER(MkaDecodeShape), c_void_p]
         L.mka_fuse_kv.restype = ctypes.c_int
         L.mka_fuse_kv.argtypes = [POINTER(_P3), POINTER(_P3), c_void_p, c_void_p, c_void_p,
                                   POINTER(MkaShape), c_void_p]
@@ -288,6 +293,33 @@ def mka_fused_attn_decode(q, k_new, v_new, Kc, Vc, Gc, len3, W_r, b_r=None, scal
     for l in range(3):
         len3[l] = int(ln[l])
     return O, LSE, idx
+
+
+def mka_fused_attn_decode_static(q, k_new, v_new, Kc, Vc, Gc, len3, W_r, b_r, O, LSE=None, idx=None,
+                                 scale=1.0, n_splits=0, routing=0):
+    """mka_fused_attn_decode through the entry point that allocates nothing: the split-K partials
+    live in the library's fixed device buffer, and every output tensor is the caller's (nothing
+    is allocated here either).  Returns None; caches, `len3`, O, LSE, idx are updated in place."""
+    _dev_check(q, W_r, b_r, Gc, O, LSE, idx, *k_new, *v_new, *Kc, *Vc)
+    _f32_check(W_r=W_r, b_r=b_r, Gc=Gc, LSE=LSE)
+    _same_dtype(q, k_new=k_new, v_new=v_new, Kc=Kc, Vc=Vc, O=O)
+    B, H, _, d = q.shape
+    s = MkaDecodeShape()
+    s.B, s.H, s.d = B, H, d
+    for l in range(3):
+        s.cap[l] = int(Kc[l].shape[2]) if Kc[l] is not None else 0
+    s.capG = int(Gc.shape[2])
+    s.dtype = _dtype_code(q)
+    s.n_splits, s.scale, s.routing = int(n_splits), float(scale), int(routing)
+    ln = (c_int32 * 3)(*[int(x) for x in len3])
+    kn, vn, kc, vc = _p3(k_new), _p3(v_new), _p3(Kc), _p3(Vc)
+    _check(lib().mka_fused_attn_decode_static(_ptr(q), ctypes.byref(kn), ctypes.byref(vn),
+                                              ctypes.byref(kc), ctypes.byref(vc), _ptr(Gc),
+                                              ctypes.byref(ln), _ptr(W_r), _ptr(b_r), _ptr(O),
+                                              _ptr(LSE), _ptr(idx), ctypes.byref(s), _stream()),
+           "mka_fused_attn_decode_static")
+    for l in range(3):
+        len3[l] = int(ln[l])
 
 
 def mka_fused_attn_bwd(dO, Q, K, V, G, O, LSE, W_r=None, len3=None, causal=True, scale=1.0,

@@ -3,8 +3,16 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "../../include/mka.h"
 #include "mka_internal.h"
+
+// Split-K partials of mka_fused_attn_decode_static: a fixed buffer in every GPU's memory image,
+// held until the process ends.  On the host this name is only a handle for hipGetSymbolAddress;
+// the address that kernels and copies may use is looked up once per device (each GPU has its
+// own copy of the array at its own address) and is the only thing host code passes on.
+static __device__ __align__(256) unsigned char scratch[MKA_DECODE_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -30,6 +38,26 @@ mka_status check_shape(const mka_shape* s, bool* empty) {
 }
 
 size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+constexpr size_t kStaticScratchBytes = MKA_DECODE_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` per device, null until looked up
+std::mutex g_scratch_mutex;
+
+// Device address of the scratch array on the current device (looked up on first use).
+mka_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MKA_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p)
+      return MKA_ERR_LAUNCH;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MKA_OK;
+}
 
 }  // namespace
 
@@ -423,6 +451,31 @@ mka_status mka_fused_attn_decode(const void* q, const void* const k_new[3],
   if (!workspace || workspace_bytes < decode_partial_bytes(a)) return MKA_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MKA_ERR_ALIGN;
   a.partial = static_cast<float*>(workspace);
+  if (mka::launch_decode(a, (hipStream_t)stream) != hipSuccess) return MKA_ERR_LAUNCH;
+  for (int l = 0; l < 3; ++l) len[l] = a.len[l];
+  return MKA_OK;
+}
+
+mka_status mka_fused_attn_decode_static(const void* q, const void* const k_new[3],
+                                        const void* const v_new[3], void* const Kc[3],
+                                        void* const Vc[3], float* Gc, int32_t len[3],
+                                        const float* W_r, const float* b_r, void* O, float* LSE,
+                                        int32_t* idx_out, const mka_decode_shape* s, void* stream) {
+  mka::DecodeArgs a;
+  bool noop = false;
+  const mka_status st =
+      decode_prepare(q, k_new, v_new, Kc, Vc, Gc, len, W_r, b_r, O, LSE, idx_out, s, &a, &noop);
+  if (st != MKA_OK) return st;
+  if (noop) return MKA_OK;
+  // the library's own split count is lowered until the partials fit the fixed buffer; a count
+  // the caller fixed, or a batch that does not fit with one split, is refused
+  if (s->n_splits == 0)
+    while (a.n_splits > 1 && decode_partial_bytes(a) > kStaticScratchBytes) --a.n_splits;
+  if (decode_partial_bytes(a) > kStaticScratchBytes) return MKA_ERR_WORKSPACE;
+  void* buf = nullptr;
+  const mka_status sb = static_scratch(&buf);  // this device's copy of `scratch`
+  if (sb != MKA_OK) return sb;
+  a.partial = static_cast<float*>(buf);
   if (mka::launch_decode(a, (hipStream_t)stream) != hipSuccess) return MKA_ERR_LAUNCH;
   for (int l = 0; l < 3; ++l) len[l] = a.len[l];
   return MKA_OK;

@@ -158,6 +158,38 @@ def test_decode_rejects_bad_arguments(m):
     assert rc == 3 and ln == [8, 8, 8]                    # lengths untouched on error
 
 
+def test_static_decode_validates_like_decode_and_enforces_its_size_limit(m):
+    """The entry point that allocates nothing: same argument checks as mka_fused_attn_decode, in
+    the same order, plus the limit of its fixed scratch buffer - all before any device is
+    touched."""
+    from paper_2603_20586_amd.binding import MkaDecodeShape, _P3
+
+    L = m.lib()
+
+    def call(B=1, H=2, d=64, n_splits=0, len3=(8, 8, 8), cap=(16, 8, 8), q=FAKE, dtype=1):
+        s = MkaDecodeShape()
+        s.B, s.H, s.d, s.capG, s.dtype, s.n_splits, s.scale = B, H, d, 16, dtype, n_splits, 0.125
+        for i in range(3):
+            s.cap[i] = cap[i]
+        ln = (ctypes.c_int32 * 3)(*len3)
+        kn, kc = _P3(FAKE, None, None), _P3(FAKE, FAKE, FAKE)
+        return L.mka_fused_attn_decode_static(q, ctypes.byref(kn), ctypes.byref(kn), ctypes.byref(kc),
+                                              ctypes.byref(kc), FAKE, ctypes.byref(ln), FAKE, None,
+                                              FAKE, None, None, ctypes.byref(s), None)
+
+    assert L.mka_fused_attn_decode_static(FAKE, None, None, None, None, FAKE, None, FAKE, None, FAKE,
+                                          None, None, None, None) == 1
+    assert call(dtype=9) == 3
+    assert call(d=100) == 6
+    assert call(q=None) == 1
+    assert call(q=FAKE + 4) == 4
+    assert call(len3=(8, 9, 8)) == 2                       # a lagging level cannot be appended to
+    assert call(B=0) == 0                                  # no heads: nothing to do
+    # 8 MiB of partials: 4096 heads x 66 floats x 4 B = 1.03 MiB per split
+    assert call(B=64, H=64, n_splits=8) == 5               # 8.25 MiB: refused
+    assert call(B=255, H=257) == 5                         # 65 535 heads do not fit even unsplit
+
+
 def test_measure_helpers_reject_bad_arguments_on_the_host(m):
     import ctypes
     from paper_2603_20586_amd import measure
