@@ -118,7 +118,7 @@ __device__ __forceinline__ void bwd_main_tile(
     const float* __restrict__ LSE2p, const float* __restrict__ Dp, int Tqp, bf16* __restrict__ dK0,
     bf16* __restrict__ dK1, bf16* __restrict__ dK2, bf16* __restrict__ dV0, bf16* __restrict__ dV1,
     bf16* __restrict__ dV2, bf16* __restrict__ Kf_out, bf16* __restrict__ Vf_out,
-    float* __restrict__ dgate, int Tq, int S,
+    unsigned char* __restrict__ dS_out, int n_kvt, float* __restrict__ dgate, int Tq, int S,
     int len0, int len1, int len2, int causal, float c, float tau, int jt, long bh) {
   using L = BwdSmem<D>;
   constexpr int BR = L::BR, RSTR = L::RSTR;
@@ -242,10 +242,10 @@ __device__ __forceinline__ void bwd_main_tile(
         const uint4 pk = pack8(kf), pv = pack8(vf);
         *reinterpret_cast<uint4*>(&sKrow[(sg * 4 + u) * RSTR + cc * 8]) = pk;
         *reinterpret_cast<uint4*>(&sVrow[(sg * 4 + u) * RSTR + cc * 8]) = pv;
-        if (in) {  // the fused stream, for the dQ kernel
+        if (in) {  // the fused stream, for the dQ kernel (Vf only if it recomputes dP)
           const long eoff = kvbase + (long)j * D + cc * 8;
           *reinterpret_cast<uint4*>(Kf_out + eoff) = pk;
-          *reinterpret_cast<uint4*>(Vf_out + eoff) = pv;
+          if (Vf_out) *reinterpret_cast<uint4*>(Vf_out + eoff) = pv;
         }
       }
     }
@@ -298,6 +298,14 @@ __device__ __forceinline__ void bwd_main_tile(
   auto pt_off = [&](int h) { return Rl * BR + 8 * ((2 * h + g + (Rl >> 1)) & 3); };
   bf16* sPbase = reinterpret_cast<bf16*>(lds + L::OFF_P);
 
+  // role K leaves dS of every (key tile, query tile) pair in the workspace for the dQ kernel: its
+  // two packed registers, 1 KiB per store instruction (block layout: see bwd_dqg_bf16.hip)
+  // ordered [head][group of 8 query tiles][key tile][slot half][tile in group][4 KiB]: the dQ
+  // kernel's workgroup (8 query tiles) then streams one contiguous 32 KiB run per 64 slots
+  unsigned char* ds_lane = nullptr;
+  const int n_qg = (n_qt + 7) / 8;
+  if (dS_out) ds_lane = dS_out + (sw >> 1) * 32768 + (sw & 1) * 2048 + li * 32 + g * 16;
+
   int b5 = 0;  // it % NSLOT
   for (int it = 0; it < n_tiles + 1; ++it) {
     request(it + 3, b5 + 3 >= L::NSLOT ? b5 + 3 - L::NSLOT : b5 + 3);
@@ -338,6 +346,13 @@ __device__ __forceinline__ void bwd_main_tile(
           const bf16x8 a1 = tr_frag(tb, db, 1);
           acc[db] = mfma32(a0, sB0, acc[db]);
           acc[db] = mfma32(a1, sB1, acc[db]);
+        }
+        if (ds_lane) {  // behind the MFMAs: the stores then do not delay their issue
+          __builtin_amdgcn_sched_barrier(0);
+          const int qtile = qt0 + k;
+          const size_t blk = (((size_t)bh * n_qg + (qtile >> 3)) * n_kvt + jt) * 65536 + (size_t)(qtile & 7) * 4096;
+          *reinterpret_cast<uint4*>(ds_lane + blk) = s0;
+          *reinterpret_cast<uint4*>(ds_lane + blk + 1024) = s1;
         }
       }
     } else {
@@ -505,7 +520,7 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
     const float* __restrict__ LSE2p, const float* __restrict__ Dp, int Tqp, bf16* __restrict__ dK0,
     bf16* __restrict__ dK1, bf16* __restrict__ dK2, bf16* __restrict__ dV0, bf16* __restrict__ dV1,
     bf16* __restrict__ dV2, bf16* __restrict__ Kf_out, bf16* __restrict__ Vf_out,
-    float* __restrict__ dgate, int Tq, int S,
+    unsigned char* __restrict__ dS_out, float* __restrict__ dgate, int Tq, int S,
     int len0, int len1, int len2, int causal, float c, float tau, int n_kvtiles, int BH,
     int pair) {
   // All KV tiles of one (batch, head) run on ONE XCD (block index = 8 * slot + xcd): they share
@@ -520,11 +535,13 @@ __global__ __launch_bounds__(512, 1) void bwd_main_kernel(
   const long bh = (long)(slot / n_first) * 8 + xcd;
   if (bh >= BH) return;
   bwd_main_tile<D>(dO, Q, K0, K1, K2, V0, V1, V2, G, LSE2p, Dp, Tqp, dK0, dK1, dK2, dV0, dV1, dV2,
-                   Kf_out, Vf_out, dgate, Tq, S, len0, len1, len2, causal, c, tau, jt0, bh);
+                   Kf_out, Vf_out, dS_out, n_kvtiles, dgate, Tq, S, len0, len1, len2, causal, c, tau,
+                   jt0, bh);
   if (pair && jt1 != jt0) {
     __syncthreads();  // the first tile's epilogue staging is dead
     bwd_main_tile<D>(dO, Q, K0, K1, K2, V0, V1, V2, G, LSE2p, Dp, Tqp, dK0, dK1, dK2, dV0, dV1, dV2,
-                     Kf_out, Vf_out, dgate, Tq, S, len0, len1, len2, causal, c, tau, jt1, bh);
+                     Kf_out, Vf_out, dS_out, n_kvtiles, dgate, Tq, S, len0, len1, len2, causal, c,
+                     tau, jt1, bh);
   }
 }
 
@@ -595,11 +612,25 @@ __global__ __launch_bounds__(256) void bwd_reduce_kernel(const float* __restrict
 
 size_t a256(size_t n) { return (n + 255) & ~(size_t)255; }
 
+// Stored score gradients (the dQ kernel then needs one product per pair instead of three): one
+// 8 KiB block per (128-slot key tile, 32-row query tile) of every head, the full rectangle (under
+// a causal mask about half of it is written and read).  Taken when it stays below this many bytes
+// in total and below 4 GiB per head (32-bit block offsets); C5 needs 4 GiB.
+constexpr size_t kDsCapBytes = (size_t)32 << 30;
+size_t ds_bytes(int BH, int Tq, int S) {
+  // query tiles padded to whole groups of 8 (one workgroup of the dQ kernel)
+  const size_t per_head = (size_t)((S + BCB - 1) / BCB) * (size_t)((Tq + 255) / 256) * 8 * 8192;
+  if (per_head >= ((size_t)1 << 32)) return 0;
+  const size_t all = per_head * (size_t)BH;
+  return all <= kDsCapBytes ? all : 0;
+}
+
 struct BwdWs {
-  size_t off_d, off_lse, off_dg, off_part, off_kf, off_vf, total;
+  size_t off_d, off_lse, off_dg, off_part, off_kf, off_vf, off_ds, total;
   int nparts, Tqp;
 };
-BwdWs carve(int BH, int Tq, int S, int d) {
+// with_ds: Kf, then the dS blocks (no Vf: the dQ kernel does not recompute dP); else Kf and Vf
+BwdWs carve(int BH, int Tq, int S, int d, bool with_ds) {
   BwdWs w;
   const size_t rows = (size_t)BH * Tq;
   w.nparts = (int)((rows + FIN_ROWS - 1) / FIN_ROWS);
@@ -611,21 +642,30 @@ BwdWs carve(int BH, int Tq, int S, int d) {
   w.off_part = w.off_dg + a256(rows * 3 * sizeof(float));
   w.off_kf = w.off_part + a256((size_t)w.nparts * (d * 3 + 3) * sizeof(float));
   w.off_vf = w.off_kf + a256((size_t)BH * S * d * sizeof(bf16));
-  w.total = w.off_vf + a256((size_t)BH * S * d * sizeof(bf16));
+  w.off_ds = w.off_vf;
+  const size_t vf_end = w.off_vf + a256((size_t)BH * S * d * sizeof(bf16));
+  const size_t ds_end = w.off_ds + a256(ds_bytes(BH, Tq, S));
+  // never below what the other route needs: a workspace sized for the stored gradients is
+  // accepted whichever route a later build picks
+  w.total = with_ds && ds_end > vf_end ? ds_end : vf_end;
   return w;
 }
 
 template <int D>
 hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
   using L = BwdSmem<D>;
-  const BwdWs w = carve(a.BH, a.Tq, a.S, D);
+  // the route with stored score gradients when the caller's workspace has room for them
+  const bool with_ds = ds_bytes(a.BH, a.Tq, a.S) > 0 &&
+                       a.workspace_bytes >= carve(a.BH, a.Tq, a.S, D, true).total;
+  const BwdWs w = carve(a.BH, a.Tq, a.S, D, with_ds);
   unsigned char* ws = static_cast<unsigned char*>(a.workspace);
   float* Dp = reinterpret_cast<float*>(ws + w.off_d);
   float* LSE2p = reinterpret_cast<float*>(ws + w.off_lse);
   float* dgate = a.W_r ? reinterpret_cast<float*>(ws + w.off_dg) : nullptr;
   float* dWpart = reinterpret_cast<float*>(ws + w.off_part);
   bf16* Kf = reinterpret_cast<bf16*>(ws + w.off_kf);
-  bf16* Vf = reinterpret_cast<bf16*>(ws + w.off_vf);
+  bf16* Vf = with_ds ? nullptr : reinterpret_cast<bf16*>(ws + w.off_vf);
+  unsigned char* dSb = with_ds ? ws + w.off_ds : nullptr;
   const long rows = (long)a.BH * a.Tq;
   constexpr int CPR = D / 8;
 
@@ -667,15 +707,23 @@ hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
                      (const bf16*)Kp[0], (const bf16*)Kp[1], (const bf16*)Kp[2],
                      (const bf16*)Vp[0], (const bf16*)Vp[1], (const bf16*)Vp[2], a.G, LSE2p, Dp, w.Tqp,
                      (bf16*)a.dK[0], (bf16*)a.dK[1], (bf16*)a.dK[2], (bf16*)a.dV[0],
-                     (bf16*)a.dV[1], (bf16*)a.dV[2], Kf, Vf, dgate, a.Tq, a.S, a.len[0], a.len[1],
+                     (bf16*)a.dV[1], (bf16*)a.dV[2], Kf, Vf, dSb, dgate, a.Tq, a.S, a.len[0], a.len[1],
                      a.len[2], a.causal, a.scale * kLog2e, a.scale, n_kvtiles, a.BH, pair);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
 
-  BwdDqArgs q;
-  q.Q = a.Q; q.dO = a.dO; q.Kf = Kf; q.Vf = Vf; q.LSE2p = LSE2p; q.Dp = Dp; q.Tqp = w.Tqp; q.dgate = dgate; q.W_r = a.W_r; q.dQ = a.dQ;
-  q.BH = a.BH; q.Tq = a.Tq; q.S = a.S; q.d = D; q.causal = a.causal; q.scale = a.scale;
-  e = launch_bwd_dq_bf16(q, st);
+  if (with_ds) {
+    BwdDqgArgs q;
+    q.Kf = Kf; q.dS = dSb; q.dgate = dgate; q.W_r = a.W_r; q.dQ = a.dQ;
+    q.BH = a.BH; q.Tq = a.Tq; q.S = a.S; q.d = D; q.causal = a.causal; q.scale = a.scale;
+    q.n_qt32 = (a.Tq + 31) / 32; q.n_kvt = n_kvtiles;
+    e = launch_bwd_dqg_bf16(q, st);
+  } else {
+    BwdDqArgs q;
+    q.Q = a.Q; q.dO = a.dO; q.Kf = Kf; q.Vf = Vf; q.LSE2p = LSE2p; q.Dp = Dp; q.Tqp = w.Tqp; q.dgate = dgate; q.W_r = a.W_r; q.dQ = a.dQ;
+    q.BH = a.BH; q.Tq = a.Tq; q.S = a.S; q.d = D; q.causal = a.causal; q.scale = a.scale;
+    e = launch_bwd_dq_bf16(q, st);
+  }
   if (e != hipSuccess) return e;
 
   if (a.W_r && (a.dW_r || a.db_r)) {
@@ -692,8 +740,9 @@ hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
 
 }  // namespace
 
-size_t bwd_workspace_bytes(int BH, int Tq, int S, int d) {
-  return carve(BH, Tq, S, d).total;
+size_t bwd_workspace_bytes(int BH, int Tq, int S, int d, bool with_ds) {
+  if (with_ds && ds_bytes(BH, Tq, S) == 0) return 0;
+  return carve(BH, Tq, S, d, with_ds).total;
 }
 
 hipError_t launch_bwd_bf16(const BwdArgs& a, hipStream_t st) {

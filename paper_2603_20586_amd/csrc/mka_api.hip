@@ -110,9 +110,14 @@ size_t mka_workspace_bytes(mka_op op, const mka_shape* s) {
       return mka::prefix_mean_workspace_bytes((int)bh, s->S, s->d);
     case MKA_OP_DECODE:
       return align256(bh * mka::kMaxSplits * (size_t)(s->d + 2) * sizeof(float));
-    case MKA_OP_BWD:
+    case MKA_OP_BWD: {  // the faster route (stored score gradients) when the problem allows it
       if (s->Tq <= 0 || s->S < s->Tq) return 0;
-      return mka::bwd_workspace_bytes((int)bh, s->Tq, s->S, s->d);
+      const size_t with_ds = mka::bwd_workspace_bytes((int)bh, s->Tq, s->S, s->d, true);
+      return with_ds ? with_ds : mka::bwd_workspace_bytes((int)bh, s->Tq, s->S, s->d, false);
+    }
+    case MKA_OP_BWD_RECOMPUTE:
+      if (s->Tq <= 0 || s->S < s->Tq) return 0;
+      return mka::bwd_workspace_bytes((int)bh, s->Tq, s->S, s->d, false);
   }
   return 0;
 }
@@ -508,7 +513,7 @@ mka_status mka_fused_attn_bwd(const void* dO, const void* Q, const void* const K
   if (!a.K[0] && !a.K[1] && !a.K[2]) return MKA_ERR_NULL;  // at least one memory level
   if (empty) return MKA_OK;
   const int BH = shape->B * shape->H;
-  const size_t need = mka::bwd_workspace_bytes(BH, shape->Tq, shape->S, shape->d);
+  const size_t need = mka::bwd_workspace_bytes(BH, shape->Tq, shape->S, shape->d, false);
   if (!workspace || workspace_bytes < need) return MKA_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MKA_ERR_ALIGN;
   a.dO = dO; a.Q = Q; a.G = G; a.O = O; a.LSE = LSE; a.W_r = W_r; a.dQ = dQ;
@@ -518,6 +523,7 @@ mka_status mka_fused_attn_bwd(const void* dO, const void* Q, const void* const K
   a.causal = shape->causal ? 1 : 0;
   a.scale = shape->scale;
   a.workspace = workspace;
+  a.workspace_bytes = workspace_bytes;
   const hipError_t e = mka::launch_bwd_bf16(a, (hipStream_t)stream);
   if (e == hipErrorNotSupported) return MKA_ERR_UNSUPPORTED;
   return e == hipSuccess ? MKA_OK : MKA_ERR_LAUNCH;

@@ -50,6 +50,20 @@ struct BwdDqArgs {
 };
 hipError_t launch_bwd_dq_bf16(const BwdDqArgs& a, hipStream_t st);
 
+// dQ from stored score gradients: dQ = tau sum_j dS[t,j] Kf[j] + dg W_r^T
+struct BwdDqgArgs {
+  const void* Kf;      // fused keys [B*H,S,d] bf16, as written by the main backward kernel
+  const void* dS;      // [B*H][ceil(n_qt32/8)][n_kvt][8] blocks of 8 KiB (128 slots x 32 rows, bf16)
+  const float* dgate;  // [B*H,Tq,3] or null
+  const float* W_r;    // [d,3] or null
+  void* dQ;
+  int BH, Tq, S, d;
+  int n_qt32, n_kvt;   // 32-row query tiles and 128-slot key tiles per head
+  int causal;
+  float scale;
+};
+hipError_t launch_bwd_dqg_bf16(const BwdDqgArgs& a, hipStream_t st);
+
 struct MixArgs {
   const void* Q;
   const void* K[3];
@@ -144,8 +158,11 @@ struct BwdArgs {
   int causal;
   float scale;
   void* workspace;
+  size_t workspace_bytes;
 };
 hipError_t launch_bwd_bf16(const BwdArgs& a, hipStream_t st);
-size_t bwd_workspace_bytes(int BH, int Tq, int S, int d);
+// with_ds: room for the stored score gradients (one product instead of three in the dQ kernel);
+// 0 is returned for with_ds when the problem is too large for that route
+size_t bwd_workspace_bytes(int BH, int Tq, int S, int d, bool with_ds);
 
 }  // namespace mka

@@ -18,3 +18,15 @@ def oracle():
 
     o.build()
     return o
+
+
+@pytest.fixture(autouse=True)
+def _seed_default_generators(request):
+    """Every test starts from the same default-generator state (CPU and GPU), derived from its
+    name: inputs drawn without an explicit generator are reproducible from run to run."""
+    import zlib
+
+    import torch
+
+    torch.manual_seed(zlib.crc32(request.node.nodeid.encode()) & 0x7FFFFFFF)
+    yield
