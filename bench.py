@@ -15,7 +15,7 @@ slots, the widened rows) are timed beside it and reported under "workloads" / "r
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--only LIST] [--no-cpu]
 prints ONE JSON line.  --only takes a comma-separated subset of
-step,C2,C3,C4,C5,paged,refs (default: all) so that a profiler run can cover one workload.
+step,C2,C3,C3mix,C3full,C4,C5,paged,paged128K,refs (default: all) so that a profiler run can cover one workload.
 """
 from __future__ import annotations
 
@@ -31,7 +31,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
-GROUPS = ("step", "C2", "C3", "C4", "C5", "paged", "refs")
+GROUPS = ("step", "C2", "C3", "C3mix", "C3full", "C4", "C5", "paged", "paged128K", "refs")
 
 
 def attn_pairs(Tq, S, causal=True):
@@ -372,24 +372,39 @@ def main():
         rooflines["C3_fwd"] = roof_mfma(fl3, ms3, "prefuse_kernel + mix_bf16_kernel (both in the events)")
         rooflines["C3_fwd_folded"] = roof_mfma(fl3, ms3f, "fwd_bf16_kernel")
         rooflines["C3_attention_core"] = roof_mfma(fl3, msp, "mix_bf16_kernel (one memory)")
-        # the same shape through the per-query gated mixture over the three memories (3x the
-        # pairs) and through symbolic (full) MKA: three attentions + a combine pass
-        msm = time_region(lambda: mka.mka_mixture_attn_fwd(
-            inp3["Q"], inp3["K"], inp3["V"], G3, causal=True, scale=inp3["scale"], O=O3, LSE=L3), 5, 2)
-        wsf = ws(mka.mka_workspace_bytes(MKA_OP_FULL_MKA, shp3))
-        msfull = time_region(lambda: mka.mka_full_attn_fwd(
-            inp3["Q"], inp3["K"], inp3["V"], G3, causal=True, scale=inp3["scale"], O=O3,
-            workspace=wsf), 5, 2)
-        del wsf
-        workloads["C3_full_mka_fwd"] = {"ms": msfull, "tflops": 3 * fl3 / msfull / 1e9,
-                                        "vs_route_fused": msfull / ms3}
-        workloads["C3_gated_mixture_fwd"] = {"ms": msm, "tflops": 3 * fl3 / msm / 1e9}
-        rooflines["C3_mixture"] = roof_mfma(3 * fl3, msm, "mix_bf16_kernel (three memories)")
+        del inp3, G3, O3, L3
+        torch.cuda.empty_cache()
+
+    # the C3 shape through the per-query gated mixture over the three memories (3x the pairs) and
+    # through symbolic (full) MKA: three attentions + a combine pass
+    if only & {"C3mix", "C3full"}:
+        inp3, c3 = si.config_inputs("C3", device=dev)
+        B3, H3, T3 = c3["B"], c3["H"], c3["Tq"]
+        G3 = torch.zeros((B3, H3, T3, 3), device=dev)
+        O3 = torch.empty_like(inp3["Q"])
+        L3 = torch.empty((B3, H3, T3), device=dev)
+        mka.mka_route(inp3["Q"], inp3["W_r"], inp3["b_r"], G=G3, want_idx=False)
+        shp3 = _shape(inp3["Q"], T3, None, True, inp3["scale"])
+        fl3 = 4 * d * attn_pairs(T3, T3) * B3 * H3
+        if "C3mix" in only:
+            msm = time_region(lambda: mka.mka_mixture_attn_fwd(
+                inp3["Q"], inp3["K"], inp3["V"], G3, causal=True, scale=inp3["scale"], O=O3, LSE=L3), 5, 2)
+            workloads["C3_gated_mixture_fwd"] = {"ms": msm, "tflops": 3 * fl3 / msm / 1e9}
+            rooflines["C3_mixture"] = roof_mfma(3 * fl3, msm, "mix_bf16_kernel (three memories)")
+        if "C3full" in only:
+            wsf = ws(mka.mka_workspace_bytes(MKA_OP_FULL_MKA, shp3))
+            msfull = time_region(lambda: mka.mka_full_attn_fwd(
+                inp3["Q"], inp3["K"], inp3["V"], G3, causal=True, scale=inp3["scale"], O=O3,
+                workspace=wsf), 5, 2)
+            del wsf
+            workloads["C3_full_mka_fwd"] = {"ms": msfull, "tflops": 3 * fl3 / msfull / 1e9}
+            if "C3_prefill_fwd" in workloads:
+                workloads["C3_full_mka_fwd"]["vs_route_fused"] = msfull / workloads["C3_prefill_fwd"]["ms"]
         del inp3, G3, O3, L3
         torch.cuda.empty_cache()
 
     # ------------------------------------------------------------ paged fused-KV cache decode
-    if "paged" in only:
+    if only & {"paged", "paged128K"}:
         # the decode shape of C4 over the fused cache (one K and one V stream: a third of the raw
         # bytes) in pages of 128 slots behind a shuffled page table, at 32K slots and at the
         # context length the paper pages for (128K)
@@ -398,7 +413,7 @@ def main():
         q4p = torch.randn((B4, H4, 1, d), generator=g4, device=dev).to(torch.bfloat16)
         O4p = torch.empty_like(q4p)
         wsp = ws(64 * B4 * H4 * (d + 2) * 4)
-        for Sp in (32768, 131072):
+        for Sp in [x for g, x in (("paged", 32768), ("paged128K", 131072)) if g in only]:
             npg = Sp // P4
             Kp4 = torch.empty((B4 * npg, H4, P4, d), device=dev, dtype=torch.bfloat16)
             for i in range(0, B4 * npg, 256):
@@ -417,7 +432,7 @@ def main():
             rooflines[key] = roof_hbm(bytesp, msp4, "paged_split_kernel (+combine in the events)")
             del Kp4, Vp4, tab4, sl4
             torch.cuda.empty_cache()
-        if "C4_decode" in workloads:
+        if "C4_decode" in workloads and "paged_fused_decode_32K" in workloads:
             workloads["paged_fused_decode_32K"]["vs_raw_cache_decode"] = \
                 workloads["C4_decode"]["ms_per_step"] / workloads["paged_fused_decode_32K"]["ms_per_step"]
         del wsp

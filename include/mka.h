@@ -63,7 +63,7 @@ typedef enum {
   MKA_OP_FWD_MATERIALISED = 4, /* what makes mka_fused_attn_fwd write Kf, Vf (see there)   */
   MKA_OP_FULL_MKA = 5,         /* mka_full_attn_fwd: three partial outputs [B,H,Tq,d]      */
   MKA_OP_PREFIX_MEAN = 6,      /* mka_prefix_mean: chunk sums                              */
-  MKA_OP_BWD_RECOMPUTE = 7     /* the least mka_fused_attn_bwd accepts (see there)         */
+  MKA_OP_BWD_STORED_DS = 7     /* what makes mka_fused_attn_bwd store dS (see there)       */
 } mka_op;
 
 /* Problem shape of route / forward / backward. */
@@ -219,15 +219,18 @@ mka_status mka_fused_attn_decode_static(const void* q, const void* const k_new[3
  * Every output is a fixed-order sum: the same call gives the same bits (dQ is
  * accumulated in registers by a query-stationary kernel, dW_r/db_r by a
  * two-stage reduction).  The workspace holds the padded D / LSE rows, the gate gradients, the
- * router-gradient partial sums, the fused key stream and - route A - the score gradients dS
- * (bf16, 8 KiB per pair of a 128-slot key tile and a 32-row query tile, the full rectangle) that
- * the key-stationary kernel leaves for the dQ kernel, or - route B - the fused value stream, with
- * which the dQ kernel forms S, dP and dS a second time (three products per pair instead of one).
- * mka_workspace_bytes(MKA_OP_BWD, shape) is the size for route A where the library provides it
- * (dS of at most 32 GiB in total and 4 GiB per head; config C5: 4.5 GiB) and for route B
- * otherwise; MKA_OP_BWD_RECOMPUTE is the size for route B, the least the call accepts
- * (MKA_ERR_WORKSPACE below it).  A workspace smaller than route A's selects route B.  Both give
- * the same result up to the rounding of dS to bf16, which both apply before the last product. */
+ * router-gradient partial sums and the fused key / value streams: the key-stationary kernel
+ * (dK_l, dV_l, router gradient) writes them, the query-stationary dQ kernel forms S, dP and dS from
+ * them a second time.  mka_workspace_bytes(MKA_OP_BWD, shape) is that size and the least the call
+ * accepts (MKA_ERR_WORKSPACE below it).
+ * Alternative route, taken when the workspace holds at least
+ * mka_workspace_bytes(MKA_OP_BWD_STORED_DS, shape) bytes (0 = not provided for this shape: dS above
+ * 32 GiB in total or 4 GiB per head): the key-stationary kernel also leaves the score gradients dS
+ * in the workspace (bf16, 8 KiB per pair of a 128-slot key tile and a 32-row query tile, the full
+ * rectangle; config C5: 4 GiB) and the dQ kernel reads them back - one product per pair instead
+ * of three.  Same result up to rounding order.  Measured on MI355X it is the faster one for single
+ * calls (C5 2.28 against 2.41 ms) and no faster in a loop of back-to-back calls (2.29 against
+ * 2.27 ms), which is why it is not the default. */
 mka_status mka_fused_attn_bwd(const void* dO, const void* Q, const void* const K[3],
                               const void* const V[3], const float* G, const void* O,
                               const float* LSE, const float* W_r, void* dQ, void* const dK[3],

@@ -614,8 +614,8 @@ size_t a256(size_t n) { return (n + 255) & ~(size_t)255; }
 
 // Stored score gradients (the dQ kernel then needs one product per pair instead of three): one
 // 8 KiB block per (128-slot key tile, 32-row query tile) of every head, the full rectangle (under
-// a causal mask about half of it is written and read).  Taken when it stays below this many bytes
-// in total and below 4 GiB per head (32-bit block offsets); C5 needs 4 GiB.
+// a causal mask about half of it is written and read).  Provided when it stays below this many
+// bytes in total and below 4 GiB per head (32-bit block offsets); C5 needs 4 GiB.
 constexpr size_t kDsCapBytes = (size_t)32 << 30;
 size_t ds_bytes(int BH, int Tq, int S) {
   // query tiles padded to whole groups of 8 (one workgroup of the dQ kernel)
@@ -645,16 +645,16 @@ BwdWs carve(int BH, int Tq, int S, int d, bool with_ds) {
   w.off_ds = w.off_vf;
   const size_t vf_end = w.off_vf + a256((size_t)BH * S * d * sizeof(bf16));
   const size_t ds_end = w.off_ds + a256(ds_bytes(BH, Tq, S));
-  // never below what the other route needs: a workspace sized for the stored gradients is
-  // accepted whichever route a later build picks
-  w.total = with_ds && ds_end > vf_end ? ds_end : vf_end;
+  // the size for the stored gradients is always above the other route's, so that the size of
+  // the caller's workspace tells which route is wanted
+  w.total = with_ds ? (ds_end > vf_end + 256 ? ds_end : vf_end + 256) : vf_end;
   return w;
 }
 
 template <int D>
 hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
   using L = BwdSmem<D>;
-  // the route with stored score gradients when the caller's workspace has room for them
+  // the route with stored score gradients when the caller's workspace has the size asked for it
   const bool with_ds = ds_bytes(a.BH, a.Tq, a.S) > 0 &&
                        a.workspace_bytes >= carve(a.BH, a.Tq, a.S, D, true).total;
   const BwdWs w = carve(a.BH, a.Tq, a.S, D, with_ds);

@@ -3,10 +3,11 @@
     python -m paper_2603_20586_amd.measure.prof_summary stats  <kernel_stats.csv>  <out.txt>  "<command>"
     python -m paper_2603_20586_amd.measure.prof_summary trace  <kernel_trace.csv>  <out.txt>  "<command>"
     python -m paper_2603_20586_amd.measure.prof_summary pmc    <counter_collection.csv> <out.txt> "<command>"
-    python -m paper_2603_20586_amd.measure.prof_summary traffic <fetch_summary.txt> <write_summary.txt> <traffic.json>
+    python -m paper_2603_20586_amd.measure.prof_summary traffic <profiles dir> <traffic.json>
 
-`traffic`: scaled FETCH_SIZE + WRITE_SIZE of the dominant kernel of each roofline line of
-`bench.py` (picked by kernel name and workgroup count) -> HBM bytes per launch, as JSON.
+`traffic`: scaled FETCH_SIZE + WRITE_SIZE of the kernels behind each roofline line of `bench.py`
+(picked by the run's workload group, kernel name and workgroup count; one profiler run per
+workload: `bench.py --only <group>`) -> HBM bytes per launch, as JSON.
 `stats`: per-kernel calls / average / total time.  `trace`: the same from the kernel trace, one
 line per (kernel, workgroup count), i.e. per launch shape: one kernel runs at several workloads in
 one bench.py run, and the roofline lines are per workload.  `pmc`: per-kernel average of every counter in
@@ -112,40 +113,56 @@ def pmc(src, dst, cmd):
     open(dst, "w").write("\n".join(out) + "\n")
 
 
-# roofline key of bench.py -> [(kernel, workgroups of its launch at that workload), ...]: the
-# kernels that carry the line's algorithmic work; their traffic is summed
-TRAFFIC_KEYS = {   # causal launches: one workgroup per PAIR of tiles
-    "C2_fwd": [("mka::fwd_bf16_kernel<128>", 256)],       # 64 heads x 8/2 query tiles
-    "C3_fwd_folded": [("mka::fwd_bf16_kernel<128>", 512)],   # 32 heads x 32/2 query tiles
-    "C2_bwd": [("mka::bwd_main_kernel<128>", 512),        # 64 heads x 16/2 KV tiles
-               ("mka::bwd_dq_kernel<128>", 256)],         # 64 heads x 8/2 query tiles
-    "C5_bwd": [("mka::bwd_main_kernel<128>", 2048),       # 128 heads x 32/2 KV tiles
-               ("mka::bwd_dq_kernel<128>", 1024)],        # 128 heads x 16/2 query tiles
-    "C4_decode": [("mka::decode_split_kernel<bf16,128,4,false>", 2048)],  # 4 splits x 512 heads
+# roofline key of bench.py -> (profile group = the `--only` value of the run, [(kernel, workgroups of
+# its launch at that workload), ...]): the kernels that carry the line's algorithmic work; their
+# traffic is summed.  Causal launches: one workgroup per PAIR of tiles.
+TRAFFIC_KEYS = {
+    "C5_fwd": ("step", [("mka::route_kernel<bf16,128>", 8192), ("mka::prefuse_kernel<128>", 16384),
+                        ("mka::mix_bf16_kernel<128,1>", 1024)]),      # 128 heads x 16/2 query tiles
+    "C5_bwd": ("step", [("mka::bwd_main_kernel<128>", 2048),          # 128 heads x 32/2 key tiles
+                        ("mka::bwd_dq_kernel<128>", 1024)]),
+    "C4_decode_step": ("step", [("mka::decode_split_kernel<bf16,128,4,false>", 2048)]),  # 4 splits x 512
+    "C2_fwd": ("C2", [("mka::fwd_bf16_kernel<128>", 256)]),           # 64 heads x 8/2 query tiles
+    "C2_fwd_materialised": ("C2", [("mka::prefuse_kernel<128>", 4096), ("mka::mix_bf16_kernel<128,1>", 256)]),
+    "C2_bwd": ("C2", [("mka::bwd_main_kernel<128>", 512), ("mka::bwd_dq_kernel<128>", 256)]),
+    "C3_fwd": ("C3", [("mka::prefuse_kernel<128>", 8192), ("mka::mix_bf16_kernel<128,1>", 512)]),
+    "C3_attention_core": ("C3", [("mka::mix_bf16_kernel<128,1>", 512)]),  # 32 heads x 32/2 query tiles
+    "C3_fwd_folded": ("C3", [("mka::fwd_bf16_kernel<128>", 512)]),
+    "C3_mixture": ("C3mix", [("mka::mix_bf16_kernel<128,1>", 512)]),
+    "paged_fused_decode_32K": ("paged", [("mka::paged_split_kernel<128>", 2048)]),
+    "paged_fused_decode_128K": ("paged128K", [("mka::paged_split_kernel<128>", 2048)]),
 }
 
 
-def traffic(fetch_txt, write_txt, dst):
+def traffic(profiles_dir, dst):
+    """<profiles_dir>/<group>_fetch_size.txt and <group>_write_size.txt -> HBM bytes per launch of
+    every roofline key whose kernels appear in its group's summaries."""
     import json
+    import os
 
     def scaled(path):
         out = {}
+        if not os.path.exists(path):
+            return out
         for line in open(path):
             f = [x.strip() for x in line.split("|")]
             if len(f) == 6 and f[5] and not line.startswith("#"):
                 out[(f[0], int(f[1]))] = float(f[5]) * 1e6  # scaled_MB -> bytes
         return out
 
-    rd, wr = scaled(fetch_txt), scaled(write_txt)
-    res = {k: int(sum(rd[v] + wr[v] for v in vs)) for k, vs in TRAFFIC_KEYS.items()
-           if all(v in rd and v in wr for v in vs)}
+    res = {}
+    for key, (group, ks) in TRAFFIC_KEYS.items():
+        rd = scaled(os.path.join(profiles_dir, f"{group}_fetch_size.txt"))
+        wr = scaled(os.path.join(profiles_dir, f"{group}_write_size.txt"))
+        if all(k in rd and k in wr for k in ks):
+            res[key] = int(sum(rd[k] + wr[k] for k in ks))
     json.dump(res, open(dst, "w"), indent=1, sort_keys=True)
     print(json.dumps(res, indent=1, sort_keys=True))
 
 
 if __name__ == "__main__":
     if sys.argv[1] == "traffic":
-        traffic(sys.argv[2], sys.argv[3], sys.argv[4])
+        traffic(sys.argv[2], sys.argv[3])
     else:
         mode, src, dst, cmd = sys.argv[1], sys.argv[2], sys.argv[3], sys.argv[4]
         {"stats": stats, "trace": trace, "pmc": pmc}[mode](src, dst, cmd)

@@ -103,10 +103,10 @@ def test_C5_training_all_heads(mka, oracle):
                                             causal=True, scale=inp["scale"])
     g = mka.mka_fused_attn_bwd(inp["dO"], inp["Q"], inp["K"], inp["V"], G, O, LSE, inp["W_r"],
                                causal=True, scale=inp["scale"])
-    # the library's default here stores dS for the dQ kernel; the other route recomputes the
-    # scores: same main kernel (bit-identical dK / dV / dW_r), its dQ is checked below as well
+    # the alternative route stores dS for the dQ kernel instead of recomputing the scores: same
+    # main kernel (bit-identical dK / dV / dW_r), its dQ is checked below as well
     dQ_rec = mka.mka_fused_attn_bwd(inp["dO"], inp["Q"], inp["K"], inp["V"], G, O, LSE, inp["W_r"],
-                                    causal=True, scale=inp["scale"], recompute=True,
+                                    causal=True, scale=inp["scale"], stored_ds=True,
                                     grads_for=(False, False, False))["dQ"]
     torch.cuda.synchronize()
     # Router gradients of the configured problem: they sum over all 128 heads and 524 288 rows

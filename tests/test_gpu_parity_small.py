@@ -334,10 +334,10 @@ def _check_bwd(mka, oracle, inp, S, len3, causal, Gprev=None, use_router=True, s
         Gref = Gprev.cpu()
     g = mka.mka_fused_attn_bwd(inp["dO"], inp["Q"], inp["K"], inp["V"], G, O, LSE, W, len3=len3,
                                causal=causal, scale=inp["scale"])
-    # the other dQ route (scores recomputed instead of dS read back): same main kernel, so
-    # everything but dQ agrees bit for bit, and dQ is checked against the oracle like the first
+    # the other dQ route (dS stored by the main kernel and read back instead of recomputed): same
+    # main kernel, so everything but dQ agrees bit for bit; dQ is checked against the oracle too
     g_rec = mka.mka_fused_attn_bwd(inp["dO"], inp["Q"], inp["K"], inp["V"], G, O, LSE, W, len3=len3,
-                                   causal=causal, scale=inp["scale"], recompute=True)
+                                   causal=causal, scale=inp["scale"], stored_ds=True)
     torch.cuda.synchronize()
     for l in range(3):
         assert torch.equal(g["dK"][l], g_rec["dK"][l]) and torch.equal(g["dV"][l], g_rec["dV"][l])
@@ -348,7 +348,7 @@ def _check_bwd(mka, oracle, inp, S, len3, causal, Gprev=None, use_router=True, s
                      tau=inp["scale"])
     # Contract: raw max-abs 2e-2 on dQ, dK_l, dV_l.  Only the labelled stress cases (router scaled
     # up tenfold) are judged on the error normalised by the gradient's own scale, see there.
-    errs = {"dQ": (g["dQ"], ref["dQ"]), "dQ(recompute route)": (g_rec["dQ"], ref["dQ"])}
+    errs = {"dQ": (g["dQ"], ref["dQ"]), "dQ(stored-dS route)": (g_rec["dQ"], ref["dQ"])}
     for l in range(3):
         errs[f"dK{l}"] = (g["dK"][l], ref["dK"][l])
         errs[f"dV{l}"] = (g["dV"][l], ref["dV"][l])
