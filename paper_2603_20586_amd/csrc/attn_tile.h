@@ -29,6 +29,9 @@ __device__ __forceinline__ int mx_swz(int r) {
 // lds + 16 * lane.  Counted by vmcnt like any other load; the LDS write is done when the count
 // drops.  m0 carries the LDS address (one wait state between its write and the load).
 __device__ __forceinline__ void mx_dma16(const void* base, unsigned off, unsigned lds) {
+#if MKA_ELIM & 8
+  return;
+#endif
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
                : "v"(off), "s"(base), "s"(lds)
@@ -36,6 +39,9 @@ __device__ __forceinline__ void mx_dma16(const void* base, unsigned off, unsigne
 }
 // 4 bytes per lane, each lane with its own address, to LDS address lds + 4 * lane.
 __device__ __forceinline__ void mx_dma4(const void* src, unsigned lds) {
+#if MKA_ELIM & 8
+  return;
+#endif
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
                :
                : "v"(src), "s"(lds)

@@ -319,7 +319,7 @@ __device__ __forceinline__ void bwd_main_tile(
         for (int r = 0; r < 16; ++r) pacc[r] = 0.f;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-          const bf16x8 ao = *reinterpret_cast<const bf16x8*>(lds + tb + L::QB + (aq0 ^ (unsigned)(kk << 5)));
+          const bf16x8 ao = lds_frag(lds + tb + L::QB + (aq0 ^ (unsigned)(kk << 5)));
           pacc = mfma32(ao, breg[kk], pacc);
         }
         // register r <-> row 16 (r/8) + 8 g + r%8 of the tile, column = the lane's slot
@@ -366,7 +366,7 @@ __device__ __forceinline__ void bwd_main_tile(
         for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-          const bf16x8 aq = *reinterpret_cast<const bf16x8*>(lds + tb + (aq0 ^ (unsigned)(kk << 5)));
+          const bf16x8 aq = lds_frag(lds + tb + (aq0 ^ (unsigned)(kk << 5)));
           sacc = mfma32(aq, breg[kk], sacc);
         }
         const float* sL = reinterpret_cast<const float*>(lds + tb + 2 * L::QB);
@@ -403,7 +403,7 @@ __device__ __forceinline__ void bwd_main_tile(
       }
     }
     wait_tile();  // this wave's part of tile it+1 has landed
-    __syncthreads();
+    loop_barrier();
     b5 = b5 == L::NSLOT - 1 ? 0 : b5 + 1;
   }
   mx_wait_loads<0>();  // the surplus requests must land before the epilogue reuses the buffers

@@ -67,7 +67,7 @@ __device__ __forceinline__ void dq_unit(F1&& mid1, F2&& mid2, bf16x8 (&fr)[D / 1
   unsigned ka = ko + a0, xl = ko + x_lo, xh = ko + x_hi, na = kn + a0;
   asm volatile("" : "+v"(ka), "+v"(xl), "+v"(xh), "+v"(na));
   auto row_frag = [&](unsigned base, int kk, int tensor) __attribute__((always_inline)) {
-    return *reinterpret_cast<const bf16x8*>(smem + tensor * TSZ + (base ^ (unsigned)(kk << 5)));
+    return lds_frag(smem + tensor * TSZ + (base ^ (unsigned)(kk << 5)));
   };
   // Kf^T fragment of dQ MFMA i (head dims 32 (i % DB) .., k-step i / DB): the transpose of 8
   // slots x 32 head dims of the row-major K tile
@@ -241,7 +241,7 @@ __device__ __forceinline__ void bwd_dq_tile(
   int rb = 0;  // ring position of the tile being consumed
   for (int T = 0; T < NT; ++T) {
     mx_wait_loads<LPT>();  // this wave's part of tile T+1 has landed (T+2 may be in flight)
-    __syncthreads();       // tile T+1 complete; the buffers of tile T-1 are free
+    loop_barrier();        // tile T+1 complete; the buffers of tile T-1 are free
     request_begin();       // tile T+3, issued in four places of the two units
     const int rb1 = rb == SM::NB - 1 ? 0 : rb + 1;
     const unsigned k0 = (unsigned)(2 * rb * SM::TSZ);   // K rows of unit 0; unit 1 is 32 rows on

@@ -289,11 +289,11 @@ __device__ __forceinline__ void half_step(
   for (int kk = 0; kk < KK; ++kk) {
     sn = mfma32(fr[kk % PF], qreg[kk], sn);
     if (kk + PF < KK) {
-      fr[kk % PF] = *reinterpret_cast<const bf16x8*>(arow + 16 * (kk + PF));
+      fr[kk % PF] = lds_frag(arow + 16 * (kk + PF));
     } else {  // the K fragments are all on their way: start on the Vf^T fragments
       const int i = kk + PF - KK;  // PV MFMA i uses rows 32 (i % DB), k half i / DB
       if (i < NPV)
-        fr[kk % PF] = *reinterpret_cast<const bf16x8*>(vbase + 32 * (i % DB) * VSTR + 16 * (i / DB));
+        fr[kk % PF] = lds_frag(vbase + 32 * (i % DB) * VSTR + 16 * (i / DB));
     }
 #pragma unroll
     for (int r = kk * EPK; r < (kk + 1) * EPK; ++r) {
@@ -324,7 +324,7 @@ __device__ __forceinline__ void half_step(
     oacc[i % DB] = mfma32(fr[(KP + i) % PF], i / DB ? p1 : p0, oacc[i % DB]);
     if (i + PF < NPV) {
       const int n = i + PF;
-      fr[(KP + i) % PF] = *reinterpret_cast<const bf16x8*>(vbase + 32 * (n % DB) * VSTR + 16 * (n / DB));
+      fr[(KP + i) % PF] = lds_frag(vbase + 32 * (n % DB) * VSTR + 16 * (n / DB));
     }
 #pragma unroll
     for (int hs = (KK + i) * SPM; hs < (KK + i + 1) * SPM; ++hs) stage(hs);
@@ -399,7 +399,7 @@ __device__ __forceinline__ void run_tiles(bf16* smem, const bf16* __restrict__ P
       half_step<D, GV, true>(s_a, s_b, sK, 1, j0, sVT, 0, qreg, oacc, m, lsum, c, jmax, raw, tmp,
                              dst1, 2, true, jl, 0, true, true, P0, P1, P2, Gb, S, len0, len1, len2,
                              li, g, tg);
-      __syncthreads();  // tile jt+1 is complete in LDS; K buffer jt&1 may be overwritten
+      loop_barrier();  // tile jt+1 is complete in LDS; K buffer jt&1 may be overwritten
       half_step<D, GV, true>(s_b, s_a, sK1, 0, j0 + 32, sVT, 1, qreg, oacc, m, lsum, c, jmax, raw,
                              tmp, dst2, 0, true, jl, 2, true, true, P0, P1, P2, Gb, S, len0, len1,
                              len2, li, g, tg);

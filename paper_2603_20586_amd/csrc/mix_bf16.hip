@@ -89,13 +89,40 @@ __device__ __forceinline__ f32x16 mx_s_unit(const char* sK, unsigned a0, const b
 struct MixRow {
   float m, lsum;  // running reference exponent (log2 units, gate included) and denominator
   float bl;       // log2 gate of the level being consumed
+  float kb;       // bl - m (bl while nothing has been seen): what the exponentials add to c * score
   int jmax;       // last visible slot of that level
 };
+
+// Step k (0..7) of the running maximum over the 16 registers of an accumulator: eight steps
+// cover it (three-operand maxima; no NaN canonicalisation of the inputs: they come out of an
+// MFMA or are -inf).
+template <int K>
+__device__ __forceinline__ void mx_max_step(float& m, const f32x16& s) {
+  // (volatile: the statements keep their place between the MFMAs)
+  if (K == 0) asm volatile("v_max3_f32 %0, %1, %2, %3" : "=v"(m) : "v"(s[0]), "v"(s[1]), "v"(s[2]));
+  else if (K < 7) asm volatile("v_max3_f32 %0, %1, %2, %3" : "=v"(m) : "v"(m), "v"(s[2 * K + 1]), "v"(s[(2 * K + 2) & 15]));
+  else asm volatile("v_max_f32 %0, %1, %2" : "=v"(m) : "v"(m), "v"(s[15]));
+}
 
 // One half step of a wave: finish the unit whose S^T is s_now (32 slots from jb of a level:
 // softmax, then O^T += V^T P^T with the V rows of unit U of the tile at sV) and compute the S^T
 // of the following unit into s_next - for each of the wave's R row blocks, which share every
 // LDS fragment.
+//
+// Every MFMA of the half step is followed by a few vector instructions of another stage of the
+// pipeline, so that neither pipe sees a long stretch of the other kind: the S^T MFMAs of the
+// next unit run between the exponentials (and the rounding to bf16) of this one, the PV MFMAs of
+// this unit between the row sums of its P and the running maximum of the next unit's scores.
+//
+// Reference exponent.  Lazy max-shift (as in the route-fused forward): the reference only moves
+// when an exponent has grown more than 8 beyond it, so P may reach 2^8 and the rescale of the
+// accumulators is skipped on almost every unit.  The common case costs the in-lane maximum and
+// one compare, both done a half step early (behind the PV MFMAs): each half of a row (the lanes
+// li and li + 32) tests its own 16 slots against the row's reference, and `need` says whether
+// some lane of the wave failed.  Only then are the halves exchanged, the references moved and
+// the accumulators rescaled - at the start of the half step that consumes the unit, when the
+// accumulators are at rest.  A masked unit always takes the long way; so does the first unit of
+// a level (the caller sets need: the test was made with the previous level's gate).
 //
 // fr is a ring of D/16 LDS fragments that lives across half steps.  On entry it holds the K
 // fragments of the unit whose S^T is computed here; every S MFMA group frees a slot, which is
@@ -113,43 +140,46 @@ __device__ __forceinline__ void mx_half_step(FA&& mid_a, FB&& mid_b, f32x16 (&s_
                                              int jb, const char* sV, unsigned x_lo, unsigned x_hi,
                                              const bf16x8 (&qreg)[R][D / 16],
                                              f32x16 (&oacc)[R][D / 32], MixRow (&row)[R], float c,
-                                             int lane) {
+                                             int lane, bool& need) {
   constexpr int ROWB = D * 2, KK = D / 16, DB = D / 32;
   constexpr int EPK = 16 / KK;   // exponentials per S MFMA
   constexpr int NPV = 2 * DB;    // PV MFMAs of the unit and row block (== KK)
+  constexpr int MPS = 8 / NPV;   // steps of the running maximum per PV MFMA
   const int g = lane >> 5;
 
-  float kb[R], alpha[R];
+  if (MASK) {
 #pragma unroll
-  for (int rb = 0; rb < R; ++rb) {
-    if (MASK) {
+    for (int rb = 0; rb < R; ++rb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int j = jb + 8 * (r >> 2) + 4 * g + (r & 3);
         if (j > row[rb].jmax) s_now[rb][r] = -INFINITY;
       }
-    }
-    float mx = fmaxf(s_now[rb][0], s_now[rb][1]);
+  }
+  if (MASK || need) {
 #pragma unroll
-    for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s_now[rb][r]);
-    mx = fmaxf(mx, xor32(mx));
-    // Lazy max-shift (as in the route-fused forward): the reference exponent only moves when the
-    // row's largest exponent has grown by more than 8, so P may reach 2^8 and the rescale of the
-    // accumulators is skipped on almost every unit.
-    const float m = row[rb].m, bl = row[rb].bl;
-    const float cand = (mx == -INFINITY) ? -INFINITY : fmaf(mx, c, bl);
-    const bool move = cand - m > 8.f || (m == -INFINITY && cand > -INFINITY);
-    const float m_new = move ? cand : m;
-    alpha[rb] = move ? ((m == -INFINITY) ? 0.f : fast_exp2(m - m_new)) : 1.f;
-    kb[rb] = bl - ((m_new == -INFINITY) ? 0.f : m_new);
-    row[rb].m = m_new;
-    if (__any(move)) {
+    for (int rb = 0; rb < R; ++rb) {
+      float mx = max16(s_now[rb]);
+      mx = fmaxf(mx, xor32(mx));
+      const float m = row[rb].m, bl = row[rb].bl;
+      const float cand = (mx == -INFINITY) ? -INFINITY : fmaf(mx, c, bl);
+      const bool move = cand - m > 8.f || (m == -INFINITY && cand > -INFINITY);
+      const float m_new = move ? cand : m;
+      const float alpha = move ? ((m == -INFINITY) ? 0.f : fast_exp2(m - m_new)) : 1.f;
+      row[rb].kb = bl - ((m_new == -INFINITY) ? 0.f : m_new);
+      row[rb].m = m_new;
+      row[rb].lsum *= alpha;
+      if (__any(move)) {
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[rb][db][r] *= alpha[rb];
+          for (int r = 0; r < 16; ++r) oacc[rb][db][r] *= alpha;
+      }
     }
   }
+  float kb[R];
+#pragma unroll
+  for (int rb = 0; rb < R; ++rb) kb[rb] = row[rb].kb;
 
   // V^T fragment of PV MFMA i (rows 32 (i % DB) of V^T, k-step i / DB): the transpose of 8 slots
   // x 32 head dims of the row-major V tile.  k positions 0..3 <-> slots 16 ks + 4 g + 0..3,
@@ -160,6 +190,11 @@ __device__ __forceinline__ void mx_half_step(FA&& mid_a, FB&& mid_b, f32x16 (&s_
     const char* vrow = sV + (32 * U + 16 * ks) * ROWB;
     const uint2 lo = lds_read_tr(reinterpret_cast<const bf16*>(vrow + (x_lo ^ (unsigned)(db << 6))));
     const uint2 hi = lds_read_tr(reinterpret_cast<const bf16*>(vrow + (x_hi ^ (unsigned)(db << 6))));
+#if MKA_DOUBLE & 1
+    const uint2 lo2 = lds_read_tr(reinterpret_cast<const bf16*>(vrow + 512 + (x_lo ^ (unsigned)(db << 6))));
+    const uint2 hi2 = lds_read_tr(reinterpret_cast<const bf16*>(vrow + 512 + (x_hi ^ (unsigned)(db << 6))));
+    asm volatile("" ::"v"(lo2), "v"(hi2));
+#endif
     return __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
   };
 
@@ -170,19 +205,37 @@ __device__ __forceinline__ void mx_half_step(FA&& mid_a, FB&& mid_b, f32x16 (&s_
 #pragma unroll
     for (int r = 0; r < 16; ++r) sn[rb][r] = 0.f;
   float p[R][16];
+  uint32_t pw[R][8];  // P rounded to bf16, two slots per word
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) {
 #pragma unroll
     for (int rb = 0; rb < R; ++rb) sn[rb] = mfma32(fr[kk], qreg[rb][kk], sn[rb]);
     fr[kk] = v_frag(kk);
 #pragma unroll
-    for (int rb = 0; rb < R; ++rb)
+    for (int rb = 0; rb < R; ++rb) {
 #pragma unroll
       for (int r = kk * EPK; r < (kk + 1) * EPK; ++r) {
         float e = fast_exp2(fmaf(s_now[rb][r], c, kb[rb]));
         if (MASK) e = (s_now[rb][r] == -INFINITY) ? 0.f : e;  // also covers c == 0
+#if MKA_DOUBLE & 4
+        {
+          const float again = fast_exp2(fmaf(s_now[rb][r], c, kb[rb] + 1.f));
+          asm volatile("" ::"v"(again));
+        }
+#endif
+#if MKA_DOUBLE & 8
+        {
+          float more = fmaf(s_now[rb][r], c, kb[rb] + 1.f);
+          asm volatile("" ::"v"(more));
+          more = fmaf(s_now[rb][r], c, kb[rb] + 2.f);
+          asm volatile("" ::"v"(more));
+        }
+#endif
         p[rb][r] = e;
       }
+#pragma unroll
+      for (int r = kk * EPK; r < (kk + 1) * EPK; r += 2) pw[rb][r / 2] = pack_bf16x2(p[rb][r], p[rb][r + 1]);
+    }
     if (kk == KK / 2 - 1) mid_a();
     __builtin_amdgcn_sched_barrier(0);
   }
@@ -190,30 +243,62 @@ __device__ __forceinline__ void mx_half_step(FA&& mid_a, FB&& mid_b, f32x16 (&s_
 #pragma unroll
   for (int rb = 0; rb < R; ++rb) {
     s_next[rb] = sn[rb];
-    const uint4 pk0 = pack8(&p[rb][0]), pk1 = pack8(&p[rb][8]);
-    pk[rb][0] = __builtin_bit_cast(bf16x8, pk0);
-    pk[rb][1] = __builtin_bit_cast(bf16x8, pk1);
-    // Row sum of P in f32, before the rounding to bf16 (the rounding errors of the numerator have
-    // zero mean).  Plain adds on purpose: v_dot2_f32_bf16 would halve the instruction count but
-    // cannot issue while an MFMA of either wave of the SIMD is in the matrix pipe (measured: a
-    // wave with dot2 instructions makes no progress next to a wave that streams MFMAs).
-    const float* pr = p[rb];
-    const float psum = (((pr[0] + pr[1]) + (pr[2] + pr[3])) + ((pr[4] + pr[5]) + (pr[6] + pr[7]))) +
-                       (((pr[8] + pr[9]) + (pr[10] + pr[11])) + ((pr[12] + pr[13]) + (pr[14] + pr[15])));
-    row[rb].lsum = row[rb].lsum * alpha[rb] + psum;
+    pk[rb][0] = __builtin_bit_cast(bf16x8, make_uint4(pw[rb][0], pw[rb][1], pw[rb][2], pw[rb][3]));
+    pk[rb][1] = __builtin_bit_cast(bf16x8, make_uint4(pw[rb][4], pw[rb][5], pw[rb][6], pw[rb][7]));
   }
-  __builtin_amdgcn_sched_barrier(0);
 
-  // -- section B: O^T += V^T P^T
+  // -- section B: O^T += V^T P^T; behind the MFMAs the row sums of P (in f32, before the rounding
+  // to bf16: the rounding errors of the numerator have zero mean; plain adds on purpose:
+  // v_dot2_f32_bf16 would halve the instruction count but cannot issue while an MFMA of either
+  // wave of the SIMD is in the matrix pipe - measured: a wave with dot2 instructions makes no
+  // progress next to a wave that streams MFMAs) and the in-lane maximum of the next unit's scores
+  float lsum[R], nmax[R];
+#pragma unroll
+  for (int rb = 0; rb < R; ++rb) lsum[rb] = row[rb].lsum;
 #pragma unroll
   for (int i = 0; i < NPV; ++i) {
 #pragma unroll
     for (int rb = 0; rb < R; ++rb)
       oacc[rb][i % DB] = mfma32(fr[i], pk[rb][i / DB], oacc[rb][i % DB]);
-    fr[i] = *reinterpret_cast<const bf16x8*>(sKnn + (a0 ^ (unsigned)(i << 5)));
+    fr[i] = lds_frag(sKnn + (a0 ^ (unsigned)(i << 5)));
+#if MKA_DOUBLE & 1
+    {
+      const bf16x8 again = lds_frag(sKnn + 512 + (a0 ^ (unsigned)(i << 5)));
+      asm volatile("" ::"v"(again));
+    }
+#endif
+#pragma unroll
+    for (int rb = 0; rb < R; ++rb) {
+#pragma unroll
+      for (int r = i * (16 / NPV); r < (i + 1) * (16 / NPV); ++r)
+        asm volatile("v_add_f32 %0, %0, %1" : "+v"(lsum[rb]) : "v"(p[rb][r]));  // in place, see above
+      if (MPS == 1) {
+        if (i == 0) mx_max_step<0>(nmax[rb], s_next[rb]);
+        if (i == 1) mx_max_step<1>(nmax[rb], s_next[rb]);
+        if (i == 2) mx_max_step<2>(nmax[rb], s_next[rb]);
+        if (i == 3) mx_max_step<3>(nmax[rb], s_next[rb]);
+        if (i == 4) mx_max_step<4>(nmax[rb], s_next[rb]);
+        if (i == 5) mx_max_step<5>(nmax[rb], s_next[rb]);
+        if (i == 6) mx_max_step<6>(nmax[rb], s_next[rb]);
+        if (i == 7) mx_max_step<7>(nmax[rb], s_next[rb]);
+      } else {
+        if (i == 0) { mx_max_step<0>(nmax[rb], s_next[rb]); mx_max_step<1>(nmax[rb], s_next[rb]); }
+        if (i == 1) { mx_max_step<2>(nmax[rb], s_next[rb]); mx_max_step<3>(nmax[rb], s_next[rb]); }
+        if (i == 2) { mx_max_step<4>(nmax[rb], s_next[rb]); mx_max_step<5>(nmax[rb], s_next[rb]); }
+        if (i == 3) { mx_max_step<6>(nmax[rb], s_next[rb]); mx_max_step<7>(nmax[rb], s_next[rb]); }
+      }
+    }
     if (i == NPV / 2 - 1) mid_b();
     __builtin_amdgcn_sched_barrier(0);
   }
+  bool chk = false;
+#pragma unroll
+  for (int rb = 0; rb < R; ++rb) {
+    row[rb].lsum = lsum[rb];
+    // !(.. <= 8): also taken when there is no reference yet (kb = +inf, or NaN with a zero gate)
+    chk = chk || !(fmaf(nmax[rb], c, row[rb].kb) <= 8.f);
+  }
+  need = __any(chk);
 }
 
 // One tile of BR query rows (index qt) of head bh against the whole stream of K/V tiles.  Called
@@ -299,6 +384,7 @@ __device__ __forceinline__ void mix_tile(
     row[rb].m = -INFINITY;
     row[rb].lsum = 0.f;
     row[rb].bl = 0.f;
+    row[rb].kb = 0.f;
     row[rb].jmax = 0;
   }
 
@@ -355,6 +441,10 @@ __device__ __forceinline__ void mix_tile(
   auto request_part = [&](int q) __attribute__((always_inline)) {
     if (q < IPW) mx_dma16(rq_kc, rq_off[q], lds0 + (unsigned)(kb_w * SM::TSZ + 1024 * q));
     else mx_dma16(rq_vc, rq_off[q - IPW], lds0 + (unsigned)(SM::VOFF + vb_w * SM::TSZ + 1024 * (q - IPW)));
+#if MKA_DOUBLE & 2
+    if (q < IPW) mx_dma16(rq_kc, rq_off[q], lds0 + (unsigned)(kb_w * SM::TSZ + 1024 * q));
+    else mx_dma16(rq_vc, rq_off[q - IPW], lds0 + (unsigned)(SM::VOFF + vb_w * SM::TSZ + 1024 * (q - IPW)));
+#endif
   };
   auto request_end = [&]() __attribute__((always_inline)) {
     kb_w = kb_w == SM::NKB - 1 ? 0 : kb_w + 1;
@@ -366,7 +456,7 @@ __device__ __forceinline__ void mix_tile(
     for (int q = 0; q < 2 * IPW; ++q) request_part(q);
     request_end();
   };
-  constexpr int LPT = 2 * IPW;  // loads of a wave per tile
+  constexpr int LPT = 2 * IPW * ((MKA_DOUBLE & 2) ? 2 : 1);  // loads of a wave per tile
 
   if (NT > 0) {
     // lane constants of the LDS reads
@@ -391,9 +481,10 @@ __device__ __forceinline__ void mix_tile(
     for (int kk = 0; kk < KK; ++kk)
       fr[kk] = *reinterpret_cast<const bf16x8*>(smem + 32 * ROWB + (a0 ^ (unsigned)(kk << 5)));
     int l = -1, j0 = 0, left = 1, Sl = 0, row_lo = 0;
+    bool need = true;    // the unit in s_a has to take the long way through the reference update
     for (int T = 0; T < NT; ++T) {
       mx_wait_loads<LPT>();  // this wave's part of tile T+1 has landed (T+2 may be in flight)
-      __syncthreads();       // tile T+1 complete; K buffer of T and V buffer of T-1 are free
+      loop_barrier();        // tile T+1 complete; K buffer of T and V buffer of T-1 are free
       request_begin();       // tile T+3, issued in four places of the two half steps
       if (left > 1) {
         j0 += BC;
@@ -406,6 +497,9 @@ __device__ __forceinline__ void mix_tile(
         for (int rb = 0; rb < R; ++rb) {
           row[rb].jmax = l == 0 ? jmax0[rb] : (l == 1 ? jmax1[rb] : jmax2[rb]);
           row[rb].bl = l == 0 ? bl0[rb] : (l == 1 ? bl1[rb] : bl2[rb]);
+          // no reference yet: +inf (NaN with a zero gate) sends the first unit the long way
+          row[rb].kb = row[rb].bl - row[rb].m;
+          need = true;
         }
       }
       const int kb1 = kb == SM::NKB - 1 ? 0 : kb + 1;
@@ -424,11 +518,11 @@ __device__ __forceinline__ void mix_tile(
       auto p2 = [&]() __attribute__((always_inline)) { part(2); };
       auto p3 = [&]() __attribute__((always_inline)) { part(3); };
       // first half step: unit 0 of tile T; S^T of its unit 1; K fragments of unit 0 of tile T+1
-      if (mask0) mx_half_step<D, R, true, 0>(p0, p1, s_a, s_b, fr, sK1, a0, j0, sV, x_lo, x_hi, qreg, oacc, row, c, lane);
-      else mx_half_step<D, R, false, 0>(p0, p1, s_a, s_b, fr, sK1, a0, j0, sV, x_lo, x_hi, qreg, oacc, row, c, lane);
+      if (mask0) mx_half_step<D, R, true, 0>(p0, p1, s_a, s_b, fr, sK1, a0, j0, sV, x_lo, x_hi, qreg, oacc, row, c, lane, need);
+      else mx_half_step<D, R, false, 0>(p0, p1, s_a, s_b, fr, sK1, a0, j0, sV, x_lo, x_hi, qreg, oacc, row, c, lane, need);
       // second half step: unit 1 of tile T; S^T of unit 0 of tile T+1; K fragments of its unit 1
-      if (mask1) mx_half_step<D, R, true, 1>(p2, p3, s_b, s_a, fr, sK1 + 32 * ROWB, a0, j0 + 32, sV, x_lo, x_hi, qreg, oacc, row, c, lane);
-      else mx_half_step<D, R, false, 1>(p2, p3, s_b, s_a, fr, sK1 + 32 * ROWB, a0, j0 + 32, sV, x_lo, x_hi, qreg, oacc, row, c, lane);
+      if (mask1) mx_half_step<D, R, true, 1>(p2, p3, s_b, s_a, fr, sK1 + 32 * ROWB, a0, j0 + 32, sV, x_lo, x_hi, qreg, oacc, row, c, lane, need);
+      else mx_half_step<D, R, false, 1>(p2, p3, s_b, s_a, fr, sK1 + 32 * ROWB, a0, j0 + 32, sV, x_lo, x_hi, qreg, oacc, row, c, lane, need);
       request_end();
       kb = kb1;
       vb = vb == SM::NVB - 1 ? 0 : vb + 1;

@@ -14,6 +14,22 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Elimination builds (measurement only, never shipped: the build script passes the flag on request,
+// MKA_EXTRA_HIPCC_FLAGS=-DMKA_ELIM=<bits>).  Each bit removes one kind of work from the MFMA
+// kernels' loops while every memory access and every loop count stays what it was; the results
+// are wrong, the launch times say what the removed work costs on the critical path.
+//   1 MFMAs   2 LDS fragment reads   4 exponentials   8 LDS-direct tile loads   16 loop barriers
+// Under the board's power limit an elimination build also changes what the MFMAs draw (tiles that
+// are never loaded are constant data), so the attention core has the opposite hooks as well,
+// MKA_DOUBLE=<bits>: one kind of work done twice on the same data, results unchanged.
+//   1 LDS fragment reads   2 LDS-direct tile loads   4 exponentials   8 two more FMAs per score
+#ifndef MKA_ELIM
+#define MKA_ELIM 0
+#endif
+#ifndef MKA_DOUBLE
+#define MKA_DOUBLE 0
+#endif
+
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -97,14 +113,43 @@ __device__ __forceinline__ uint4 load16_stream(const void* p) {
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_exp2(float x) {
+#if MKA_ELIM & 4
+  return x;
+#else
+  return __builtin_amdgcn_exp2f(x);
+#endif
+}
 
 // 32x32x16 bf16 MFMA, f32 accumulate.  Operand layout (wave of 64 lanes, lane l):
 //   A (32 x 16): row l%32, k = 8*(l/32) .. +7        (8 bf16 per lane)
 //   B (16 x 32): column l%32, k = 8*(l/32) .. +7
 //   C/D (32 x 32): column l%32, register r holds row 8*(r/4) + 4*(l/32) + r%4
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+#if MKA_ELIM & 1
+  asm volatile("; mfma removed" : "+v"(c) : "v"(a), "v"(b));  // keeps the operands' producers alive
+  return c;
+#else
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+#endif
+}
+
+// 16-byte MFMA operand fragment out of LDS (ds_read_b128)
+__device__ __forceinline__ bf16x8 lds_frag(const void* p) {
+#if MKA_ELIM & 2
+  bf16x8 r;
+  asm volatile("; lds read removed" : "=v"(r) : "v"((unsigned)(size_t)p));  // no instruction, address kept alive
+  return r;
+#else
+  return *reinterpret_cast<const bf16x8*>(p);
+#endif
+}
+
+// workgroup barrier inside the tile loops
+__device__ __forceinline__ void loop_barrier() {
+#if !(MKA_ELIM & 16)
+  __syncthreads();
+#endif
 }
 
 // Transposed 16-bit LDS read (gfx950): inside every 16-lane group, lane i receives, for
@@ -113,10 +158,27 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 // rows 0..3: the block's transpose, which is the MFMA A-operand layout (row = lane, 4 k-values).
 typedef short lds_v4s __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint2 lds_read_tr(const bf16* p) {
+#if MKA_ELIM & 2
+  uint2 r;
+  asm volatile("; lds read removed" : "=v"(r) : "v"((unsigned)(size_t)p));
+  return r;
+#else
   typedef __attribute__((address_space(3))) lds_v4s* lptr;
   const lds_v4s v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p));
   return __builtin_bit_cast(uint2, v);
+#endif
 }
+// Largest of 16 accumulator registers with eight three-operand maxima (no NaN canonicalisation
+// of the inputs: they come out of an MFMA or are -inf).
+__device__ __forceinline__ float max16(const f32x16& s) {
+  float m;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(m) : "v"(s[0]), "v"(s[1]), "v"(s[2]));
+#pragma unroll
+  for (int r = 3; r < 15; r += 2) asm("v_max3_f32 %0, %1, %2, %3" : "=v"(m) : "v"(m), "v"(s[r]), "v"(s[r + 1]));
+  asm("v_max_f32 %0, %1, %2" : "=v"(m) : "v"(m), "v"(s[15]));
+  return m;
+}
+
 // Exchange with the lane 32 away (the other half of the wave).
 // One v_permlane32_swap (a VALU instruction of gfx950, no LDS round trip): with both operands
 // equal to v, the first result holds the lower half's values in both halves of the wave, the

@@ -26,6 +26,9 @@ def lib() -> ctypes.CDLL:
         L.mka_measure_mfma_loop.restype = c_int32
         L.mka_measure_mfma_loop.argtypes = [c_void_p, c_int32, c_int32,
                                             POINTER(ctypes.c_double), c_void_p]
+        L.mka_measure_mfma_loop_data.restype = c_int32
+        L.mka_measure_mfma_loop_data.argtypes = [c_void_p, c_void_p, c_int32, c_int32,
+                                                 POINTER(ctypes.c_double), c_void_p]
         L.mka_measure_stream_read.restype = c_int32
         L.mka_measure_stream_read.argtypes = [c_void_p, c_size_t, c_void_p, c_void_p]
         _lib = L
@@ -45,6 +48,22 @@ def mfma_loop(out, workgroups: int, iters: int) -> float:
                                      ctypes.byref(fl), _stream())
     if rc:
         raise RuntimeError(f"mka_measure_mfma_loop: status {rc}")
+    return fl.value
+
+
+FRAG_BYTES = 16 * 512 * 16
+
+
+def mfma_loop_data(out, frags, workgroups: int, iters: int) -> float:
+    """Enqueue the MFMA loop on the operand fragments in `frags` (FRAG_BYTES bytes of bf16 on the
+    device); returns the flops of the launch."""
+    if frags.numel() * frags.element_size() < FRAG_BYTES:
+        raise ValueError("frags is smaller than FRAG_BYTES")
+    fl = ctypes.c_double(0.0)
+    rc = lib().mka_measure_mfma_loop_data(c_void_p(out.data_ptr()), c_void_p(frags.data_ptr()),
+                                          workgroups, iters, ctypes.byref(fl), _stream())
+    if rc:
+        raise RuntimeError(f"mka_measure_mfma_loop_data: status {rc}")
     return fl.value
 
 

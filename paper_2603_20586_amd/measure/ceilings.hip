@@ -36,6 +36,38 @@ __global__ __launch_bounds__(512) void measure_mfma_kernel(float* out, int iters
   if (out) out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// The same loop on operands that change from MFMA to MFMA: every wave holds eight A and eight B
+// fragments out of `frags` (the caller fills it with the value distribution of its workload)
+// and walks through all pairings.  The board's power limit, not the issue rate, sets the clock
+// under matrix load, and the power an MFMA draws depends on how many operand bits toggle: this
+// is what the matrix pipe alone sustains on data like the attention kernels'.
+__global__ __launch_bounds__(512) void measure_mfma_data_kernel(float* out, const uint4* __restrict__ frags,
+                                                                int iters) {
+  bf16x8 a[8], b[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    a[j] = __builtin_bit_cast(bf16x8, frags[(j * 2) * 512 + threadIdx.x]);
+    b[j] = __builtin_bit_cast(bf16x8, frags[(j * 2 + 1) * 512 + threadIdx.x]);
+  }
+  f32x16 acc[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[k][r] = 0.f;
+  for (int i = 0; i < iters; ++i) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int k = 0; k < 4; ++k) acc[k] = mfma32(a[j], b[(j + k) & 7], acc[k]);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[k][r];
+  if (out) out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
 // Six streams (the buffer cut in six equal parts), each workgroup walks its slice of all six at
 // once: per trip a lane issues 4 x 6 independent 16-byte non-temporal loads before the first use,
 // 16 lanes cover 256 consecutive bytes - the decode kernel's traffic without its arithmetic.
@@ -69,6 +101,16 @@ extern "C" int32_t mka_measure_mfma_loop(float* out, int32_t workgroups, int32_t
   hipLaunchKernelGGL(mka::measure_mfma_kernel, dim3((unsigned)workgroups), dim3(512), 0,
                      static_cast<hipStream_t>(stream), out, iters);
   if (flops) *flops = (double)workgroups * 8.0 * iters * 4.0 * 32768.0;  // 2*32*32*16 per MFMA
+  return hipGetLastError() == hipSuccess ? 0 : 7;
+}
+
+extern "C" int32_t mka_measure_mfma_loop_data(float* out, const void* frags, int32_t workgroups,
+                                              int32_t iters, double* flops, void* stream) {
+  if (workgroups <= 0 || iters <= 0 || !out || !frags) return 2;
+  if (reinterpret_cast<uintptr_t>(frags) & 15) return 4;
+  hipLaunchKernelGGL(mka::measure_mfma_data_kernel, dim3((unsigned)workgroups), dim3(512), 0,
+                     static_cast<hipStream_t>(stream), out, static_cast<const uint4*>(frags), iters);
+  if (flops) *flops = (double)workgroups * 8.0 * iters * 32.0 * 32768.0;
   return hipGetLastError() == hipSuccess ? 0 : 7;
 }
 

@@ -39,7 +39,8 @@ def test_every_declared_symbol_is_exported(m):
     from paper_2603_20586_amd import measure
 
     mnames = _declared("mka_measure.h")
-    assert mnames == {"mka_measure_mfma_loop", "mka_measure_stream_read"}
+    assert mnames == {"mka_measure_mfma_loop", "mka_measure_mfma_loop_data",
+                      "mka_measure_stream_read"}
     for n in mnames:
         assert hasattr(measure.lib(), n), n
         assert not hasattr(L, n), n
@@ -198,6 +199,9 @@ def test_measure_helpers_reject_bad_arguments_on_the_host(m):
     assert L.mka_measure_mfma_loop(None, 4, 10, None, None) == 2      # no output buffer
     assert L.mka_measure_mfma_loop(ctypes.c_void_p(256), 0, 10, None, None) == 2
     assert L.mka_measure_mfma_loop(ctypes.c_void_p(256), 4, 0, None, None) == 2
+    assert L.mka_measure_mfma_loop_data(ctypes.c_void_p(256), None, 4, 10, None, None) == 2  # no operands
+    assert L.mka_measure_mfma_loop_data(ctypes.c_void_p(256), ctypes.c_void_p(4100), 4, 10, None, None) == 4
+    assert L.mka_measure_mfma_loop_data(ctypes.c_void_p(256), ctypes.c_void_p(4096), 4, 0, None, None) == 2
     assert L.mka_measure_stream_read(None, 1 << 20, None, None) == 2
     assert L.mka_measure_stream_read(ctypes.c_void_p(4096), 64, None, None) == 2   # too small
     assert L.mka_measure_stream_read(ctypes.c_void_p(4100), 1 << 20, None, None) == 4  # misaligned
