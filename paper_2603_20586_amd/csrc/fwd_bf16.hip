@@ -221,7 +221,8 @@ __device__ __forceinline__ void stage_slice(int q, int part, int h, const PairRa
 template <int D, bool GV, bool FAST>
 __device__ __forceinline__ void half_step(
     f32x16 s_now, f32x16& s_next, const bf16* sKn, int unit_n, int jb, const bf16* sVT, int unit,
-    const bf16x8 (&qreg)[D / 16], f32x16 (&oacc)[D / 32], float& m, float& lsum, float c, int jmax,
+    const bf16x8 (&qreg)[D / 16], f32x16 (&oacc)[D / 32], float& m, float& mc, float& lsum, float c,
+    int jmax,
     PairRaw& raw, StageTmp& tmp, bf16* dst, int qf, bool do_fuse, int jl, int ql, bool do_load,
     bool full, const bf16* __restrict__ P0, const bf16* __restrict__ P1,
     const bf16* __restrict__ P2, const float* __restrict__ Gb, int S, int len0, int len1, int len2,
@@ -258,25 +259,31 @@ __device__ __forceinline__ void half_step(
       if (j > jmax) s_now[r] = -INFINITY;
     }
   }
-  float mx = fmaxf(s_now[0], s_now[1]);
-#pragma unroll
-  for (int r = 2; r < 16; ++r) mx = fmaxf(mx, s_now[r]);
-  mx = fmaxf(mx, xor32(mx));
   // Lazy max-shift: the reference m only moves when the row max has grown by more than 2^8
   // in the exponent; until then P = exp2(c (s - m)) may exceed 1 (at most 256), which bf16 and
   // the f32 sums hold without loss, and the rescale of the accumulators is skipped.  The
   // recursion is unchanged (O and z are always relative to the same m), only m is stale.
+  // The common case costs the in-lane maximum and one compare: each half of a row (the lanes li
+  // and li + 32) tests its own 16 slots against the row's reference (mc = m c; -inf before the
+  // first visible slot, which fails the test); only when some lane of the wave fails it are the
+  // halves exchanged, the references moved and the accumulators rescaled.  A unit with masked
+  // slots always takes the long way.
   // Every row sees slot 0, so m is finite after the first unit that has a visible slot.
-  const bool move = (mx - m) * c > 8.f || m == -INFINITY;
-  const float m_new = move ? mx : m;
-  const float alpha = move ? ((m == -INFINITY) ? 0.f : fast_exp2((m - m_new) * c)) : 1.f;
-  const float mc = (m_new == -INFINITY) ? 0.f : m_new * c;
-  m = m_new;
-  if (__any(move)) {
+  const float lmax = max16(s_now);
+  if (__any(!FAST || !(fmaf(lmax, c, -mc) <= 8.f))) {
+    const float mx = fmaxf(lmax, xor32(lmax));
+    const bool move = (mx - m) * c > 8.f || m == -INFINITY;
+    const float m_new = move ? mx : m;
+    const float alpha = move ? ((m == -INFINITY) ? 0.f : fast_exp2((m - m_new) * c)) : 1.f;
+    m = m_new;
+    mc = m_new * c;
+    lsum *= alpha;
+    if (__any(move)) {
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+      for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+    }
   }
 
   // -- section A: S^T of the next unit, between the exponentials of this one
@@ -313,7 +320,7 @@ __device__ __forceinline__ void half_step(
   // cannot issue while an MFMA of either wave of the SIMD is in the matrix pipe.
   const float psum = (((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]))) +
                      (((p[8] + p[9]) + (p[10] + p[11])) + ((p[12] + p[13]) + (p[14] + p[15])));
-  lsum = lsum * alpha + psum;
+  lsum += psum;
   __builtin_amdgcn_sched_barrier(0);
 
   // -- section B: O^T += Vf^T P^T (k half 0 = columns 16 ks .. of the unit with P^T regs 0-7),
@@ -341,7 +348,7 @@ template <int D, bool GV>
 __device__ __forceinline__ void run_tiles(bf16* smem, const bf16* __restrict__ P0,
                                           const bf16* __restrict__ P1, const bf16* __restrict__ P2,
                                           const float* __restrict__ Gb, const bf16x8 (&qreg)[D / 16],
-                                          f32x16 (&oacc)[D / 32], float& m, float& lsum, float c,
+                                          f32x16 (&oacc)[D / 32], float& m, float& mc, float& lsum, float c,
                                           int ntiles, int S, int len0, int len1, int len2,
                                           int causal, int row_lo, int jmax, int li, int g, int tg) {
   using L = FwdSmem<D>;
@@ -396,19 +403,19 @@ __device__ __forceinline__ void run_tiles(bf16* smem, const bf16* __restrict__ P
     const bool full2 = j0 + 3 * BC <= lenmin;
     const int jl = j0 + 2 * BC;  // both half steps load raw data of tile jt+2
     if (!need_mask && has2 && full2) {
-      half_step<D, GV, true>(s_a, s_b, sK, 1, j0, sVT, 0, qreg, oacc, m, lsum, c, jmax, raw, tmp,
+      half_step<D, GV, true>(s_a, s_b, sK, 1, j0, sVT, 0, qreg, oacc, m, mc, lsum, c, jmax, raw, tmp,
                              dst1, 2, true, jl, 0, true, true, P0, P1, P2, Gb, S, len0, len1, len2,
                              li, g, tg);
       loop_barrier();  // tile jt+1 is complete in LDS; K buffer jt&1 may be overwritten
-      half_step<D, GV, true>(s_b, s_a, sK1, 0, j0 + 32, sVT, 1, qreg, oacc, m, lsum, c, jmax, raw,
+      half_step<D, GV, true>(s_b, s_a, sK1, 0, j0 + 32, sVT, 1, qreg, oacc, m, mc, lsum, c, jmax, raw,
                              tmp, dst2, 0, true, jl, 2, true, true, P0, P1, P2, Gb, S, len0, len1,
                              len2, li, g, tg);
     } else {
-      half_step<D, GV, false>(s_a, s_b, sK, 1, j0, sVT, 0, qreg, oacc, m, lsum, c, jmax, raw, tmp,
+      half_step<D, GV, false>(s_a, s_b, sK, 1, j0, sVT, 0, qreg, oacc, m, mc, lsum, c, jmax, raw, tmp,
                               dst1, 2, has1, jl, 0, has2, full2, P0, P1, P2, Gb, S, len0, len1,
                               len2, li, g, tg);
       __syncthreads();
-      half_step<D, GV, false>(s_b, s_a, sK1, 0, j0 + 32, sVT, 1, qreg, oacc, m, lsum, c, jmax, raw,
+      half_step<D, GV, false>(s_b, s_a, sK1, 0, j0 + 32, sVT, 1, qreg, oacc, m, mc, lsum, c, jmax, raw,
                               tmp, dst2, 0, has2, jl, 2, has2, full2, P0, P1, P2, Gb, S, len0, len1,
                               len2, li, g, tg);
     }
@@ -464,7 +471,7 @@ __device__ __forceinline__ void fwd_tile(
   for (int db = 0; db < DB; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
-  float m = -INFINITY, lsum = 0.f;
+  float m = -INFINITY, mc = -INFINITY, lsum = 0.f;  // mc = m c, kept beside m
 
   int t_last = qt * BR + BR - 1;
   if (t_last > Tq - 1) t_last = Tq - 1;
@@ -476,10 +483,10 @@ __device__ __forceinline__ void fwd_tile(
   // waves 0-3 stage the K half of every tile, waves 4-7 the V half; the two loops have the same
   // trip count and one barrier per trip
   if (!grpV)
-    run_tiles<D, false>(smem, K0b, K1b, K2b, Gb, qreg, oacc, m, lsum, c, ntiles, S, len0, len1, len2,
+    run_tiles<D, false>(smem, K0b, K1b, K2b, Gb, qreg, oacc, m, mc, lsum, c, ntiles, S, len0, len1, len2,
                         causal, tw0 + off, jmax, li, g, tg);
   else
-    run_tiles<D, true>(smem, V0b, V1b, V2b, Gb, qreg, oacc, m, lsum, c, ntiles, S, len0, len1, len2,
+    run_tiles<D, true>(smem, V0b, V1b, V2b, Gb, qreg, oacc, m, mc, lsum, c, ntiles, S, len0, len1, len2,
                        causal, tw0 + off, jmax, li, g, tg);
 
   // ---- epilogue: normalise, transpose O^T through LDS (tile buffers are free after the last
