@@ -60,6 +60,25 @@ def test_mixture_shapes(mka, oracle, d, Tq, S3, causal):
     _check(mka, oracle, Q, K, V, G, causal, 1.0 / np.sqrt(d))
 
 
+@pytest.mark.parametrize("d", [128, 64])
+def test_mixture_reference_exponent_moves_along_the_stream(mka, oracle, d):
+    """Keys that grow with the slot index in every memory, so that the reference exponent of the
+    lazy max-shift moves in many units of the stream, not just in the first (the kernel's rare
+    path), and drops back at each level change relative to the new level's scores."""
+    announce(f"mixture growing keys d={d}")
+    Q, K, V, G = _inputs(2, 2, 260, (500, 333, 400), d, seed=37)
+    K = [(k.float() * torch.linspace(1.0, 12.0, k.shape[2], device="cuda").view(1, 1, -1, 1)).to(torch.bfloat16)
+         for k in K]
+    V = [(v.float() * 0.25).to(torch.bfloat16) for v in V]   # |O| <= 1: the output's own rounding
+    for causal in (True, False):
+        O, LSE = mka.mka_mixture_attn_fwd(Q, K, V, G, causal=causal, scale=1.0 / np.sqrt(d))
+        torch.cuda.synchronize()
+        Oref, Lref = oracle.mixture_fwd(Q.cpu(), cpu_list(K), cpu_list(V), G.cpu(), causal=causal,
+                                        tau=1.0 / np.sqrt(d))
+        assert max_abs(O, Oref) <= BF16_ATOL, max_abs(O, Oref)
+        assert float(np.max(np.abs(to_np(LSE) - Lref))) <= BF16_ATOL
+
+
 def test_mixture_without_gates_is_attention_over_the_concatenation(mka, oracle):
     announce("mixture no gates")
     Q, K, V, _ = _inputs(1, 3, 190, (190, 200, 250), 128, seed=32)

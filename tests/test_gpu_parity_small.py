@@ -182,6 +182,38 @@ def test_fwd_bf16_shapes(mka, oracle, d, Tq, S, causal, len3, materialise):
     assert max_abs(LSE, LSEref) <= BF16_ATOL
 
 
+@pytest.mark.parametrize("d", [128, 64])
+@pytest.mark.parametrize("materialise", [False, True])
+def test_fwd_bf16_reference_exponent_moves_along_the_stream(mka, oracle, d, materialise):
+    """Keys that grow with the slot index (x1 .. x14 over the stream): the largest score of a row
+    rises by several tens in the exponent, so the lazy max-shift has to move its reference in many
+    units well after the first one - the rare path of the kernels (exchange between the halves of
+    a row, rescale of the accumulators), which N(0,1) keys hardly ever take.  Non-causal as well:
+    every row then sees the whole growth.
+    The gates are given and one-hot, so that the fused rows are the chosen level's rows exactly:
+    with scores of this size the rounding of a soft fusion to bf16 alone moves a logit by 0.1,
+    which is the format's limit and not what this case is about; V is scaled to |O| <= 1 for the
+    same reason (an output of 4 rounds to bf16 with an error of 0.008)."""
+    announce(f"fwd bf16 growing keys d={d} materialise={materialise}")
+    Tq, S = 300, 700
+    inp = si.prefill_inputs(2, 2, Tq, S, d, dtype="bf16", seed=23, device="cuda")
+    ramp = torch.linspace(1.0, 14.0, S, device="cuda").view(1, 1, S, 1)
+    inp["K"] = [(k.float() * ramp).to(torch.bfloat16) for k in inp["K"]]
+    inp["V"] = [(v.float() * 0.25).to(torch.bfloat16) for v in inp["V"]]
+    level = torch.randint(0, 3, (2, 2, S), device="cuda")
+    G = torch.nn.functional.one_hot(level, 3).float()
+    for causal in (True, False):
+        O, LSE, G2, idx = mka.mka_fused_attn_fwd(inp["Q"], inp["K"], inp["V"], None, None,
+                                                 G=G.clone(), causal=causal, scale=inp["scale"],
+                                                 materialise=materialise)
+        torch.cuda.synchronize()
+        Oref, LSEref = oracle.fwd(inp["Q"].cpu(), cpu_list(inp["K"]), cpu_list(inp["V"]), G.cpu(),
+                                  causal=causal, tau=inp["scale"])
+        assert float(np.max(LSEref) - np.min(LSEref)) > 8.0   # the growth is really there
+        assert max_abs(O, Oref) <= BF16_ATOL, max_abs(O, Oref)
+        assert max_abs(LSE, LSEref) <= BF16_ATOL, max_abs(LSE, LSEref)
+
+
 def test_fwd_bf16_given_gates_no_router(mka, oracle):
     announce("fwd bf16 given gates")
     inp = si.prefill_inputs(1, 2, 150, 150, 128, dtype="bf16", seed=8, device="cuda")
