@@ -5,45 +5,39 @@
 // One lane owns one query row.  The logits are an fp64 fma chain in ascending k that starts
 // from the bias; every product bf16*f32 or f32*f32 is exact in fp64 and each fma is correctly
 // rounded, so the logits (hence the argmax) are reproducible bit for bit by any other
-// implementation that uses the same chain.  A wave stages its 64 rows through LDS so that the
-// global reads are coalesced 16-byte loads; the kernel is bound by reading Q once.
+// implementation that uses the same chain.  A lane reads its row straight from global memory,
+// 16 bytes at a time and four chunks ahead (a wave instruction touches 64 rows; the four
+// instructions that share a 64-byte sector hit in the vector cache), and W_r through scalar
+// loads (a uniform address), widened to fp64 on the way into the fma: no LDS, no barrier, so
+// the waves of a compute unit overlap their loads and chains freely.  Measured against the
+// earlier version (64 rows staged through LDS per single-wave workgroup, W_r as an fp64 table in
+// LDS, 8-9 waves per compute unit): 29 us instead of 43 us for the 524 288 rows of the training
+// config in a loop of back-to-back launches (4.6 TB/s of Q; unroll 2 / 8 and 64 / 256 rows per
+// workgroup measured, this is the best).
 #include "mka_dev.h"
 #include "mka_internal.h"
 
 namespace mka {
 
+constexpr int RT_WG = 128;  // rows (threads) per workgroup
+
 template <typename T, int D>
-__global__ __launch_bounds__(64) void route_kernel(const T* __restrict__ Q,
-                                                   const float* __restrict__ W_r,
-                                                   const float* __restrict__ b_r,
-                                                   float* __restrict__ G, int32_t* __restrict__ idx,
-                                                   long rows, int Tq, int S, int mode) {
+__global__ __launch_bounds__(RT_WG) void route_kernel(const T* __restrict__ Q,
+                                                      const float* __restrict__ W_r,
+                                                      const float* __restrict__ b_r,
+                                                      float* __restrict__ G,
+                                                      int32_t* __restrict__ idx, long rows, int Tq,
+                                                      int S, int mode) {
   constexpr int ROWB = D * (int)sizeof(T);   // bytes per row
-  constexpr int STR = ROWB + 16;             // padded LDS row stride (bytes)
   constexpr int CPR = ROWB / 16;             // 16-byte chunks per row
   constexpr int EPC = 16 / (int)sizeof(T);   // elements per chunk
-  __shared__ __attribute__((aligned(16))) unsigned char sq[64 * STR];
-  __shared__ double sw[D * 3];
-  const int lane = threadIdx.x;
-  const long row0 = (long)blockIdx.x * 64;
-  for (int i = lane; i < D * 3; i += 64) sw[i] = (double)W_r[i];
-  // coalesced copy of up to 64 rows into LDS
-  const unsigned char* src = reinterpret_cast<const unsigned char*>(Q) + row0 * ROWB;
-  const long nrows = (rows - row0) < 64 ? (rows - row0) : 64;
-  for (int c = lane; c < 64 * CPR; c += 64) {
-    const int r = c / CPR, cc = c % CPR;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (r < nrows) v = *reinterpret_cast<const uint4*>(src + (long)r * ROWB + cc * 16);
-    *reinterpret_cast<uint4*>(&sq[r * STR + cc * 16]) = v;
-  }
-  __syncthreads();
-  const long row = row0 + lane;
+  const long row = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (row >= rows) return;
   double g0 = b_r ? (double)b_r[0] : 0.0;
   double g1 = b_r ? (double)b_r[1] : 0.0;
   double g2 = b_r ? (double)b_r[2] : 0.0;
-  const unsigned char* myrow = &sq[lane * STR];
-#pragma unroll 2
+  const unsigned char* myrow = reinterpret_cast<const unsigned char*>(Q) + row * ROWB;
+#pragma unroll 4
   for (int cc = 0; cc < CPR; ++cc) {
     const uint4 u = *reinterpret_cast<const uint4*>(myrow + cc * 16);
     float f[8];
@@ -57,9 +51,10 @@ __global__ __launch_bounds__(64) void route_kernel(const T* __restrict__ Q,
     for (int e = 0; e < EPC; ++e) {
       const int k = cc * EPC + e;
       const double q = (double)f[e];
-      g0 = fma(q, sw[k * 3 + 0], g0);
-      g1 = fma(q, sw[k * 3 + 1], g1);
-      g2 = fma(q, sw[k * 3 + 2], g2);
+      // W_r at a uniform address: scalar loads, widened to fp64 on the way into the fma
+      g0 = fma(q, (double)W_r[k * 3 + 0], g0);
+      g1 = fma(q, (double)W_r[k * 3 + 1], g1);
+      g2 = fma(q, (double)W_r[k * 3 + 2], g2);
     }
   }
   float lam[3];
@@ -78,9 +73,9 @@ __global__ __launch_bounds__(64) void route_kernel(const T* __restrict__ Q,
 hipError_t launch_route(const RouteArgs& a, hipStream_t st) {
   const long rows = (long)a.BH * a.Tq;
   if (rows == 0) return hipSuccess;
-  const unsigned grid = (unsigned)((rows + 63) / 64);
+  const unsigned grid = (unsigned)((rows + RT_WG - 1) / RT_WG);
 #define MKA_ROUTE(T, D)                                                                        \
-  hipLaunchKernelGGL((route_kernel<T, D>), dim3(grid), dim3(64), 0, st, (const T*)a.Q, a.W_r, \
+  hipLaunchKernelGGL((route_kernel<T, D>), dim3(grid), dim3(RT_WG), 0, st, (const T*)a.Q, a.W_r, \
                      a.b_r, a.G, a.idx, rows, a.Tq, a.S, a.mode)
   if (a.bf16) {
     if (a.d == 128) MKA_ROUTE(bf16, 128); else MKA_ROUTE(bf16, 64);
