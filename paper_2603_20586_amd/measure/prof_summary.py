@@ -117,7 +117,7 @@ def pmc(src, dst, cmd):
 # its launch at that workload), ...]): the kernels that carry the line's algorithmic work; their
 # traffic is summed.  Causal launches: one workgroup per PAIR of tiles.
 TRAFFIC_KEYS = {
-    "C5_fwd": ("step", [("mka::route_kernel<bf16,128>", 8192), ("mka::prefuse_kernel<128>", 16384),
+    "C5_fwd": ("step", [("mka::route_kernel<bf16,128>", 4096), ("mka::prefuse_kernel<128>", 16384),
                         ("mka::mix_bf16_kernel<128,1>", 1024)]),      # 128 heads x 16/2 query tiles
     "C5_bwd": ("step", [("mka::bwd_main_kernel<128>", 2048),          # 128 heads x 32/2 key tiles
                         ("mka::bwd_dq_kernel<128>", 1024)]),
