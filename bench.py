@@ -69,8 +69,8 @@ def main():
 
     import paper_2603_20586_amd as mka  # raises if libmka.so is not built: no fallback
     import synth_inputs as si
-    from paper_2603_20586_amd.binding import (MKA_OP_BWD, MKA_OP_DECODE, MKA_OP_FULL_MKA,
-                                              MKA_OP_FWD, _shape)
+    from paper_2603_20586_amd.binding import (MKA_OP_BWD, MKA_OP_BWD_RECOMPUTE, MKA_OP_DECODE,
+                                              MKA_OP_FULL_MKA, MKA_OP_FWD, _shape)
 
     mka.lib()
     if not torch.cuda.is_available():
@@ -196,7 +196,7 @@ def main():
         }
         rooflines["C5_fwd"] = roof_mfma(fl5f, ms_f, "route_kernel + prefuse_kernel + mix_bf16_kernel "
                                                     "(all in the events)")
-        rooflines["C5_bwd"] = roof_mfma(fl5b, ms_b, "bwd_main_kernel + bwd_dq_kernel "
+        rooflines["C5_bwd"] = roof_mfma(fl5b, ms_b, "bwd_main_kernel + bwd_dqg_kernel "
                                                     "(+prep/wpart/reduce in the events)")
         rooflines["C4_decode_step"] = roof_hbm(bytes4_first, ms_d,
                                                "decode_split_kernel (+append/combine in the events)")
@@ -208,8 +208,14 @@ def main():
         msf5 = time_region(f5, 5, 2)
         msf5f = time_region(f5_folded, 5, 2)
         msb5 = time_region(b5, 5, 2)
+        ws5r = ws(mka.mka_workspace_bytes(MKA_OP_BWD_RECOMPUTE, shp5))
+        msb5r = time_region(lambda: mka.mka_fused_attn_bwd(
+            inp5["dO"], inp5["Q"], inp5["K"], inp5["V"], G5, O5, L5, inp5["W_r"], causal=True,
+            scale=inp5["scale"], workspace=ws5r), 5, 2)
+        del ws5r
         workloads["C5_train"] = {
             "fwd_ms": msf5, "fwd_folded_ms": msf5f, "bwd_ms": msb5,
+            "bwd_recompute_route_ms": msb5r, "bwd_recompute_route_tflops": fl5b / msb5r / 1e9,
             "fwd_tflops": fl5f / msf5 / 1e9, "fwd_folded_tflops": fl5f / msf5f / 1e9,
             "bwd_tflops": fl5b / msb5 / 1e9,
             "fwd_bwd_tflops": (fl5f + fl5b) / (msf5 + msb5) / 1e9,
@@ -217,8 +223,10 @@ def main():
         rooflines.setdefault("C5_fwd", roof_mfma(fl5f, msf5, "route_kernel + prefuse_kernel + "
                                                              "mix_bf16_kernel (all in the events)"))
         rooflines["C5_fwd_folded"] = roof_mfma(fl5f, msf5f, "route_kernel + fwd_bf16_kernel")
-        rooflines.setdefault("C5_bwd", roof_mfma(fl5b, msb5, "bwd_main_kernel + bwd_dq_kernel "
+        rooflines.setdefault("C5_bwd", roof_mfma(fl5b, msb5, "bwd_main_kernel + bwd_dqg_kernel "
                                                              "(+prep/wpart/reduce in the events)"))
+        rooflines["C5_bwd_recompute"] = roof_mfma(fl5b, msb5r, "bwd_main_kernel + bwd_dq_kernel "
+                                                               "(+prep/wpart/reduce in the events)")
 
     if "C4" in only:
         # the configured run: 64 decode steps with an appended L1 entry per step
@@ -330,7 +338,7 @@ def main():
             "tokens_per_s_prefill": B * T / (ms_fd * 1e-3)}
         rooflines["C2_fwd"] = roof_mfma(fl2, ms_ff, "fwd_bf16_kernel")
         rooflines["C2_fwd_materialised"] = roof_mfma(fl2, ms_fm, "prefuse_kernel + mix_bf16_kernel")
-        rooflines["C2_bwd"] = roof_mfma(2.5 * fl2, ms_b, "bwd_main_kernel + bwd_dq_kernel "
+        rooflines["C2_bwd"] = roof_mfma(2.5 * fl2, ms_b, "bwd_main_kernel + bwd_dqg_kernel "
                                                          "(+prep/wpart/reduce in the events)")
         del inp, G, O, LSE, ws_bwd, ws_mat
         torch.cuda.empty_cache()

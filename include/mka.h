@@ -63,7 +63,8 @@ typedef enum {
   MKA_OP_FWD_MATERIALISED = 4, /* what makes mka_fused_attn_fwd write Kf, Vf (see there)   */
   MKA_OP_FULL_MKA = 5,         /* mka_full_attn_fwd: three partial outputs [B,H,Tq,d]      */
   MKA_OP_PREFIX_MEAN = 6,      /* mka_prefix_mean: chunk sums                              */
-  MKA_OP_BWD_STORED_DS = 7     /* what makes mka_fused_attn_bwd store dS (see there)       */
+  MKA_OP_BWD_STORED_DS = 7,    /* what makes mka_fused_attn_bwd store dS (see there)       */
+  MKA_OP_BWD_RECOMPUTE = 8     /* the least mka_fused_attn_bwd accepts (see there)         */
 } mka_op;
 
 /* Problem shape of route / forward / backward. */
@@ -219,18 +220,19 @@ mka_status mka_fused_attn_decode_static(const void* q, const void* const k_new[3
  * Every output is a fixed-order sum: the same call gives the same bits (dQ is
  * accumulated in registers by a query-stationary kernel, dW_r/db_r by a
  * two-stage reduction).  The workspace holds the padded D / LSE rows, the gate gradients, the
- * router-gradient partial sums and the fused key / value streams: the key-stationary kernel
- * (dK_l, dV_l, router gradient) writes them, the query-stationary dQ kernel forms S, dP and dS from
- * them a second time.  mka_workspace_bytes(MKA_OP_BWD, shape) is that size and the least the call
- * accepts (MKA_ERR_WORKSPACE below it).
- * Alternative route, taken when the workspace holds at least
- * mka_workspace_bytes(MKA_OP_BWD_STORED_DS, shape) bytes (0 = not provided for this shape: dS above
- * 32 GiB in total or 4 GiB per head): the key-stationary kernel also leaves the score gradients dS
- * in the workspace (bf16, 8 KiB per pair of a 128-slot key tile and a 32-row query tile, the full
- * rectangle; config C5: 4 GiB) and the dQ kernel reads them back - one product per pair instead
- * of three.  Same result up to rounding order.  Measured on MI355X it is the faster one for single
- * calls (C5 2.28 against 2.41 ms) and no faster in a loop of back-to-back calls (2.29 against
- * 2.27 ms), which is why it is not the default. */
+ * router-gradient partial sums and the fused key / value streams.  Two routes to dQ:
+ *  - stored score gradients: the key-stationary kernel (dK_l, dV_l, router gradient) also leaves
+ *    dS in the workspace (bf16, 8 KiB per pair of a 128-slot key tile and a 32-row query tile, the
+ *    full rectangle, streamed past the caches; config C5: 4 GiB) and the query-stationary dQ
+ *    kernel reads them back - one product per pair.  Taken when the workspace holds at least
+ *    mka_workspace_bytes(MKA_OP_BWD_STORED_DS, shape) bytes (0 = not provided for this shape: dS
+ *    above 32 GiB in total or 4 GiB per head).
+ *  - recomputation: the dQ kernel forms S, dP and dS a second time from the fused streams - three
+ *    products per pair, a workspace of mka_workspace_bytes(MKA_OP_BWD_RECOMPUTE, shape) bytes,
+ *    the least the call accepts (MKA_ERR_WORKSPACE below it).
+ * Same result up to rounding order.  mka_workspace_bytes(MKA_OP_BWD, shape) is the size of the
+ * route the library recommends: the first where it is provided (measured on MI355X in loops of
+ * back-to-back calls: C5 2.22 against 2.37 ms, C2 0.374 against 0.390 ms), else the second. */
 mka_status mka_fused_attn_bwd(const void* dO, const void* Q, const void* const K[3],
                               const void* const V[3], const float* G, const void* O,
                               const float* LSE, const float* W_r, void* dQ, void* const dK[3],

@@ -12,7 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "libmka.so")
 
 MKA_F32, MKA_BF16 = 0, 1
 MKA_OP_ROUTE, MKA_OP_FWD, MKA_OP_DECODE, MKA_OP_BWD, MKA_OP_FWD_MATERIALISED = 0, 1, 2, 3, 4
-MKA_OP_FULL_MKA, MKA_OP_PREFIX_MEAN, MKA_OP_BWD_STORED_DS = 5, 6, 7
+MKA_OP_FULL_MKA, MKA_OP_PREFIX_MEAN, MKA_OP_BWD_STORED_DS, MKA_OP_BWD_RECOMPUTE = 5, 6, 7, 8
 
 
 class MkaError(RuntimeError):
@@ -323,11 +323,11 @@ def mka_fused_attn_decode_static(q, k_new, v_new, Kc, Vc, Gc, len3, W_r, b_r, O,
 
 
 def mka_fused_attn_bwd(dO, Q, K, V, G, O, LSE, W_r=None, len3=None, causal=True, scale=1.0,
-                       workspace=None, grads_for=(True, True, True), stored_ds=False):
+                       workspace=None, grads_for=(True, True, True), stored_ds=None):
     """Backward of the forward.  Returns dict(dQ, dK[3], dV[3], dW_r, db_r).  Without a
-    `workspace` one of the library's size is allocated (`stored_ds=True`: the larger one, with
-    which the dQ kernel reads stored score gradients instead of recomputing them, where the
-    library provides that route)."""
+    `workspace` one is allocated: of the size the library recommends (`stored_ds=None`), of the
+    size with which the dQ kernel reads stored score gradients where the library provides that
+    route (`True`), or of the smallest size, with which it recomputes them (`False`)."""
     _dev_check(dO, Q, G, O, LSE, W_r, *K, *V)
     _f32_check(W_r=W_r, G=G, LSE=LSE)
     _same_dtype(Q, dO=dO, O=O, K=K, V=V)
@@ -335,9 +335,13 @@ def mka_fused_attn_bwd(dO, Q, K, V, G, O, LSE, W_r=None, len3=None, causal=True,
     S = G.shape[2]
     s = _shape(Q, S, len3, causal, scale)
     if workspace is None:
-        nbytes = mka_workspace_bytes(MKA_OP_BWD, s)
-        if stored_ds:
-            nbytes = max(nbytes, mka_workspace_bytes(MKA_OP_BWD_STORED_DS, s))
+        if stored_ds is None:
+            nbytes = mka_workspace_bytes(MKA_OP_BWD, s)
+        elif stored_ds:
+            nbytes = max(mka_workspace_bytes(MKA_OP_BWD_RECOMPUTE, s),
+                         mka_workspace_bytes(MKA_OP_BWD_STORED_DS, s))
+        else:
+            nbytes = mka_workspace_bytes(MKA_OP_BWD_RECOMPUTE, s)
         workspace = _workspace(nbytes, Q.device)
     dQ = torch.empty_like(Q)
     dK = [torch.empty_like(K[l]) if (K[l] is not None and grads_for[l]) else None

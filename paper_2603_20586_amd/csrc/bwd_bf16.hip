@@ -351,8 +351,11 @@ __device__ __forceinline__ void bwd_main_tile(
           __builtin_amdgcn_sched_barrier(0);
           const int qtile = qt0 + k;
           const size_t blk = (((size_t)bh * n_qg + (qtile >> 3)) * n_kvt + jt) * 65536 + (size_t)(qtile & 7) * 4096;
-          *reinterpret_cast<uint4*>(ds_lane + blk) = s0;
-          *reinterpret_cast<uint4*>(ds_lane + blk + 1024) = s1;
+          // streamed past the caches: 2 B per pair is far more than the L2 holds, and the query
+          // tiles that the other key tiles of the head re-read should stay there
+          typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+          __builtin_nontemporal_store(u32x4v{s0.x, s0.y, s0.z, s0.w}, reinterpret_cast<u32x4v*>(ds_lane + blk));
+          __builtin_nontemporal_store(u32x4v{s1.x, s1.y, s1.z, s1.w}, reinterpret_cast<u32x4v*>(ds_lane + blk + 1024));
         }
       }
     } else {
@@ -402,7 +405,12 @@ __device__ __forceinline__ void bwd_main_tile(
         }
       }
     }
-    wait_tile();  // this wave's part of tile it+1 has landed
+    // this wave's part of tile it+1 has landed.  The dS stores of a role-K wave count on vmcnt
+    // like its tile loads: behind the loads of tile it+1 it has issued, per iteration, the loads
+    // of one more tile and two stores (from iteration 1 on), so from iteration 3 on the count to
+    // wait for is that of two tiles plus six stores - waiting for fewer would wait for stores.
+    if (dS_out && uw >= 4 && it >= 3) mx_wait_loads<2 * LPW + 6>();
+    else wait_tile();
     loop_barrier();
     b5 = b5 == L::NSLOT - 1 ? 0 : b5 + 1;
   }

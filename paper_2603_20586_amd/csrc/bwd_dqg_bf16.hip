@@ -1,5 +1,6 @@
 // dQ of the route-fused attention backward from STORED score gradients, bf16 MFMA path - the
-// alternative to the kernel that recomputes them (bwd_dq_bf16.hip, the default).  The paper prints
+// route taken when the workspace has room for them; the kernel that recomputes them
+// (bwd_dq_bf16.hip) serves the minimal workspace.  The paper prints
 // no backward; this is the query-side contraction of the chain rule through Alg. 2 step 9:
 //
 //   dQ[t] = tau sum_j dS[t,j] Kf[j] + sum_l dg[t,l] W_r[:,l]
@@ -19,11 +20,13 @@
 // out of LDS (ds_read_b64_tr_b16) - Kf^T from the row-major key tile, dS^T from the layout below -
 // and dQ^T stays in registers until the epilogue adds the router term and stores bf16 rows once.
 // Every sum has a fixed order.
-// Measured (T = 4096, B H = 128): 0.55 ms against 0.83 ms for the recomputing kernel; the dS stream
+// Measured (T = 4096, B H = 128): 0.53 ms against 0.80 ms for the recomputing kernel; the dS stream
 // arrives at 4.8 TB/s whatever the prefetch depth (4 or 6 stages) or the block order, the kernel
 // takes the same time without its MFMAs and LDS reads (0.54 ms), 0.35 ms without the dS loads and
-// 0.47 ms without the Kf loads; and the main kernel pays for the stores, so that in a loop of
-// back-to-back calls the backward as a whole gains nothing.
+// 0.47 ms without the Kf loads.  The main kernel pays 0.12 ms for the stores (non-temporal, and
+// counted in its role-K waves' vmcnt waits; with cached stores and uncounted waits it paid 0.18
+// ms and this kernel 0.55), so that in a loop of back-to-back calls the backward as a whole
+// takes 2.22 ms against 2.37 ms.
 //
 // dS layout: per (head, group of 8 query tiles, 128-slot key tile) 64 KiB = [slot half: 2][query
 // tile in group: 8][4 KiB]; inside the 4 KiB (64 slots x 32 rows) [slot block: 2][row half h: 2]

@@ -110,7 +110,12 @@ size_t mka_workspace_bytes(mka_op op, const mka_shape* s) {
       return mka::prefix_mean_workspace_bytes((int)bh, s->S, s->d);
     case MKA_OP_DECODE:
       return align256(bh * mka::kMaxSplits * (size_t)(s->d + 2) * sizeof(float));
-    case MKA_OP_BWD:
+    case MKA_OP_BWD: {  // the recommended route: stored dS where provided
+      if (s->Tq <= 0 || s->S < s->Tq) return 0;
+      const size_t stored = mka::bwd_workspace_bytes((int)bh, s->Tq, s->S, s->d, true);
+      return stored ? stored : mka::bwd_workspace_bytes((int)bh, s->Tq, s->S, s->d, false);
+    }
+    case MKA_OP_BWD_RECOMPUTE:
       if (s->Tq <= 0 || s->S < s->Tq) return 0;
       return mka::bwd_workspace_bytes((int)bh, s->Tq, s->S, s->d, false);
     case MKA_OP_BWD_STORED_DS:  // 0 when the problem is too large for that route

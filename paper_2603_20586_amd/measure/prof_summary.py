@@ -120,11 +120,11 @@ TRAFFIC_KEYS = {
     "C5_fwd": ("step", [("mka::route_kernel<bf16,128>", 4096), ("mka::prefuse_kernel<128>", 16384),
                         ("mka::mix_bf16_kernel<128,1>", 1024)]),      # 128 heads x 16/2 query tiles
     "C5_bwd": ("step", [("mka::bwd_main_kernel<128>", 2048),          # 128 heads x 32/2 key tiles
-                        ("mka::bwd_dq_kernel<128>", 1024)]),
+                        ("mka::bwd_dqg_kernel<128>", 1024)]),
     "C4_decode_step": ("step", [("mka::decode_split_kernel<bf16,128,4,false>", 2048)]),  # 4 splits x 512
     "C2_fwd": ("C2", [("mka::fwd_bf16_kernel<128>", 256)]),           # 64 heads x 8/2 query tiles
     "C2_fwd_materialised": ("C2", [("mka::prefuse_kernel<128>", 4096), ("mka::mix_bf16_kernel<128,1>", 256)]),
-    "C2_bwd": ("C2", [("mka::bwd_main_kernel<128>", 512), ("mka::bwd_dq_kernel<128>", 256)]),
+    "C2_bwd": ("C2", [("mka::bwd_main_kernel<128>", 512), ("mka::bwd_dqg_kernel<128>", 256)]),
     "C3_fwd": ("C3", [("mka::prefuse_kernel<128>", 8192), ("mka::mix_bf16_kernel<128,1>", 512)]),
     "C3_attention_core": ("C3", [("mka::mix_bf16_kernel<128,1>", 512)]),  # 32 heads x 32/2 query tiles
     "C3_fwd_folded": ("C3", [("mka::fwd_bf16_kernel<128>", 512)]),

@@ -118,6 +118,15 @@ def test_route_and_bwd_reject_bad_arguments(m):
     assert args(_shape(m), None, 0) == 5                  # workspace required
     assert args(_shape(m), FAKE, 16) == 5
     assert m.mka_workspace_bytes(3, _shape(m)) > 0
+    # backward sizes: 8 = the least accepted (recomputation), 7 = stored score gradients (0 where
+    # that route is not provided), 3 = the recommended one: the stored route's where provided
+    c5 = _shape(m, B=8, H=16, Tq=4096, S=4096, d=128)
+    rec, sto = m.mka_workspace_bytes(8, c5), m.mka_workspace_bytes(7, c5)
+    assert 0 < rec < sto and m.mka_workspace_bytes(3, c5) == sto
+    assert sto > 8 * 16 * (4096 // 128) * (4096 // 32) * 8192   # holds 8 KiB per tile pair
+    huge = _shape(m, B=64, H=64, Tq=16384, S=16384, d=128)   # dS would exceed 32 GiB
+    assert m.mka_workspace_bytes(7, huge) == 0
+    assert m.mka_workspace_bytes(3, huge) == m.mka_workspace_bytes(8, huge) > 0
     # forward: no workspace recommended for a short block; the materialised route's size is
     # two [B,H,S,d] bf16 tensors; long blocks get it recommended; f32 has no such route
     assert m.mka_workspace_bytes(1, _shape(m)) == 0

@@ -102,7 +102,7 @@ def test_C5_training_all_heads(mka, oracle):
     O, LSE, G, idx = mka.mka_fused_attn_fwd(inp["Q"], inp["K"], inp["V"], inp["W_r"], inp["b_r"],
                                             causal=True, scale=inp["scale"])
     g = mka.mka_fused_attn_bwd(inp["dO"], inp["Q"], inp["K"], inp["V"], G, O, LSE, inp["W_r"],
-                               causal=True, scale=inp["scale"])
+                               causal=True, scale=inp["scale"], stored_ds=False)
     # the alternative route stores dS for the dQ kernel instead of recomputing the scores: same
     # main kernel (bit-identical dK / dV / dW_r), its dQ is checked below as well
     dQ_rec = mka.mka_fused_attn_bwd(inp["dO"], inp["Q"], inp["K"], inp["V"], G, O, LSE, inp["W_r"],
@@ -140,10 +140,15 @@ def test_C5_training_all_heads(mka, oracle):
     assert eb <= BF16_ATOL, eb
     # the same call again gives the same bits (fixed-order sums everywhere)
     g2 = mka.mka_fused_attn_bwd(inp["dO"], inp["Q"], inp["K"], inp["V"], G, O, LSE, inp["W_r"],
-                                causal=True, scale=inp["scale"])
+                                causal=True, scale=inp["scale"], stored_ds=False)
+    # ... on either route (the default workspace is the recommended route's: stored dS here)
+    dQ_rec2 = mka.mka_fused_attn_bwd(inp["dO"], inp["Q"], inp["K"], inp["V"], G, O, LSE, inp["W_r"],
+                                     causal=True, scale=inp["scale"],
+                                     grads_for=(False, False, False))["dQ"]
     torch.cuda.synchronize()
     assert torch.equal(g2["dW_r"], g["dW_r"]) and torch.equal(g2["db_r"], g["db_r"])
     assert torch.equal(g2["dQ"], g["dQ"])
+    assert torch.equal(dQ_rec2, dQ_rec)
     for l in range(3):
         assert torch.equal(g2["dK"][l], g["dK"][l]) and torch.equal(g2["dV"][l], g["dV"][l])
 

@@ -365,7 +365,7 @@ def _check_bwd(mka, oracle, inp, S, len3, causal, Gprev=None, use_router=True, s
                                               len3=len3, causal=causal, scale=inp["scale"])
         Gref = Gprev.cpu()
     g = mka.mka_fused_attn_bwd(inp["dO"], inp["Q"], inp["K"], inp["V"], G, O, LSE, W, len3=len3,
-                               causal=causal, scale=inp["scale"])
+                               causal=causal, scale=inp["scale"], stored_ds=False)
     # the other dQ route (dS stored by the main kernel and read back instead of recomputed): same
     # main kernel, so everything but dQ agrees bit for bit; dQ is checked against the oracle too
     g_rec = mka.mka_fused_attn_bwd(inp["dO"], inp["Q"], inp["K"], inp["V"], G, O, LSE, W, len3=len3,
@@ -455,17 +455,19 @@ def test_bwd_same_call_same_bits(mka):
     inp = si.prefill_inputs(2, 3, 600, 700, 128, dtype="bf16", seed=21, device="cuda", with_dO=True)
     O, LSE, G, _ = mka.mka_fused_attn_fwd(inp["Q"], inp["K"], inp["V"], inp["W_r"], inp["b_r"],
                                           causal=True, scale=inp["scale"])
-    outs = []
-    for _ in range(2):
-        g = mka.mka_fused_attn_bwd(inp["dO"], inp["Q"], inp["K"], inp["V"], G, O, LSE, inp["W_r"],
-                                   causal=True, scale=inp["scale"])
-        torch.cuda.synchronize()
-        outs.append(g)
-    a, b = outs
-    assert torch.equal(a["dQ"], b["dQ"])
-    assert torch.equal(a["dW_r"], b["dW_r"]) and torch.equal(a["db_r"], b["db_r"])
-    for l in range(3):
-        assert torch.equal(a["dK"][l], b["dK"][l]) and torch.equal(a["dV"][l], b["dV"][l])
+    for route in (None, False, True):   # the recommended workspace, recomputation, stored dS
+        outs = []
+        for _ in range(2):
+            g = mka.mka_fused_attn_bwd(inp["dO"], inp["Q"], inp["K"], inp["V"], G, O, LSE,
+                                       inp["W_r"], causal=True, scale=inp["scale"],
+                                       stored_ds=route)
+            torch.cuda.synchronize()
+            outs.append(g)
+        a, b = outs
+        assert torch.equal(a["dQ"], b["dQ"])
+        assert torch.equal(a["dW_r"], b["dW_r"]) and torch.equal(a["db_r"], b["db_r"])
+        for l in range(3):
+            assert torch.equal(a["dK"][l], b["dK"][l]) and torch.equal(a["dV"][l], b["dV"][l])
 
 
 def test_bwd_bf16_given_gates_no_router(mka, oracle):
