@@ -153,13 +153,17 @@ __device__ __forceinline__ void bwd_main_tile(
   const int qt0 = t_first / BR;
 
   // ---- staging: query tiles go from global memory straight into LDS (no registers hold data in
-  // flight), requested three iterations before their first use; every wave issues an equal
-  // share of a tile's load instructions (1 KiB each: lane i fills LDS row RPI q + i / CPR, chunk
+  // flight), requested three iterations before their first use; every requesting wave issues an
+  // equal share of a tile's load instructions (1 KiB each: lane i fills LDS row RPI q + i / CPR, chunk
   // position i % CPR of instruction q, and picks the query row and chunk that belong there),
   // wave 0 one more for the rows' LSE and D values.
   constexpr int ROWB = D * 2, RPI = 64 / CPR;
   constexpr int IPT = L::QB / 1024;  // load instructions per tensor and tile
-  constexpr int LPW = 2 * IPT / 8;   // per wave
+  // The role-V waves (the first four) issue all of them: the role-K waves then have no loads
+  // of their own to wait for, and when they store dS their stores are all that counts on their
+  // vmcnt (measured against requests spread over all eight waves: main kernel -1 %).
+  constexpr int RQW = 4;             // waves that issue the tile requests
+  constexpr int LPW = 2 * IPT / RQW; // per requesting wave
   const int n_tiles = n_qt - qt0;
   const int uw = __builtin_amdgcn_readfirstlane(wave);
   const char* Qb = reinterpret_cast<const char*>(Q + qbase);
@@ -167,7 +171,7 @@ __device__ __forceinline__ void bwd_main_tile(
   unsigned st_row[LPW], st_chunk[LPW];
 #pragma unroll
   for (int e = 0; e < LPW; ++e) {
-    const int q = (8 * e + uw) % IPT;
+    const int q = (RQW * e + (uw % RQW)) % IPT;
     const int r = RPI * q + lane / CPR;
     st_row[e] = (unsigned)tile_row(r);
     st_chunk[e] = 16u * (unsigned)((lane % CPR) ^ mx_swz<D>(r));
@@ -179,18 +183,21 @@ __device__ __forceinline__ void bwd_main_tile(
   auto request = [&](int k, int slot) __attribute__((always_inline)) {
     const int t0 = (qt0 + (k < n_tiles ? k : n_tiles - 1)) * BR;
     const unsigned sb = lds_base + (unsigned)(slot * L::SLOTB);
+    if (uw < RQW)
 #pragma unroll
     for (int e = 0; e < LPW; ++e) {
-      const int idx = 8 * e + uw, tensor = idx / IPT, q = idx % IPT;
+      const int idx = RQW * e + uw, tensor = idx / IPT, q = idx % IPT;
       const unsigned o = min((unsigned)t0 + st_row[e], (unsigned)(Tq - 1)) * (unsigned)ROWB + st_chunk[e];
       mx_dma16(tensor ? dOb : Qb, o, sb + (unsigned)(tensor * L::QB + 1024 * q));
     }
     if (uw == 0) mx_dma4(ld_src + t0, sb + 2 * L::QB);
   };
   // before a barrier that publishes a tile: all but the two youngest tiles of this wave landed
+  // (the counts are exact because a requesting wave issues nothing else that counts on vmcnt
+  // inside the loop)
   auto wait_tile = [&]() __attribute__((always_inline)) {
     if (uw == 0) mx_wait_loads<2 * (LPW + 1)>();
-    else mx_wait_loads<2 * LPW>();
+    else if (uw < RQW) mx_wait_loads<2 * LPW>();
   };
 
   // the first three query tiles fly while the set-up runs
@@ -353,9 +360,8 @@ __device__ __forceinline__ void bwd_main_tile(
           const size_t blk = (((size_t)bh * n_qg + (qtile >> 3)) * n_kvt + jt) * 65536 + (size_t)(qtile & 7) * 4096;
           // streamed past the caches: 2 B per pair is far more than the L2 holds, and the query
           // tiles that the other key tiles of the head re-read should stay there
-          typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
-          __builtin_nontemporal_store(u32x4v{s0.x, s0.y, s0.z, s0.w}, reinterpret_cast<u32x4v*>(ds_lane + blk));
-          __builtin_nontemporal_store(u32x4v{s1.x, s1.y, s1.z, s1.w}, reinterpret_cast<u32x4v*>(ds_lane + blk + 1024));
+          store16_stream(ds_lane + blk, s0);
+          store16_stream(ds_lane + blk + 1024, s1);
         }
       }
     } else {
@@ -405,12 +411,8 @@ __device__ __forceinline__ void bwd_main_tile(
         }
       }
     }
-    // this wave's part of tile it+1 has landed.  The dS stores of a role-K wave count on vmcnt
-    // like its tile loads: behind the loads of tile it+1 it has issued, per iteration, the loads
-    // of one more tile and two stores (from iteration 1 on), so from iteration 3 on the count to
-    // wait for is that of two tiles plus six stores - waiting for fewer would wait for stores.
-    if (dS_out && uw >= 4 && it >= 3) mx_wait_loads<2 * LPW + 6>();
-    else wait_tile();
+    wait_tile();  // this wave's part of tile it+1 has landed (role K: nothing to wait for; its
+                  // dS stores count on vmcnt too, and must not be waited for here)
     loop_barrier();
     b5 = b5 == L::NSLOT - 1 ? 0 : b5 + 1;
   }

@@ -113,6 +113,12 @@ __device__ __forceinline__ uint4 load16_stream(const void* p) {
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// 16-byte streaming store (data that no kernel of the same call reads back soon): past the
+// caches, so that it does not push out what other workgroups are re-reading.
+__device__ __forceinline__ void store16_stream(void* p, const uint4& v) {
+  __builtin_nontemporal_store(u32x4{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4*>(p));
+}
+
 __device__ __forceinline__ float fast_exp2(float x) {
 #if MKA_ELIM & 4
   return x;
