@@ -47,6 +47,7 @@ __device__ __forceinline__ int swap23(int i) {
 // Per query row: D = dO.O and LSE in log2 units, in arrays padded to whole 32-row tiles per
 // (batch, head) (padding: D = 0, LSE = +inf, hence P = 0), so that the other kernels can fetch a
 // tile's rows without tests.
+constexpr int PREP_U = 4;  // items per thread
 template <int D>
 __global__ __launch_bounds__(256) void bwd_prep_kernel(const bf16* __restrict__ dO,
                                                        const bf16* __restrict__ O,
@@ -55,25 +56,39 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(const bf16* __restrict__ 
                                                        float* __restrict__ LSE2p, int Tq, int Tqp,
                                                        long prows) {
   constexpr int CPR = D / 8;
-  const long item = (long)blockIdx.x * 256 + threadIdx.x;
-  const long prow = item / CPR;  // padded row index
-  const int cc = (int)(item % CPR);
-  const long bh = prow / Tqp;
-  const int t = (int)(prow % Tqp);
-  const bool real = prow < prows && t < Tq;
-  const long row = bh * Tq + t;
-  float part = 0.f;
-  if (real) {
+  // PREP_U items (row, 16-byte chunk) per thread, 256 items apart, all loads issued first
+  uint4 ra[PREP_U], rb[PREP_U];
+  long prow_[PREP_U], row_[PREP_U];
+  bool real_[PREP_U];
+#pragma unroll
+  for (int u = 0; u < PREP_U; ++u) {
+    const long item = ((long)blockIdx.x * PREP_U + u) * 256 + threadIdx.x;
+    const long prow = item / CPR;  // padded row index
+    const int cc = (int)(item % CPR);
+    const long bh = prow / Tqp;
+    const int t = (int)(prow % Tqp);
+    real_[u] = prow < prows && t < Tq;
+    prow_[u] = prow;
+    row_[u] = bh * Tq + t;
+    ra[u] = rb[u] = make_uint4(0, 0, 0, 0);
+    if (real_[u]) {
+      ra[u] = load16_stream(dO + row_[u] * D + cc * 8);
+      rb[u] = load16_stream(O + row_[u] * D + cc * 8);
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < PREP_U; ++u) {
     float a[8], b[8];
-    unpack8(*reinterpret_cast<const uint4*>(dO + row * D + cc * 8), a);
-    unpack8(*reinterpret_cast<const uint4*>(O + row * D + cc * 8), b);
+    unpack8(ra[u], a);
+    unpack8(rb[u], b);
+    float part = 0.f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) part = fmaf(a[e], b[e], part);
-  }
-  part = group_sum<CPR>(part);  // CPR consecutive lanes hold one row
-  if (prow < prows && cc == 0) {
-    Dp[prow] = real ? part : 0.f;
-    LSE2p[prow] = real ? LSE[row] * kLog2e : INFINITY;
+    part = group_sum<CPR>(part);  // CPR consecutive lanes hold one row
+    if (prow_[u] < prows && threadIdx.x % CPR == 0) {
+      Dp[prow_[u]] = real_[u] ? part : 0.f;
+      LSE2p[prow_[u]] = real_[u] ? LSE[row_[u]] * kLog2e : INFINITY;
+    }
   }
 }
 
@@ -569,12 +584,16 @@ __global__ __launch_bounds__(256) void bwd_wpart_kernel(const float* __restrict_
 #pragma unroll
   for (int e = 0; e < 8; ++e) wacc[e][0] = wacc[e][1] = wacc[e][2] = 0.f;
   const long row0 = (long)blockIdx.x * FIN_ROWS;
+  // (rows past the end read the last row with zero weights: no early exit, so that the loads
+  // of four iterations are in flight at once)
+#pragma unroll 4
   for (int i = rl; i < FIN_ROWS; i += RL) {
-    const long row = row0 + i;
-    if (row >= rows) break;
-    const float dg0 = dgate[row * 3 + 0], dg1 = dgate[row * 3 + 1], dg2 = dgate[row * 3 + 2];
+    const bool in = row0 + i < rows;
+    const long row = in ? row0 + i : rows - 1;
+    const float dg0 = in ? dgate[row * 3 + 0] : 0.f, dg1 = in ? dgate[row * 3 + 1] : 0.f,
+                dg2 = in ? dgate[row * 3 + 2] : 0.f;
     float q[8];
-    unpack8(*reinterpret_cast<const uint4*>(Q + row * D + cc * 8), q);
+    unpack8(load16_stream(Q + row * D + cc * 8), q);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       wacc[e][0] = fmaf(q[e], dg0, wacc[e][0]);
@@ -680,7 +699,7 @@ hipError_t launch_bwd_t(const BwdArgs& a, hipStream_t st) {
   constexpr int CPR = D / 8;
 
   const long prows = (long)a.BH * w.Tqp;
-  hipLaunchKernelGGL((bwd_prep_kernel<D>), dim3((unsigned)((prows * CPR + 255) / 256)), dim3(256),
+  hipLaunchKernelGGL((bwd_prep_kernel<D>), dim3((unsigned)((prows * CPR + 256 * PREP_U - 1) / (256 * PREP_U))), dim3(256),
                      0, st, (const bf16*)a.dO, (const bf16*)a.O, a.LSE, Dp, LSE2p, a.Tq, w.Tqp,
                      prows);
   hipError_t e = hipGetLastError();
