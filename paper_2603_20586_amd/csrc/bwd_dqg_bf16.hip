@@ -186,20 +186,38 @@ __device__ __forceinline__ void bwd_dqg_tile(const bf16* __restrict__ Kf,
       const bool vis = has_rows && s < NS && (!causal || s * DG_BC - off <= tw0 + 31);
       if (vis) {
         const char* sK = smem + rb * SM::KT;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
+        // fragments of k-step ks (16 slots): dS^T as the B operand, Kf^T (DB blocks of 32 head
+        // dims) as A operands.  They are read one k-step ahead of their MFMAs: left to itself the
+        // compiler reads each fragment right before its MFMA, and every MFMA then waits a full
+        // LDS round trip.
+        auto frags = [&](int ks, bf16x8& b, bf16x8 (&a)[DB]) __attribute__((always_inline)) {
           const char* dp = sD + (ks >> 1) * (2 * DG_PIECE) + (ks & 1) * 512 + bx;
           const uint2 blo = lds_read_tr(reinterpret_cast<const bf16*>(dp));
           const uint2 bhi = lds_read_tr(reinterpret_cast<const bf16*>(dp + 256));
-          const bf16x8 b = __builtin_bit_cast(bf16x8, make_uint4(blo.x, blo.y, bhi.x, bhi.y));
+          b = __builtin_bit_cast(bf16x8, make_uint4(blo.x, blo.y, bhi.x, bhi.y));
+          const char* kr = sK + 16 * ks * ROWB;
 #pragma unroll
           for (int db = 0; db < DB; ++db) {
-            const char* kr = sK + 16 * ks * ROWB;
             const uint2 lo = lds_read_tr(reinterpret_cast<const bf16*>(kr + (x_lo ^ (unsigned)(db << 6))));
             const uint2 hi = lds_read_tr(reinterpret_cast<const bf16*>(kr + (x_hi ^ (unsigned)(db << 6))));
-            const bf16x8 a = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
-            acc[db] = mfma32(a, b, acc[db]);
+            a[db] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
           }
+        };
+        bf16x8 b0, b1, a0[DB], a1[DB];
+        frags(0, b0, a0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ks = 0; ks < 4; ks += 2) {
+          frags(ks + 1, b1, a1);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int db = 0; db < DB; ++db) acc[db] = mfma32(a0[db], b0, acc[db]);
+          __builtin_amdgcn_sched_barrier(0);
+          if (ks + 2 < 4) frags(ks + 2, b0, a0);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int db = 0; db < DB; ++db) acc[db] = mfma32(a1[db], b1, acc[db]);
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
       rb = rb == SM::NST - 1 ? 0 : rb + 1;
