@@ -272,9 +272,11 @@ __device__ __forceinline__ void mx_half_step(FA&& mid_a, FB&& mid_b, f32x16 (&s_
 #pragma unroll
       for (int r = i * (16 / NPV); r < (i + 1) * (16 / NPV); ++r)
         asm volatile("v_add_f32 %0, %0, %1" : "+v"(lsum[rb]) : "v"(p[rb][r]));  // in place, see above
+      // (none behind the first PV MFMA: the last S^T MFMA has only just been issued, and the
+      // running maximum is inline assembly, whose distance to the MFMA that writes its operands
+      // is the kernel's to keep)
       if (MPS == 1) {
-        if (i == 0) mx_max_step<0>(nmax[rb], s_next[rb]);
-        if (i == 1) mx_max_step<1>(nmax[rb], s_next[rb]);
+        if (i == 1) { mx_max_step<0>(nmax[rb], s_next[rb]); mx_max_step<1>(nmax[rb], s_next[rb]); }
         if (i == 2) mx_max_step<2>(nmax[rb], s_next[rb]);
         if (i == 3) mx_max_step<3>(nmax[rb], s_next[rb]);
         if (i == 4) mx_max_step<4>(nmax[rb], s_next[rb]);
@@ -282,9 +284,8 @@ __device__ __forceinline__ void mx_half_step(FA&& mid_a, FB&& mid_b, f32x16 (&s_
         if (i == 6) mx_max_step<6>(nmax[rb], s_next[rb]);
         if (i == 7) mx_max_step<7>(nmax[rb], s_next[rb]);
       } else {
-        if (i == 0) { mx_max_step<0>(nmax[rb], s_next[rb]); mx_max_step<1>(nmax[rb], s_next[rb]); }
-        if (i == 1) { mx_max_step<2>(nmax[rb], s_next[rb]); mx_max_step<3>(nmax[rb], s_next[rb]); }
-        if (i == 2) { mx_max_step<4>(nmax[rb], s_next[rb]); mx_max_step<5>(nmax[rb], s_next[rb]); }
+        if (i == 1) { mx_max_step<0>(nmax[rb], s_next[rb]); mx_max_step<1>(nmax[rb], s_next[rb]); mx_max_step<2>(nmax[rb], s_next[rb]); }
+        if (i == 2) { mx_max_step<3>(nmax[rb], s_next[rb]); mx_max_step<4>(nmax[rb], s_next[rb]); mx_max_step<5>(nmax[rb], s_next[rb]); }
         if (i == 3) { mx_max_step<6>(nmax[rb], s_next[rb]); mx_max_step<7>(nmax[rb], s_next[rb]); }
       }
     }
